@@ -1,0 +1,127 @@
+"""ctypes binding of the CPU oracle (``scheinfer_oracle.c``).
+
+TEST INFRASTRUCTURE ONLY: imported by ``tests/``, by ``__graft_entry__.smoke()`` and by the
+``cpu_baseline`` leg of ``bench.py``.  The GPU library never imports or calls anything here, and
+this module imports nothing from the GPU package.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "scheinfer_oracle.c")
+_LIB = os.path.join(_HERE, "libscheinfer_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (plain -O2, OpenMP for the trivial parallel-for)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + ".tmp.%d" % os.getpid()
+        subprocess.check_call(["gcc", "-O2", "-std=c99", "-fopenmp", "-fPIC", "-shared", "-o", tmp, _SRC, "-lm"])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        L = ctypes.CDLL(_LIB)
+        c_i, c_d, c_p = ctypes.c_int, ctypes.c_double, ctypes.c_void_p
+        L.so_silu.restype = c_d
+        L.so_silu.argtypes = [c_d]
+        L.so_set_threads.argtypes = [c_i]
+        L.so_get_threads.restype = c_i
+        L.so_split_counts.restype = c_i
+        L.so_split_counts.argtypes = [c_i, c_i, c_d, c_d, c_p, c_p, c_p]
+        L.so_route.restype = c_i
+        L.so_route.argtypes = [c_p, c_i, c_i, c_i, c_p, c_p, c_p, c_p, c_p, c_p]
+        L.so_layer_forward.restype = c_i
+        L.so_layer_forward.argtypes = [c_p, c_i, c_i, c_i, c_i, c_i, c_p, c_p, c_p, c_p, c_i, c_p, c_p, c_p,
+                                       c_i, c_i, c_i, c_i, c_i, c_p, c_i, c_p]
+        _lib = L
+    return _lib
+
+
+def _ptr(a):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def set_threads(n: int) -> None:
+    _load().so_set_threads(int(n))
+
+
+def get_threads() -> int:
+    return int(_load().so_get_threads())
+
+
+def silu(z: float) -> float:
+    return float(_load().so_silu(float(z)))
+
+
+def split_counts(H: int, granule: int, r_gg: float, r_cg: float):
+    """(n_cc, n_cg, n_gg) hidden-column counts for the given rates; rates are taken as float32."""
+    n = [ctypes.c_int(0) for _ in range(3)]
+    rc = _load().so_split_counts(int(H), int(granule), float(np.float32(r_gg)), float(np.float32(r_cg)),
+                                 ctypes.byref(n[0]), ctypes.byref(n[1]), ctypes.byref(n[2]))
+    if rc:
+        raise ValueError("so_split_counts: invalid arguments")
+    return n[0].value, n[1].value, n[2].value
+
+
+def route(logits: np.ndarray, k: int) -> dict:
+    logits = np.ascontiguousarray(logits, dtype=np.float32)
+    T, E = logits.shape
+    n = max(T * k, 1)
+    out = {"idx": np.zeros(n, np.int32), "w": np.zeros(n, np.float64), "count": np.zeros(E, np.int32),
+           "off": np.zeros(E + 1, np.int32), "perm": np.zeros(n, np.int32), "inv": np.zeros(n, np.int32)}
+    rc = _load().so_route(_ptr(logits), T, E, int(k), _ptr(out["idx"]), _ptr(out["w"]), _ptr(out["count"]),
+                          _ptr(out["off"]), _ptr(out["perm"]), _ptr(out["inv"]))
+    if rc:
+        raise ValueError("so_route failed with code %d" % rc)
+    for key in ("idx", "w"):
+        out[key] = out[key][:T * k].reshape(T, k)
+    for key in ("perm", "inv"):
+        out[key] = out[key][:T * k]
+    return out
+
+
+def layer_forward(x, w_gate, w_up, w_down, logits=None, top_k=1, shared=None, counts=(0, 0),
+                  shared_counts=(0, 0), n_g=0, sel=None) -> np.ndarray:
+    """y[T or len(sel), M] in float64.
+
+    x: uint16 [T, M]; w_*: uint16 [E, H, M]; logits: float32 [T, E] or None (E must be 1);
+    shared: None or (s_gate, s_up, s_down) uint16 [Hs, M]; counts = (n_cc, n_cg) hidden columns of
+    the CC and CG parts (0, 0 = unsliced); shared_counts likewise for the shared expert.
+    """
+    x = np.ascontiguousarray(x, dtype=np.uint16)
+    T, M = x.shape
+    wg = np.ascontiguousarray(w_gate, dtype=np.uint16)
+    wu = np.ascontiguousarray(w_up, dtype=np.uint16)
+    wd = np.ascontiguousarray(w_down, dtype=np.uint16)
+    E, H, M2 = wg.shape
+    assert M2 == M and wu.shape == wg.shape and wd.shape == wg.shape
+    lg = None
+    if logits is not None:
+        lg = np.ascontiguousarray(logits, dtype=np.float32)
+        assert lg.shape == (T, E)
+    Hs, sg, su, sd = 0, None, None, None
+    if shared is not None:
+        sg, su, sd = (np.ascontiguousarray(a, dtype=np.uint16) for a in shared)
+        Hs = sg.shape[0]
+        assert sg.shape == (Hs, M) and su.shape == sg.shape and sd.shape == sg.shape
+    sel_a = None if sel is None else np.ascontiguousarray(sel, dtype=np.int32)
+    n_out = T if sel_a is None else len(sel_a)
+    y = np.zeros((n_out, M), np.float64)
+    rc = _load().so_layer_forward(_ptr(x), T, M, H, E, int(top_k), _ptr(lg), _ptr(wg), _ptr(wu), _ptr(wd), Hs,
+                                  _ptr(sg), _ptr(su), _ptr(sd), int(counts[0]), int(counts[1]),
+                                  int(shared_counts[0]), int(shared_counts[1]), int(n_g), _ptr(sel_a),
+                                  0 if sel_a is None else len(sel_a), _ptr(y))
+    if rc:
+        raise ValueError("so_layer_forward failed with code %d" % rc)
+    return y
