@@ -1,0 +1,262 @@
+// Host side of the layer: the CC part (Section III-B: parameters stored and executed on the CPU;
+// Stream-A of Section III-C).  A persistent pool of threads computes, for the X1 tokens,
+//   Y^CC[t] = sum_s w[t][s] * ( SiLU(x_t Wg^CC) * (x_t Wu^CC) ) Wd^CC   (+ the shared expert's CC part)
+// from the chunk-major bf16 weights in pinned host memory, in fp32.
+//
+// Work items are (expert, block of up to 8 rows of that expert, slice of its CC chunks); each item
+// owns its output rows in a scratch array, so no two threads ever add into the same memory and the
+// result does not depend on scheduling.  A second pass sums slices and slots per token.
+#include <atomic>
+#include <condition_variable>
+#include <cstring>
+#include <mutex>
+#include <thread>
+#include <vector>
+
+#include <algorithm>
+#include <cmath>
+
+#include "cc_worker.h"
+
+namespace si {
+
+namespace {
+
+typedef float v8f __attribute__((vector_size(32)));
+typedef uint16_t v8u16 __attribute__((vector_size(16)));
+typedef uint32_t v8u32 __attribute__((vector_size(32)));
+
+constexpr int RB = 8;  // rows per item
+
+inline v8f bf16x8_to_f32(const uint16_t* p) {
+  v8u16 raw;
+  std::memcpy(&raw, p, sizeof raw);
+  v8u32 wide = __builtin_convertvector(raw, v8u32) << 16;
+  v8f out;
+  std::memcpy(&out, &wide, sizeof out);
+  return out;
+}
+
+inline float hsum(v8f v) { return ((v[0] + v[4]) + (v[2] + v[6])) + ((v[1] + v[5]) + (v[3] + v[7])); }
+
+inline float silu_f(float z) { return z / (1.f + std::exp(-z)); }
+
+struct Item {
+  int expert;      // E = shared
+  int row0, nrows; // range in the expert's row list
+  int c0, c1;      // CC chunk range
+  int slice;
+};
+
+}  // namespace
+
+class CcPool {
+ public:
+  explicit CcPool(int n) : n_threads_(n < 1 ? 1 : n) {
+    for (int i = 0; i < n_threads_; ++i) threads_.emplace_back([this, i] { worker(i); });
+  }
+  ~CcPool() {
+    {
+      std::lock_guard<std::mutex> lk(mu_);
+      stop_ = true;
+      ++generation_;
+    }
+    cv_.notify_all();
+    for (auto& t : threads_) t.join();
+  }
+
+  void start(const CcJob& job) {
+    wait();
+    job_ = job;
+    plan();
+    {
+      std::lock_guard<std::mutex> lk(mu_);
+      next_item_.store(0);
+      next_token_.store(0);
+      items_done_.store(0);
+      running_ = n_threads_;
+      ++generation_;
+    }
+    cv_.notify_all();
+  }
+
+  void wait() {
+    std::unique_lock<std::mutex> lk(mu_);
+    done_cv_.wait(lk, [this] { return running_ == 0; });
+  }
+
+ private:
+  // expert-sorted row lists of the X1 tokens (built on the host from idx; order as the GPU's)
+  void plan() {
+    const CcJob& j = job_;
+    const int EX = j.E + (j.shared ? 1 : 0);
+    row_begin_.assign(EX + 1, 0);
+    for (int t = 0; t < j.T1; ++t)
+      for (int s = 0; s < j.k; ++s) row_begin_[j.idx[(size_t)t * j.k + s] + 1]++;
+    if (j.shared) row_begin_[j.E + 1] = j.T1;
+    for (int e = 0; e < EX; ++e) row_begin_[e + 1] += row_begin_[e];
+    const int n_rows = row_begin_[EX];
+    row_pair_.resize(n_rows);  // pair id t*k+s, or -(t+1) for a shared row
+    std::vector<int> fill(row_begin_.begin(), row_begin_.end() - 1);
+    for (int t = 0; t < j.T1; ++t)
+      for (int s = 0; s < j.k; ++s) row_pair_[fill[j.idx[(size_t)t * j.k + s]]++] = t * j.k + s;
+    if (j.shared)
+      for (int t = 0; t < j.T1; ++t) row_pair_[fill[j.E]++] = -(t + 1);
+    // number of row blocks, then how finely to slice the chunk range
+    int n_blocks = 0;
+    for (int e = 0; e < EX; ++e) n_blocks += (row_begin_[e + 1] - row_begin_[e] + RB - 1) / RB;
+    int want = 4 * n_threads_;
+    n_slices_ = n_blocks >= want ? 1 : (want + (n_blocks > 0 ? n_blocks : 1) - 1) / (n_blocks > 0 ? n_blocks : 1);
+    int max_chunks = std::max(j.n_cc_chunks, j.shared ? j.s_cc_chunks : 0);
+    if (n_slices_ > max_chunks) n_slices_ = max_chunks > 0 ? max_chunks : 1;
+    items_.clear();
+    for (int e = 0; e < EX; ++e) {
+      const int nch = e < j.E ? j.n_cc_chunks : j.s_cc_chunks;
+      if (nch == 0) continue;
+      for (int r = row_begin_[e]; r < row_begin_[e + 1]; r += RB)
+        for (int z = 0; z < n_slices_; ++z) {
+          int c0 = (int)((long)nch * z / n_slices_), c1 = (int)((long)nch * (z + 1) / n_slices_);
+          if (c1 > c0) items_.push_back({e, r, std::min(RB, row_begin_[e + 1] - r), c0, c1, z});
+        }
+    }
+    scratch_.assign((size_t)n_slices_ * n_rows * j.M, 0.f);
+    n_rows_ = n_rows;
+  }
+
+  void run_item(const Item& it, std::vector<float>& xf, std::vector<float>& hbuf) {
+    const CcJob& j = job_;
+    const int M = j.M;
+    const uint16_t* ebase = it.expert < j.E ? j.routed + (size_t)it.expert * j.expert_stride : j.shared;
+    xf.resize((size_t)RB * M);
+    for (int r = 0; r < it.nrows; ++r) {
+      int pr = row_pair_[it.row0 + r];
+      int t = pr >= 0 ? pr / j.k : -pr - 1;
+      const uint16_t* xr = j.x + (size_t)t * M;
+      for (int m = 0; m < M; m += 8) {
+        v8f v = bf16x8_to_f32(xr + m);
+        std::memcpy(&xf[(size_t)r * M + m], &v, sizeof v);
+      }
+    }
+    hbuf.resize((size_t)RB * CHUNK_J);
+    for (int c = it.c0; c < it.c1; ++c) {
+      const uint16_t* cb = ebase + (size_t)c * 3 * CHUNK_J * M;
+      // FC1 + activation
+      for (int jj = 0; jj < CHUNK_J; ++jj) {
+        const uint16_t* gr = cb + (size_t)jj * M;
+        const uint16_t* ur = cb + (size_t)(CHUNK_J + jj) * M;
+        v8f ag[RB], au[RB];
+        for (int r = 0; r < RB; ++r) { ag[r] = v8f{0, 0, 0, 0, 0, 0, 0, 0}; au[r] = ag[r]; }
+        for (int m = 0; m < M; m += 8) {
+          v8f wg = bf16x8_to_f32(gr + m), wu = bf16x8_to_f32(ur + m);
+          for (int r = 0; r < it.nrows; ++r) {
+            v8f xv;
+            std::memcpy(&xv, &xf[(size_t)r * M + m], sizeof xv);
+            ag[r] += xv * wg;
+            au[r] += xv * wu;
+          }
+        }
+        for (int r = 0; r < it.nrows; ++r) hbuf[(size_t)r * CHUNK_J + jj] = silu_f(hsum(ag[r])) * hsum(au[r]);
+      }
+      // FC2: down block [8 groups][M][8 j]
+      const uint16_t* db = cb + (size_t)2 * CHUNK_J * M;
+      for (int m = 0; m < M; ++m) {
+        v8f wd[8];
+        for (int q = 0; q < 8; ++q) wd[q] = bf16x8_to_f32(db + ((size_t)q * M + m) * 8);
+        for (int r = 0; r < it.nrows; ++r) {
+          v8f a = v8f{0, 0, 0, 0, 0, 0, 0, 0};
+          for (int q = 0; q < 8; ++q) {
+            v8f hv;
+            std::memcpy(&hv, &hbuf[(size_t)r * CHUNK_J + q * 8], sizeof hv);
+            a += hv * wd[q];
+          }
+          scratch_[((size_t)it.slice * n_rows_ + it.row0 + r) * M + m] += hsum(a);
+        }
+      }
+    }
+  }
+
+  void reduce_token(int t) {
+    const CcJob& j = job_;
+    const int M = j.M;
+    float* out = j.ycc + (size_t)t * M;
+    for (int m = 0; m < M; ++m) out[m] = 0.f;
+    // rows of token t: find them through a per-token inverse built lazily
+    for (int s = 0; s < j.k + (j.shared ? 1 : 0); ++s) {
+      int row;
+      float wgt;
+      if (s < j.k) { row = inv_[(size_t)t * j.k + s]; wgt = j.w[(size_t)t * j.k + s]; }
+      else { row = row_begin_[j.E] + t; wgt = 1.f; }
+      const int e = s < j.k ? j.idx[(size_t)t * j.k + s] : j.E;
+      if ((e < j.E ? j.n_cc_chunks : j.s_cc_chunks) == 0) continue;
+      for (int z = 0; z < n_slices_; ++z) {
+        const float* src = &scratch_[((size_t)z * n_rows_ + row) * M];
+        for (int m = 0; m < M; ++m) out[m] += wgt * src[m];
+      }
+    }
+  }
+
+  void worker(int) {
+    unsigned long seen = 0;
+    std::vector<float> xf, hbuf;
+    for (;;) {
+      {
+        std::unique_lock<std::mutex> lk(mu_);
+        cv_.wait(lk, [&] { return generation_ != seen; });
+        seen = generation_;
+        if (stop_) return;
+      }
+      const int n_items = (int)items_.size();
+      for (;;) {
+        int i = next_item_.fetch_add(1);
+        if (i >= n_items) break;
+        run_item(items_[i], xf, hbuf);
+        items_done_.fetch_add(1);
+      }
+      // barrier: the inverse map is built by whoever finishes first; wait until all items are done
+      while (items_done_.load(std::memory_order_acquire) < n_items) std::this_thread::yield();
+      {
+        std::lock_guard<std::mutex> lk(inv_mu_);
+        if (inv_gen_ != seen) {
+          inv_.assign((size_t)job_.T1 * job_.k, 0);
+          for (int e = 0; e < job_.E; ++e)
+            for (int r = row_begin_[e]; r < row_begin_[e + 1]; ++r) inv_[row_pair_[r]] = r;
+          inv_gen_ = seen;
+        }
+      }
+      for (;;) {
+        int t = next_token_.fetch_add(1);
+        if (t >= job_.T1) break;
+        reduce_token(t);
+      }
+      {
+        std::lock_guard<std::mutex> lk(mu_);
+        if (--running_ == 0) done_cv_.notify_all();
+      }
+    }
+  }
+
+  int n_threads_;
+  std::vector<std::thread> threads_;
+  std::mutex mu_, inv_mu_;
+  std::condition_variable cv_, done_cv_;
+  unsigned long generation_ = 0, inv_gen_ = 0;
+  bool stop_ = false;
+  int running_ = 0;
+  CcJob job_{};
+  std::vector<int> row_begin_, row_pair_, inv_;
+  std::vector<Item> items_;
+  std::vector<float> scratch_;
+  int n_slices_ = 1, n_rows_ = 0;
+  std::atomic<int> next_item_{0}, next_token_{0}, items_done_{0};
+};
+
+CcPool* cc_pool_create(int n_threads) { return new CcPool(n_threads); }
+void cc_pool_destroy(CcPool* p) { delete p; }
+void cc_pool_start(CcPool* p, const CcJob& job) { p->start(job); }
+void cc_pool_wait(CcPool* p) { p->wait(); }
+void cc_pool_run(CcPool* p, const CcJob& job) {
+  p->start(job);
+  p->wait();
+}
+
+}  // namespace si

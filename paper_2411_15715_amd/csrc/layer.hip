@@ -1,0 +1,686 @@
+// C ABI of the library: Memory Manager (slice + place, Section III-B) and Task Scheduler (one
+// layer forward over the CPU / copy / GPU resources, Section III-C) for one MI355X.
+//
+//   Stream-A  CPU computation  -> CcPool worker threads
+//   Stream-B  kernel launches  -> the calling host thread
+//   Stream-C  CPU->GPU copies  -> copy_stream (hipMemcpyAsync from pinned memory into a staging ring)
+//   Stream-D  GPU computation  -> the caller's stream
+// Dependencies: a CG kernel waits for the event recorded after its copy; a copy into a staging
+// slot waits for the event recorded after the kernels that last read the slot.
+#include <algorithm>
+#include <atomic>
+#include <chrono>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <functional>
+#include <string>
+#include <thread>
+#include <vector>
+
+#include "si_internal.h"
+
+using namespace si;
+
+namespace {
+
+thread_local std::string g_err;
+
+int fail(int code, const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  g_err = buf;
+  return code;
+}
+
+#define HIP_TRY(expr)                                                                           \
+  do {                                                                                          \
+    hipError_t _e = (expr);                                                                     \
+    if (_e != hipSuccess) return fail(SI_EHIP, "%s failed: %s", #expr, hipGetErrorString(_e));  \
+  } while (0)
+
+struct Seg { hipEvent_t a, b; int kind; };  // kind: 0 route, 1 gpu compute, 2 copy
+
+int split_counts(int H, int g, float r_gg, float r_cg, int* n_gg, int* n_cg, int* n_cc) {
+  if (H <= 0 || g <= 0 || H % g != 0) return -1;
+  const double a = (double)r_gg, b = (double)r_gg + (double)r_cg;
+  if (a < 0.0 || (double)r_cg < 0.0 || b > 1.0 + 1e-4) return -1;
+  const int units = H / g;
+  int ia = (int)std::floor(a * units + 0.5), ib = (int)std::floor(b * units + 0.5);
+  ia = std::min(ia, units);
+  ib = std::max(std::min(ib, units), ia);
+  *n_gg = ia * g;
+  *n_cg = (ib - ia) * g;
+  *n_cc = H - ib * g;
+  return 0;
+}
+
+// one expert [H][M] x3 -> chunk-major chunks [c0, c1) written at dst (see si_internal.h)
+void repack_chunks(const uint16_t* wg, const uint16_t* wu, const uint16_t* wd, int M, int c0, int c1, uint16_t* dst) {
+  for (int c = c0; c < c1; ++c) {
+    uint16_t* o = dst + (size_t)(c - c0) * 3 * CHUNK_J * M;
+    std::memcpy(o, wg + (size_t)c * CHUNK_J * M, (size_t)CHUNK_J * M * 2);
+    std::memcpy(o + (size_t)CHUNK_J * M, wu + (size_t)c * CHUNK_J * M, (size_t)CHUNK_J * M * 2);
+    uint16_t* d = o + (size_t)2 * CHUNK_J * M;
+    const uint16_t* src = wd + (size_t)c * CHUNK_J * M;
+    for (int q = 0; q < 8; ++q)
+      for (int jj = 0; jj < 8; ++jj) {
+        const uint16_t* row = src + (size_t)(q * 8 + jj) * M;
+        uint16_t* oq = d + (size_t)q * M * 8 + jj;
+        for (int m = 0; m < M; ++m) oq[(size_t)m * 8] = row[m];
+      }
+  }
+}
+
+void parallel_for(int n, int n_threads, const std::function<void(int)>& fn) {
+  if (n <= 0) return;
+  n_threads = std::max(1, std::min(n_threads, n));
+  std::atomic<int> next{0};
+  std::vector<std::thread> th;
+  for (int i = 0; i < n_threads; ++i)
+    th.emplace_back([&] {
+      for (;;) {
+        int j = next.fetch_add(1);
+        if (j >= n) break;
+        fn(j);
+      }
+    });
+  for (auto& t : th) t.join();
+}
+
+}  // namespace
+
+struct si_layer {
+  si_layer_desc_t desc{};
+  int M = 0, H = 0, E = 0, k = 0, Hs = 0, EX = 0, has_shared = 0, max_T = 0, device = 0;
+  int n_gg = 0, n_cg = 0, n_cc = 0, s_gg = 0, s_cg = 0, s_cc = 0;          // columns
+  int ch_gg = 0, ch_cg = 0, ch_cc = 0, sch_gg = 0, sch_cg = 0, sch_cc = 0;  // chunks
+  size_t ce = 0;                                                            // elements per chunk
+  uint16_t* d_gg = nullptr;     // device [E][ch_gg] chunks
+  uint16_t* d_sgg = nullptr;    // device [sch_gg] chunks
+  uint16_t* h_routed = nullptr; // pinned [E][ch_cc + ch_cg] chunks (CC first, then CG)
+  uint16_t* h_shared = nullptr; // pinned [sch_cc + sch_cg] chunks
+  int n_stage = 0, stage_chunks = 0;
+  std::vector<uint16_t*> d_stage;
+  std::vector<hipEvent_t> ev_ready, ev_free;
+  std::vector<char> slot_used;
+  long piece_counter = 0;
+  hipStream_t copy_stream = nullptr;
+  hipEvent_t ev_host = nullptr;
+  // device workspaces
+  char* d_plan = nullptr;
+  Plan plan{};
+  int max_tiles = 0;
+  float* d_h = nullptr;       // decode activations [rows_dec][ldh]
+  int ldh_dec = 0, rows_dec = 0;
+  float* d_part = nullptr;    // decode partials [3*DOWN_SLOTS][rows_dec][M]
+  uint16_t* d_hact = nullptr; // prefill activations
+  size_t hact_elems = 0;
+  float* d_yp = nullptr;      // prefill per-row outputs [max_T*(k+shared)][M]
+  float* d_ycc = nullptr;     // [max_T][M]
+  // pinned host mirrors
+  uint16_t* hx = nullptr;
+  int32_t* hidx = nullptr;
+  float* hw = nullptr;
+  int32_t* hcount = nullptr;  // [EX] count then [EX] count1
+  float* hycc = nullptr;
+  CcPool* pool = nullptr;
+  // stats
+  int profiling = 0;
+  std::vector<hipEvent_t> ev_pool;
+  size_t ev_used = 0;
+  std::vector<Seg> segs;
+  hipEvent_t ev_t0 = nullptr, ev_t1 = nullptr;
+  si_stats_t last{};
+};
+
+namespace {
+
+template <class T>
+int dev_alloc(T** p, size_t n) {
+  *p = nullptr;
+  if (n == 0) return SI_OK;
+  hipError_t e = hipMalloc((void**)p, n * sizeof(T));
+  if (e != hipSuccess) { (void)hipGetLastError(); return fail(SI_ENOMEM, "hipMalloc of %zu bytes failed: %s", n * sizeof(T), hipGetErrorString(e)); }
+  return SI_OK;
+}
+
+template <class T>
+int pin_alloc(T** p, size_t n) {
+  *p = nullptr;
+  if (n == 0) return SI_OK;
+  hipError_t e = hipHostMalloc((void**)p, n * sizeof(T), hipHostMallocDefault);
+  if (e != hipSuccess) { (void)hipGetLastError(); return fail(SI_ENOMEM, "hipHostMalloc of %zu bytes failed: %s", n * sizeof(T), hipGetErrorString(e)); }
+  return SI_OK;
+}
+
+hipEvent_t next_event(si_layer* L) {
+  if (L->ev_used == L->ev_pool.size()) {
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    L->ev_pool.push_back(e);
+  }
+  return L->ev_pool[L->ev_used++];
+}
+
+struct SegScope {
+  si_layer* L; hipStream_t s; int kind; hipEvent_t a = nullptr;
+  SegScope(si_layer* l, hipStream_t st, int k) : L(l), s(st), kind(k) {
+    if (L->profiling) { a = next_event(L); if (a) (void)hipEventRecord(a, s); }
+  }
+  ~SegScope() {
+    if (L->profiling && a) { hipEvent_t b = next_event(L); if (b) { (void)hipEventRecord(b, s); L->segs.push_back({a, b, kind}); } }
+  }
+};
+
+int validate_desc(const si_layer_desc_t* d, int* g_out) {
+  if (!d) return fail(SI_EINVAL, "desc is NULL");
+  if (d->d_model <= 0 || d->d_model % 64 != 0 || d->d_model > 8192)
+    return fail(SI_EINVAL, "d_model=%d must be a positive multiple of 64 (<= 8192)", d->d_model);
+  int g = d->granule == 0 ? 64 : d->granule;
+  if (g <= 0 || g % 64 != 0) return fail(SI_EINVAL, "granule=%d must be a positive multiple of 64", d->granule);
+  if (d->d_ff > 65536 || d->d_ff_shared > 65536) return fail(SI_EINVAL, "d_ff / d_ff_shared must be <= 65536");
+  if (d->d_ff <= 0 || d->d_ff % g != 0) return fail(SI_EINVAL, "d_ff=%d must be a positive multiple of granule=%d", d->d_ff, g);
+  if (d->d_ff_shared < 0 || d->d_ff_shared % g != 0)
+    return fail(SI_EINVAL, "d_ff_shared=%d must be 0 or a multiple of granule=%d", d->d_ff_shared, g);
+  if (d->n_experts < 1 || d->n_experts > MAX_EXPERTS) return fail(SI_EINVAL, "n_experts=%d out of range [1,%d]", d->n_experts, MAX_EXPERTS);
+  if (d->top_k < 1 || d->top_k > d->n_experts) return fail(SI_EINVAL, "top_k=%d must be in [1, n_experts=%d]", d->top_k, d->n_experts);
+  if (!(d->r_gg >= 0.f && d->r_gg <= 1.f && d->r_cg >= 0.f && d->r_cg <= 1.f && d->r_cc >= 0.f && d->r_cc <= 1.f))
+    return fail(SI_EINVAL, "rates must each lie in [0,1] (got %g %g %g)", d->r_gg, d->r_cg, d->r_cc);
+  if (std::fabs((double)d->r_gg + d->r_cg + d->r_cc - 1.0) > 1e-4)
+    return fail(SI_EINVAL, "rates must sum to 1 (got %g)", (double)d->r_gg + d->r_cg + d->r_cc);
+  if (d->max_tokens < 1) return fail(SI_EINVAL, "max_tokens=%d must be >= 1", d->max_tokens);
+  if (d->cc_threads < 0 || d->cc_threads > 1024) return fail(SI_EINVAL, "cc_threads=%d out of range", d->cc_threads);
+  if (d->stage_mib < 0 || d->n_stage < 0 || d->n_stage == 1 || d->n_stage > 16)
+    return fail(SI_EINVAL, "stage_mib=%d / n_stage=%d invalid (n_stage must be 0 or in [2,16])", d->stage_mib, d->n_stage);
+  *g_out = g;
+  return SI_OK;
+}
+
+int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+}  // namespace
+
+extern "C" {
+
+const char* si_last_error(void) { return g_err.c_str(); }
+const char* si_version(void) { return "scheinfer-mi355x 0.1 (gfx950)"; }
+
+int si_split_counts(int32_t d_ff, int32_t granule, float r_gg, float r_cg, int32_t* n_gg, int32_t* n_cg, int32_t* n_cc) {
+  int g = granule == 0 ? 64 : granule;
+  int a, b, c;
+  if (!n_gg || !n_cg || !n_cc) return fail(SI_EINVAL, "output pointer is NULL");
+  if (split_counts(d_ff, g, r_gg, r_cg, &a, &b, &c)) return fail(SI_EINVAL, "invalid d_ff/granule/rates");
+  *n_gg = a; *n_cg = b; *n_cc = c;
+  return SI_OK;
+}
+
+int si_repack_chunks(const uint16_t* w_gate, const uint16_t* w_up, const uint16_t* w_down, int32_t d_ff, int32_t d_model,
+                     int32_t chunk0, int32_t n_chunks, uint16_t* out) {
+  if (!w_gate || !w_up || !w_down || !out) return fail(SI_EINVAL, "NULL pointer");
+  if (d_model <= 0 || d_model % 8 != 0 || d_ff <= 0 || d_ff % CHUNK_J != 0) return fail(SI_EINVAL, "bad d_ff=%d / d_model=%d", d_ff, d_model);
+  if (chunk0 < 0 || n_chunks < 0 || (chunk0 + n_chunks) * CHUNK_J > d_ff) return fail(SI_EINVAL, "chunk range [%d,+%d) outside d_ff=%d", chunk0, n_chunks, d_ff);
+  repack_chunks(w_gate, w_up, w_down, d_model, chunk0, chunk0 + n_chunks, out);
+  return SI_OK;
+}
+
+int si_cc_compute(const uint16_t* x, const int32_t* idx, const float* w, int32_t T1, int32_t k, int32_t d_model,
+                  int32_t n_experts, const uint16_t* routed, uint64_t expert_stride, int32_t n_cc_chunks,
+                  const uint16_t* shared, int32_t s_cc_chunks, int32_t threads, float* ycc) {
+  if (!x || !idx || !w || !ycc || (!routed && n_cc_chunks > 0)) return fail(SI_EINVAL, "NULL pointer");
+  if (T1 < 0 || k < 1 || d_model <= 0 || d_model % 8 != 0 || n_experts < 1 || n_cc_chunks < 0 || s_cc_chunks < 0 || threads < 1)
+    return fail(SI_EINVAL, "bad argument");
+  for (long q = 0; q < (long)T1 * k; ++q)
+    if (idx[q] < 0 || idx[q] >= n_experts) return fail(SI_EINVAL, "idx[%ld]=%d outside [0,%d)", q, idx[q], n_experts);
+  if (T1 == 0) return SI_OK;
+  CcJob job{};
+  job.x = x; job.idx = idx; job.w = w; job.T1 = T1; job.k = k; job.M = d_model; job.E = n_experts;
+  job.routed = routed; job.expert_stride = (size_t)expert_stride; job.n_cc_chunks = n_cc_chunks;
+  job.shared = s_cc_chunks > 0 ? shared : nullptr; job.s_cc_chunks = shared ? s_cc_chunks : 0; job.ycc = ycc;
+  if (n_cc_chunks == 0 && !job.shared) { std::memset(ycc, 0, (size_t)T1 * d_model * 4); return SI_OK; }
+  CcPool* pool = cc_pool_create(threads);
+  cc_pool_run(pool, job);
+  cc_pool_destroy(pool);
+  return SI_OK;
+}
+
+void si_layer_destroy(si_layer_t* L) {
+  if (!L) return;
+  (void)hipSetDevice(L->device);
+  if (L->pool) cc_pool_destroy(L->pool);
+  if (L->copy_stream) { (void)hipStreamSynchronize(L->copy_stream); }
+  (void)hipDeviceSynchronize();
+  for (auto p : L->d_stage) if (p) (void)hipFree(p);
+  for (auto e : L->ev_ready) if (e) (void)hipEventDestroy(e);
+  for (auto e : L->ev_free) if (e) (void)hipEventDestroy(e);
+  for (auto e : L->ev_pool) if (e) (void)hipEventDestroy(e);
+  if (L->ev_host) (void)hipEventDestroy(L->ev_host);
+  if (L->ev_t0) (void)hipEventDestroy(L->ev_t0);
+  if (L->ev_t1) (void)hipEventDestroy(L->ev_t1);
+  if (L->copy_stream) (void)hipStreamDestroy(L->copy_stream);
+  void* dev[] = {L->d_gg, L->d_sgg, L->d_plan, L->d_h, L->d_part, L->d_hact, L->d_yp, L->d_ycc};
+  for (void* p : dev) if (p) (void)hipFree(p);
+  void* pin[] = {L->h_routed, L->h_shared, L->hx, L->hidx, L->hw, L->hcount, L->hycc};
+  for (void* p : pin) if (p) (void)hipHostFree(p);
+  delete L;
+}
+
+int si_layer_create(const si_layer_desc_t* desc, const uint16_t* w_gate, const uint16_t* w_up, const uint16_t* w_down,
+                    const uint16_t* shared_gate, const uint16_t* shared_up, const uint16_t* shared_down,
+                    si_layer_t** out) {
+  int g = 64;
+  if (!out) return fail(SI_EINVAL, "out is NULL");
+  *out = nullptr;
+  int rc = validate_desc(desc, &g);
+  if (rc) return rc;
+  if (!w_gate || !w_up || !w_down) return fail(SI_EINVAL, "expert weight pointer is NULL");
+  if (desc->d_ff_shared > 0 && (!shared_gate || !shared_up || !shared_down))
+    return fail(SI_EINVAL, "d_ff_shared > 0 but a shared weight pointer is NULL");
+  int n_dev = 0;
+  if (hipGetDeviceCount(&n_dev) != hipSuccess || desc->device < 0 || desc->device >= n_dev) {
+    (void)hipGetLastError();
+    return fail(SI_EHIP, "HIP device %d not available (%d devices visible)", desc->device, n_dev);
+  }
+  HIP_TRY(hipSetDevice(desc->device));
+
+  si_layer* L = new si_layer();
+  L->desc = *desc;
+  L->M = desc->d_model; L->H = desc->d_ff; L->E = desc->n_experts; L->k = desc->top_k; L->Hs = desc->d_ff_shared;
+  L->has_shared = L->Hs > 0; L->EX = L->E + L->has_shared; L->max_T = desc->max_tokens; L->device = desc->device;
+  split_counts(L->H, g, desc->r_gg, desc->r_cg, &L->n_gg, &L->n_cg, &L->n_cc);
+  if (L->has_shared) split_counts(L->Hs, g, desc->r_gg, desc->r_cg, &L->s_gg, &L->s_cg, &L->s_cc);
+  L->ch_gg = L->n_gg / CHUNK_J; L->ch_cg = L->n_cg / CHUNK_J; L->ch_cc = L->n_cc / CHUNK_J;
+  L->sch_gg = L->s_gg / CHUNK_J; L->sch_cg = L->s_cg / CHUNK_J; L->sch_cc = L->s_cc / CHUNK_J;
+  L->ce = chunk_elems(L->M);
+  const int M = L->M, E = L->E, k = L->k, T = L->max_T;
+  const size_t ce = L->ce;
+  const int hch = L->ch_cc + L->ch_cg, shch = L->sch_cc + L->sch_cg;
+
+#define TRY_OR_DESTROY(expr) do { int _rc = (expr); if (_rc) { si_layer_destroy(L); return _rc; } } while (0)
+#define HIP_OR_DESTROY(expr) do { hipError_t _e = (expr); if (_e != hipSuccess) { fail(SI_EHIP, "%s failed: %s", #expr, hipGetErrorString(_e)); si_layer_destroy(L); return SI_EHIP; } } while (0)
+
+  // ---- placement: GG -> device, CC | CG -> pinned host (CG' aliases the CC range)
+  TRY_OR_DESTROY(dev_alloc(&L->d_gg, (size_t)E * L->ch_gg * ce));
+  TRY_OR_DESTROY(dev_alloc(&L->d_sgg, (size_t)L->sch_gg * ce));
+  TRY_OR_DESTROY(pin_alloc(&L->h_routed, (size_t)E * hch * ce));
+  TRY_OR_DESTROY(pin_alloc(&L->h_shared, (size_t)shch * ce));
+  const int hw_threads = (int)std::max(1u, std::thread::hardware_concurrency());
+  const int rp_threads = std::min(16, hw_threads);
+  {
+    // host parts: repack straight into the pinned buffers
+    const int per = hch;  // chunks per expert on the host
+    parallel_for(E * per, rp_threads, [&](int i) {
+      int e = i / per, c = i % per;
+      repack_chunks(w_gate + (size_t)e * L->H * M, w_up + (size_t)e * L->H * M, w_down + (size_t)e * L->H * M, M, c, c + 1,
+                    L->h_routed + ((size_t)e * per + c) * ce);
+    });
+    parallel_for(shch, rp_threads, [&](int c) { repack_chunks(shared_gate, shared_up, shared_down, M, c, c + 1, L->h_shared + (size_t)c * ce); });
+    // GG parts: repack through a pinned bounce buffer, a group of chunks at a time
+    const int bounce_chunks = std::max(1, (int)std::min<size_t>(256, ((size_t)256 << 20) / (ce * 2)));
+    uint16_t* bounce = nullptr;
+    if ((size_t)E * L->ch_gg + L->sch_gg > 0) TRY_OR_DESTROY(pin_alloc(&bounce, (size_t)bounce_chunks * ce));
+    auto upload = [&](const uint16_t* wg, const uint16_t* wu, const uint16_t* wd, int c_first, int n, uint16_t* dst) -> hipError_t {
+      for (int c0 = 0; c0 < n; c0 += bounce_chunks) {
+        int nb = std::min(bounce_chunks, n - c0);
+        parallel_for(nb, rp_threads, [&](int i) { repack_chunks(wg, wu, wd, M, c_first + c0 + i, c_first + c0 + i + 1, bounce + (size_t)i * ce); });
+        hipError_t e2 = hipMemcpy(dst + (size_t)c0 * ce, bounce, (size_t)nb * ce * 2, hipMemcpyHostToDevice);
+        if (e2 != hipSuccess) return e2;
+      }
+      return hipSuccess;
+    };
+    hipError_t ue = hipSuccess;
+    for (int e = 0; e < E && ue == hipSuccess; ++e)
+      ue = upload(w_gate + (size_t)e * L->H * M, w_up + (size_t)e * L->H * M, w_down + (size_t)e * L->H * M, hch, L->ch_gg,
+                  L->d_gg + (size_t)e * L->ch_gg * ce);
+    if (ue == hipSuccess && L->has_shared) ue = upload(shared_gate, shared_up, shared_down, shch, L->sch_gg, L->d_sgg);
+    if (bounce) (void)hipHostFree(bounce);
+    HIP_OR_DESTROY(ue);
+  }
+
+  // ---- staging ring for CG / CG' copies (Stream-C)
+  L->n_stage = desc->n_stage == 0 ? 2 : desc->n_stage;
+  const bool any_host = hch + shch > 0;
+  if (any_host) {
+    size_t stage_bytes = (size_t)(desc->stage_mib == 0 ? 64 : desc->stage_mib) << 20;
+    int sc = (int)std::max<size_t>(1, stage_bytes / (ce * 2));
+    // a decode piece must hold whole down-projection slots
+    int cps_max = std::max({ceil_div(L->ch_cg, DOWN_SLOTS), ceil_div(L->ch_cc, DOWN_SLOTS), ceil_div(L->sch_cg, DOWN_SLOTS), ceil_div(L->sch_cc, DOWN_SLOTS), 1});
+    L->stage_chunks = std::max(sc, cps_max);
+    L->d_stage.assign(L->n_stage, nullptr);
+    L->ev_ready.assign(L->n_stage, nullptr);
+    L->ev_free.assign(L->n_stage, nullptr);
+    L->slot_used.assign(L->n_stage, 0);
+    for (int i = 0; i < L->n_stage; ++i) {
+      TRY_OR_DESTROY(dev_alloc(&L->d_stage[i], (size_t)L->stage_chunks * ce));
+      HIP_OR_DESTROY(hipEventCreateWithFlags(&L->ev_ready[i], hipEventDisableTiming));
+      HIP_OR_DESTROY(hipEventCreateWithFlags(&L->ev_free[i], hipEventDisableTiming));
+    }
+  }
+  HIP_OR_DESTROY(hipStreamCreateWithFlags(&L->copy_stream, hipStreamNonBlocking));
+  HIP_OR_DESTROY(hipEventCreateWithFlags(&L->ev_host, hipEventDisableTiming));
+  HIP_OR_DESTROY(hipEventCreate(&L->ev_t0));
+  HIP_OR_DESTROY(hipEventCreate(&L->ev_t1));
+
+  // ---- workspaces
+  const size_t n_pairs = (size_t)T * k, n_rows = n_pairs + (L->has_shared ? T : 0);
+  L->max_tiles = (int)(n_rows / PREFILL_BM) + L->EX + 2;
+  {
+    size_t ints = 0;
+    auto take = [&](size_t n) { size_t o = ints; ints += (n + 3) / 4 * 4; return o; };
+    size_t o_idx = take(n_pairs), o_w = take(n_pairs), o_count = take(L->EX), o_off = take(L->EX + 1), o_count1 = take(L->EX),
+           o_perm = take(n_pairs), o_inv = take(n_pairs), o_rt = take(n_rows), o_touched = take(L->EX), o_nt = take(4),
+           o_te = take(L->max_tiles), o_tr = take(L->max_tiles), o_te2 = take(L->max_tiles), o_tr2 = take(L->max_tiles);
+    TRY_OR_DESTROY(dev_alloc(&L->d_plan, ints * 4));
+    int32_t* b = reinterpret_cast<int32_t*>(L->d_plan);
+    L->plan.idx = b + o_idx; L->plan.w = reinterpret_cast<float*>(b + o_w); L->plan.count = b + o_count;
+    L->plan.off = b + o_off; L->plan.count1 = b + o_count1; L->plan.perm = b + o_perm; L->plan.inv = b + o_inv;
+    L->plan.row_token = b + o_rt; L->plan.touched = b + o_touched; L->plan.n_touched = b + o_nt;
+    L->plan.n_tiles = b + o_nt + 1; L->plan.n_tiles_x2 = b + o_nt + 2;
+    L->plan.n_routed = E;
+    L->plan.tile_e = b + o_te; L->plan.tile_r = b + o_tr; L->plan.tile_e_x2 = b + o_te2; L->plan.tile_r_x2 = b + o_tr2;
+  }
+  const int T_dec = std::min(T, SI_DECODE_MAX_T);
+  L->rows_dec = T_dec * (k + L->has_shared);
+  L->ldh_dec = std::max(L->H, L->Hs);
+  TRY_OR_DESTROY(dev_alloc(&L->d_h, (size_t)L->rows_dec * L->ldh_dec));
+  TRY_OR_DESTROY(dev_alloc(&L->d_part, (size_t)3 * DOWN_SLOTS * L->rows_dec * M));
+  {
+    // widest launch of the prefill path: the GG part, or one staged piece
+    int cols = std::max({L->n_gg, L->s_gg, any_host ? L->stage_chunks * CHUNK_J : 0});
+    L->hact_elems = n_rows * (size_t)cols;
+    if (T > SI_DECODE_AUTO_T || true) TRY_OR_DESTROY(dev_alloc(&L->d_hact, L->hact_elems));
+    TRY_OR_DESTROY(dev_alloc(&L->d_yp, n_rows * (size_t)M));
+  }
+  TRY_OR_DESTROY(dev_alloc(&L->d_ycc, (size_t)T * M));
+  TRY_OR_DESTROY(pin_alloc(&L->hx, (size_t)T * M));
+  TRY_OR_DESTROY(pin_alloc(&L->hidx, n_pairs));
+  TRY_OR_DESTROY(pin_alloc(&L->hw, n_pairs));
+  TRY_OR_DESTROY(pin_alloc(&L->hcount, (size_t)2 * L->EX));
+  TRY_OR_DESTROY(pin_alloc(&L->hycc, (size_t)T * M));
+  if (L->ch_cc + L->sch_cc > 0) {
+    int nt = desc->cc_threads == 0 ? std::min(16, hw_threads) : desc->cc_threads;
+    L->pool = cc_pool_create(nt);
+  }
+  HIP_OR_DESTROY(hipDeviceSynchronize());
+  *out = L;
+  return SI_OK;
+}
+
+int si_layer_split_info(const si_layer_t* L, int32_t* n_gg, int32_t* n_cg, int32_t* n_cc, int32_t* s_gg, int32_t* s_cg, int32_t* s_cc) {
+  if (!L) return fail(SI_EINVAL, "layer is NULL");
+  if (n_gg) *n_gg = L->n_gg;
+  if (n_cg) *n_cg = L->n_cg;
+  if (n_cc) *n_cc = L->n_cc;
+  if (s_gg) *s_gg = L->s_gg;
+  if (s_cg) *s_cg = L->s_cg;
+  if (s_cc) *s_cc = L->s_cc;
+  return SI_OK;
+}
+
+int si_layer_set_profiling(si_layer_t* L, int32_t on) {
+  if (!L) return fail(SI_EINVAL, "layer is NULL");
+  L->profiling = on ? 1 : 0;
+  return SI_OK;
+}
+
+int si_route(const float* logits_dev, int32_t T, int32_t E, int32_t k, const si_routing_out_t* out, void* stream) {
+  if (!logits_dev || !out) return fail(SI_EINVAL, "logits_dev or out is NULL");
+  if (T < 0 || E < 1 || E > MAX_EXPERTS || k < 1 || k > E) return fail(SI_EINVAL, "bad T=%d E=%d k=%d", T, E, k);
+  if (T == 0) return SI_OK;
+  // scratch for idx / w when the caller does not ask for them
+  int32_t* tmp = nullptr;
+  const size_t n = (size_t)T * k;
+  Plan p{};
+  RouteOut u{nullptr, nullptr, out->count, out->off, out->perm, out->inv};
+  hipStream_t s = (hipStream_t)stream;
+  if (!out->idx || !out->w) {
+    HIP_TRY(hipMallocAsync((void**)&tmp, 2 * n * 4, s));
+  }
+  p.idx = out->idx ? out->idx : tmp;
+  p.w = out->w ? out->w : reinterpret_cast<float*>(tmp + n);
+  hipError_t e = launch_route(logits_dev, T, E, k, 0, 0, PREFILL_BM, p, u, s);
+  if (tmp) (void)hipFreeAsync(tmp, s);
+  if (e != hipSuccess) return fail(SI_EHIP, "route launch failed: %s", hipGetErrorString(e));
+  return SI_OK;
+}
+
+// One staged piece: chunks [c0, c0+n) of one expert's host range.
+struct Piece { int expert; int c0, n; int part; /* 1 = CG, 2 = CC (CG') */ };
+
+int si_layer_forward(si_layer_t* L, const void* x_dev, const float* logits_dev, int32_t T, int32_t n_g, int32_t mode,
+                     float* y_dev, const si_routing_out_t* rout, void* stream_v) {
+  if (!L) return fail(SI_EINVAL, "layer is NULL");
+  if (T < 0 || n_g < 0 || n_g > T) return fail(SI_EINVAL, "need 0 <= n_g <= T (T=%d n_g=%d)", T, n_g);
+  if (mode != SI_AUTO && mode != SI_DECODE && mode != SI_PREFILL) return fail(SI_EINVAL, "bad mode %d", mode);
+  if (T > L->max_T) return fail(SI_ESTATE, "T=%d exceeds max_tokens=%d", T, L->max_T);
+  if (T == 0) return SI_OK;
+  if (!x_dev || !y_dev) return fail(SI_EINVAL, "x_dev or y_dev is NULL");
+  if (L->E > 1 && !logits_dev) return fail(SI_EINVAL, "logits_dev is NULL for a layer with %d experts", L->E);
+  const int path = mode == SI_AUTO ? (T <= SI_DECODE_AUTO_T ? SI_DECODE : SI_PREFILL) : mode;
+  if (path == SI_DECODE && T > SI_DECODE_MAX_T) return fail(SI_ESTATE, "SI_DECODE needs T <= %d (T=%d)", SI_DECODE_MAX_T, T);
+  HIP_TRY(hipSetDevice(L->device));
+  hipStream_t stream = (hipStream_t)stream_v;
+  const uint16_t* x = static_cast<const uint16_t*>(x_dev);
+  const int M = L->M, E = L->E, k = L->k, EX = L->EX;
+  const size_t ce = L->ce;
+  const int n_x1 = T - n_g;
+  const int hch = L->ch_cc + L->ch_cg;
+  const bool any_cc = L->ch_cc + L->sch_cc > 0, any_cg = L->ch_cg + L->sch_cg > 0;
+  const bool need_cc = any_cc && n_x1 > 0;   // Stream-A work
+  const bool need_cgp = any_cc && n_g > 0;   // CG': CC weights on the GPU for X2
+  const bool need_counts = (any_cg || need_cgp) && E > 1;  // which experts to stream
+  const bool need_sync = need_cc || need_counts;
+  const auto wall0 = std::chrono::steady_clock::now();
+
+  L->ev_used = 0;
+  L->segs.clear();
+  si_stats_t st{};
+  st.path = path;
+  st.n_touched = -1;
+  if (L->profiling) HIP_TRY(hipEventRecord(L->ev_t0, stream));
+
+  // ---- token assignment (Section II-A)
+  RouteOut u{};
+  if (rout) u = RouteOut{rout->idx, rout->w, rout->count, rout->off, rout->perm, rout->inv};
+  {
+    SegScope sc(L, stream, 0);
+    hipError_t e = launch_route(E > 1 ? logits_dev : nullptr, T, E, k, L->has_shared, n_g, PREFILL_BM, L->plan, u, stream);
+    if (e != hipSuccess) return fail(SI_EHIP, "route launch failed: %s", hipGetErrorString(e));
+  }
+  // ---- hand-off to the host: X1 and the assignment (Section III-B: "X1 will be additionally
+  //      transferred into CPU"), and the per-expert counts the copy scheduler needs
+  if (need_sync) {
+    if (need_cc) {
+      HIP_TRY(hipMemcpyAsync(L->hx, x, (size_t)n_x1 * M * 2, hipMemcpyDeviceToHost, stream));
+      HIP_TRY(hipMemcpyAsync(L->hidx, L->plan.idx, (size_t)T * k * 4, hipMemcpyDeviceToHost, stream));
+      HIP_TRY(hipMemcpyAsync(L->hw, L->plan.w, (size_t)T * k * 4, hipMemcpyDeviceToHost, stream));
+    }
+    HIP_TRY(hipMemcpyAsync(L->hcount, L->plan.count, (size_t)EX * 4, hipMemcpyDeviceToHost, stream));
+    HIP_TRY(hipMemcpyAsync(L->hcount + EX, L->plan.count1, (size_t)EX * 4, hipMemcpyDeviceToHost, stream));
+    HIP_TRY(hipEventRecord(L->ev_host, stream));
+    HIP_TRY(hipEventSynchronize(L->ev_host));
+    int nt = 0;
+    for (int e = 0; e < EX; ++e) nt += L->hcount[e] > 0;
+    st.n_touched = nt;
+  } else if (E == 1) {
+    st.n_touched = EX;
+  }
+  std::chrono::steady_clock::time_point cc0;
+  if (need_cc) {
+    CcJob job{};
+    job.x = L->hx; job.idx = L->hidx; job.w = L->hw; job.T1 = n_x1; job.k = k; job.M = M; job.E = E;
+    job.routed = L->h_routed; job.expert_stride = (size_t)hch * ce; job.n_cc_chunks = L->ch_cc;
+    job.shared = (L->has_shared && L->sch_cc > 0) ? L->h_shared : nullptr; job.s_cc_chunks = L->sch_cc;
+    job.ycc = L->hycc;
+    if (L->ch_cc == 0 && !job.shared) {
+      std::memset(L->hycc, 0, (size_t)n_x1 * M * 4);
+    } else {
+      cc0 = std::chrono::steady_clock::now();
+      cc_pool_start(L->pool, job);
+    }
+  }
+
+  // counts per expert as known on the host (dense layers need no copy)
+  auto rows_all = [&](int e) { return need_sync ? L->hcount[e] : T; };
+  auto rows_x2 = [&](int e) { return need_sync ? L->hcount[e] - L->hcount[EX + e] : n_g; };
+  const int max_touched = std::min(EX, T * k + L->has_shared);
+  const int tiles_upper = (T * k) / PREFILL_BM + E;  // bound on the routed row tiles
+  const int cps_gg = std::max(1, ceil_div(L->ch_gg, DOWN_SLOTS)), cps_cg = std::max(1, ceil_div(L->ch_cg, DOWN_SLOTS)),
+            cps_cc = std::max(1, ceil_div(L->ch_cc, DOWN_SLOTS));
+  const int scps_gg = std::max(1, ceil_div(L->sch_gg, DOWN_SLOTS)), scps_cg = std::max(1, ceil_div(L->sch_cg, DOWN_SLOTS)),
+            scps_cc = std::max(1, ceil_div(L->sch_cc, DOWN_SLOTS));
+  const size_t slot_stride = (size_t)L->rows_dec * M;
+  hipError_t ke = hipSuccess;
+#define K_TRY(expr) do { ke = (expr); if (ke != hipSuccess) return fail(SI_EHIP, "%s failed: %s", #expr, hipGetErrorString(ke)); } while (0)
+
+  // process chunks [c0, c0+n) (relative to `base`) of a part on the GPU.
+  //   expert_sel < 0: all routed experts from their resident GG storage
+  //   col_base: hidden column of chunk c0 within the expert;  part: 0 GG, 1 CG, 2 CC(CG')
+  auto run_part = [&](const uint16_t* base, size_t estride, int expert_sel, int is_shared, int c0, int n, int col_base,
+                      int part, int part_chunk0, int x2_only, bool first_for_rows) -> int {
+    if (n <= 0) return SI_OK;
+    WeightView wv{base, estride, c0, n, 0};
+    const int esel = is_shared ? E : expert_sel;
+    if (path == SI_DECODE) {
+      wv.col0 = col_base;
+      const int cps = is_shared ? (part == 0 ? scps_gg : part == 1 ? scps_cg : scps_cc) : (part == 0 ? cps_gg : part == 1 ? cps_cg : cps_cc);
+      K_TRY(launch_decode_gateup(x, M, L->plan, EX, esel, x2_only, max_touched, wv, L->d_h, L->ldh_dec, stream));
+      K_TRY(launch_decode_down(L->d_h, L->ldh_dec, M, L->plan, EX, esel, x2_only, max_touched, wv,
+                               part * DOWN_SLOTS + part_chunk0 / cps, cps, L->d_part, slot_stride, stream));
+    } else {
+      int n_rt;
+      if (esel >= 0) n_rt = ceil_div(x2_only ? rows_x2(esel) : rows_all(esel), PREFILL_BM);
+      else n_rt = tiles_upper;
+      const int ldh = n * CHUNK_J;
+      K_TRY(launch_prefill_gateup(x, M, L->plan, esel, x2_only, n_rt, wv, L->d_hact, ldh, stream));
+      K_TRY(launch_prefill_down(L->d_hact, ldh, M, L->plan, esel, x2_only, n_rt, wv, L->d_yp, first_for_rows ? 0 : 1, stream));
+    }
+    return SI_OK;
+  };
+
+  // ---- GG part (Stream-D), enqueued first so that it runs under the first copies.
+  // In the prefill path the GG launch overwrites the per-row outputs and every staged piece adds to
+  // them; rows without a GG part start from zero.
+  {
+    SegScope sc(L, stream, 1);
+    int rc;
+    if (path == SI_PREFILL) {
+      if (L->ch_gg == 0) K_TRY(launch_fill_zero(L->d_yp, (size_t)T * k * M, stream));
+      if (L->has_shared && L->sch_gg == 0) K_TRY(launch_fill_zero(L->d_yp + (size_t)T * k * M, (size_t)T * M, stream));
+    }
+    if (E == 1) rc = run_part(L->d_gg, 0, 0, 0, 0, L->ch_gg, hch * CHUNK_J, 0, 0, 0, true);
+    else rc = run_part(L->d_gg, (size_t)L->ch_gg * ce, -1, 0, 0, L->ch_gg, hch * CHUNK_J, 0, 0, 0, true);
+    if (rc) return rc;
+    if (L->has_shared) {
+      rc = run_part(L->d_sgg, 0, 0, 1, 0, L->sch_gg, (L->sch_cc + L->sch_cg) * CHUNK_J, 0, 0, 0, true);
+      if (rc) return rc;
+    }
+    st.bytes_gg = 0;
+    for (int e = 0; e < EX; ++e) {
+      const bool touched = need_sync ? L->hcount[e] > 0 : true;
+      if (touched) st.bytes_gg += (double)(e < E ? L->ch_gg : L->sch_gg) * ce * 2;
+    }
+    if (!need_sync && E > 1) st.bytes_gg = -1;  // not known on the host without the counts
+  }
+
+  // ---- CG and CG' parts: copy (Stream-C) double-buffered against compute (Stream-D)
+  if (any_cg || need_cgp) {
+    for (int e = 0; e < EX; ++e) {
+      if (rows_all(e) <= 0) continue;
+      const bool sh = e >= E;
+      const int n_cc_e = sh ? L->sch_cc : L->ch_cc, n_cg_e = sh ? L->sch_cg : L->ch_cg;
+      const uint16_t* hbase = sh ? L->h_shared : L->h_routed + (size_t)e * hch * ce;
+      for (int part = 1; part <= 2; ++part) {  // CG on all rows, then CG' (the CC range) on the X2 rows
+        const int x2_only = part == 2;
+        if (part == 2 && (!need_cgp || rows_x2(e) <= 0)) continue;
+        const int pc0 = part == 2 ? 0 : n_cc_e, pn = part == 2 ? n_cc_e : n_cg_e;
+        const int cps = sh ? (part == 2 ? scps_cc : scps_cg) : (part == 2 ? cps_cc : cps_cg);
+        const int piece_max = path == SI_DECODE ? std::max(cps, L->stage_chunks / cps * cps) : L->stage_chunks;
+        for (int c = 0; c < pn; c += piece_max) {
+          const int n = std::min(piece_max, pn - c);
+          const int slot = (int)(L->piece_counter++ % L->n_stage);
+          if (L->slot_used[slot]) HIP_TRY(hipStreamWaitEvent(L->copy_stream, L->ev_free[slot], 0));
+          {
+            SegScope sc(L, L->copy_stream, 2);
+            HIP_TRY(hipMemcpyAsync(L->d_stage[slot], hbase + (size_t)(pc0 + c) * ce, (size_t)n * ce * 2, hipMemcpyHostToDevice, L->copy_stream));
+          }
+          HIP_TRY(hipEventRecord(L->ev_ready[slot], L->copy_stream));
+          HIP_TRY(hipStreamWaitEvent(stream, L->ev_ready[slot], 0));
+          {
+            SegScope sc(L, stream, 1);
+            int rc = run_part(L->d_stage[slot], 0, sh ? 0 : e, sh, 0, n, (pc0 + c) * CHUNK_J, part, c, x2_only, false);
+            if (rc) return rc;
+          }
+          HIP_TRY(hipEventRecord(L->ev_free[slot], stream));
+          L->slot_used[slot] = 1;
+          st.bytes_streamed += (double)n * ce * 2;
+          st.n_copies++;
+        }
+      }
+    }
+  }
+
+  // ---- CC result: wait for Stream-A, send Y^CC to the GPU
+  const float* ycc_dev = nullptr;
+  if (need_cc) {
+    if (L->ch_cc > 0 || (L->has_shared && L->sch_cc > 0)) {
+      cc_pool_wait(L->pool);
+      st.cc_ms = std::chrono::duration<float, std::milli>(std::chrono::steady_clock::now() - cc0).count();
+      double b = 0;
+      for (int e = 0; e < EX; ++e) if (L->hcount[EX + e] > 0) b += (double)(e < E ? L->ch_cc : L->sch_cc) * ce * 2;
+      st.bytes_cc = b;
+    }
+    HIP_TRY(hipMemcpyAsync(L->d_ycc, L->hycc, (size_t)n_x1 * M * 4, hipMemcpyHostToDevice, stream));
+    ycc_dev = L->d_ycc;
+  }
+
+  // ---- merge: Y = Y^CC (or Y^CG') + Y^CG + Y^GG (Eq. 2) and the weighted sum over experts
+  {
+    SegScope sc(L, stream, 1);
+    if (path == SI_DECODE) {
+      DecodeCombineArgs a{};
+      a.part = L->d_part; a.slot_stride = slot_stride;
+      a.n_slots_gg = ceil_div(L->ch_gg, cps_gg); a.n_slots_cg = ceil_div(L->ch_cg, cps_cg); a.n_slots_cc = need_cgp ? ceil_div(L->ch_cc, cps_cc) : 0;
+      a.s_slots_gg = ceil_div(L->sch_gg, scps_gg); a.s_slots_cg = ceil_div(L->sch_cg, scps_cg); a.s_slots_cc = need_cgp ? ceil_div(L->sch_cc, scps_cc) : 0;
+      a.ycc = ycc_dev; a.T = T; a.k = k; a.M = M; a.n_x1 = n_x1; a.has_shared = L->has_shared;
+      K_TRY(launch_decode_combine(a, L->plan, y_dev, stream));
+    } else {
+      K_TRY(launch_prefill_combine(L->d_yp, ycc_dev, T, k, M, n_x1, L->has_shared, L->plan, y_dev, stream));
+    }
+  }
+  if (L->profiling) HIP_TRY(hipEventRecord(L->ev_t1, stream));
+  st.total_ms = std::chrono::duration<float, std::milli>(std::chrono::steady_clock::now() - wall0).count();  // replaced by event time in si_layer_stats
+  L->last = st;
+  return SI_OK;
+}
+
+int si_layer_stats(si_layer_t* L, si_stats_t* out) {
+  if (!L || !out) return fail(SI_EINVAL, "layer or out is NULL");
+  si_stats_t st = L->last;
+  if (L->profiling && L->ev_used > 0) {
+    HIP_TRY(hipSetDevice(L->device));
+    HIP_TRY(hipEventSynchronize(L->ev_t1));
+    HIP_TRY(hipStreamSynchronize(L->copy_stream));
+    float ms = 0.f;
+    HIP_TRY(hipEventElapsedTime(&ms, L->ev_t0, L->ev_t1));
+    st.total_ms = ms;
+    st.copy_ms = st.gpu_ms = st.route_ms = 0.f;
+    for (const Seg& s : L->segs) {
+      float d = 0.f;
+      HIP_TRY(hipEventElapsedTime(&d, s.a, s.b));
+      if (s.kind == 0) { st.route_ms += d; st.gpu_ms += d; }
+      else if (s.kind == 1) st.gpu_ms += d;
+      else st.copy_ms += d;
+    }
+    float mx = std::max(st.copy_ms, std::max(st.gpu_ms, st.cc_ms));
+    st.overlap = st.total_ms > 0.f ? mx / st.total_ms : 0.f;
+  }
+  *out = st;
+  return SI_OK;
+}
+
+}  // extern "C"

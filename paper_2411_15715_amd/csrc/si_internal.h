@@ -1,0 +1,106 @@
+// Internal declarations shared by the translation units of libscheinfer (not part of the ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "scheinfer.h"
+#include "cc_worker.h"
+
+namespace si {
+
+// ---------------------------------------------------------------------------------------------
+// Weight storage.  One "chunk" holds SI_CHUNK_J = 64 consecutive hidden columns j of one expert:
+//   [ gate rows j0..j0+63 : 64 x M bf16 | up rows : 64 x M bf16 | down block : 8 x M x 8 bf16 ]
+// gate/up rows are contiguous in m (the contraction index of FC1); the down block stores, for each
+// group of 8 consecutive j and each m, the 8 values Wd[j0+8q+0..7][m] contiguously (16 bytes), so
+// that the contraction index of FC2 is contiguous too.  Both the decode GEMV (one 128-bit load per
+// lane) and the MFMA operand fetch (8 consecutive k per lane) read it without a transpose.
+// A part (CC, CG or GG) of an expert is a contiguous range of chunks, so a CG copy is one memcpy
+// and CG' is simply the CC chunk range of the same pinned buffer (Section III-B: same addresses).
+// ---------------------------------------------------------------------------------------------
+inline size_t chunk_elems(int M) { return (size_t)3 * CHUNK_J * M; }
+inline size_t chunk_bytes(int M) { return chunk_elems(M) * 2; }
+
+constexpr int MAX_EXPERTS = 256;      // routed experts (a shared expert adds one more table entry)
+constexpr int ROUTE_THREADS = 1024;   // block size of the assignment kernel
+constexpr int PREFILL_BM = 128;       // token rows per GEMM tile (row-tile table granularity)
+constexpr int DECODE_TB = 4;          // tokens handled per weight pass in the GEMV kernels
+constexpr int DOWN_SLOTS = 16;        // j-splits of the decode down projection per part
+
+// Device-side result of the token assignment plus the launch tables derived from it.
+// Expert tables have EX = E + (shared ? 1 : 0) entries; the shared expert is entry E and owns the
+// rows [T*k, T*k + T) (row T*k + t belongs to token t, weight 1).
+struct Plan {
+  int32_t* idx;        // [T*k]
+  float* w;            // [T*k]
+  int32_t* count;      // [EX]
+  int32_t* off;        // [EX+1]
+  int32_t* count1;     // [EX]  pairs of the expert that belong to X1 tokens (t < T - n_g)
+  int32_t* perm;       // [T*k]
+  int32_t* inv;        // [T*k]
+  int32_t* row_token;  // [T*k + T] token of each expert-sorted row
+  int32_t* touched;    // [EX] experts with count > 0, ascending
+  int32_t* n_touched;  // [1]
+  int32_t* tile_e;     // [max_tiles] expert of each row tile (all rows)
+  int32_t* tile_r;     // [max_tiles] index of the tile inside its expert
+  int32_t* n_tiles;    // [1]
+  int32_t* tile_e_x2;  // the same for the X2 rows only (CG')
+  int32_t* tile_r_x2;
+  int32_t* n_tiles_x2;  // [1]
+  int32_t n_routed;    // E: launches over "all experts" cover entries < n_routed only (the shared
+                       // expert's weights live in their own buffer and get their own launch)
+};
+
+// user-visible copies (first E entries), any pointer may be null
+struct RouteOut {
+  int32_t* idx; float* w; int32_t* count; int32_t* off; int32_t* perm; int32_t* inv;
+};
+
+// route.hip
+hipError_t launch_route(const float* logits, int T, int E, int k, int has_shared, int n_g, int bm,
+                        const Plan& plan, const RouteOut& user, hipStream_t stream);
+
+// Description of the weights one kernel launch works on.
+struct WeightView {
+  const uint16_t* base;   // chunk-major storage
+  size_t expert_stride;   // elements between experts (0 when `base` already points at the expert)
+  int chunk0;             // first chunk (relative to base / expert) to process
+  int n_chunks;           // number of chunks to process
+  int col0;               // hidden column (within the expert) of chunk0: indexes h / Hact columns
+};
+
+// decode.hip ---------------------------------------------------------------------------------
+// h[row][j] = SiLU(x_row . Wg[j]) * (x_row . Wu[j]) for the rows of the selected experts.
+//  expert_sel < 0: all touched experts (table lookup);  >= 0: only that expert.
+//  x2_only: restrict to rows of X2 tokens (CG').
+hipError_t launch_decode_gateup(const uint16_t* x, int M, const Plan& plan, int EX, int expert_sel, int x2_only,
+                                int max_touched, const WeightView& wv, float* h, int ldh, hipStream_t stream);
+// part[slot][row][m] = sum over the j of the slot of h[row][j] * Wd[j][m]
+hipError_t launch_decode_down(const float* h, int ldh, int M, const Plan& plan, int EX, int expert_sel, int x2_only,
+                              int max_touched, const WeightView& wv, int slot0, int chunks_per_slot,
+                              float* part, size_t slot_stride, hipStream_t stream);
+// y[t][m] = sum_s w[t][s] * sum_slots part[slot][inv[t*k+s]][m] + shared rows + ycc[t][m]
+struct DecodeCombineArgs {
+  const float* part; size_t slot_stride;
+  int n_slots_gg, n_slots_cg, n_slots_cc;   // valid slots per part (routed experts); slot ids: part*DOWN_SLOTS + s
+  int s_slots_gg, s_slots_cg, s_slots_cc;   // the same for the rows of the shared expert
+  const float* ycc;                         // [T1][M] or null
+  int T, k, M, n_x1, has_shared;
+};
+hipError_t launch_decode_combine(const DecodeCombineArgs& a, const Plan& plan, float* y, hipStream_t stream);
+
+// prefill.hip --------------------------------------------------------------------------------
+// Hact[row][c] (bf16) for c in [0, 64*n_chunks): SwiGLU of the gate/up products (MFMA, fp32 acc)
+hipError_t launch_prefill_gateup(const uint16_t* x, int M, const Plan& plan, int expert_sel, int x2_only,
+                                 int n_row_tiles, const WeightView& wv, uint16_t* hact, int ldh,
+                                 hipStream_t stream);
+// Yp[row][m] (fp32) (+)= Hact[row][:] . Wd[chunks][m]
+hipError_t launch_prefill_down(const uint16_t* hact, int ldh, int M, const Plan& plan, int expert_sel,
+                               int x2_only, int n_row_tiles, const WeightView& wv, float* yp, int accumulate,
+                               hipStream_t stream);
+// y[t][m] = sum_s w[t][s]*Yp[inv[t*k+s]][m] + Yp[T*k+t][m] (shared) + ycc[t][m] (X1 rows)
+hipError_t launch_prefill_combine(const float* yp, const float* ycc, int T, int k, int M, int n_x1,
+                                  int has_shared, const Plan& plan, float* y, hipStream_t stream);
+hipError_t launch_fill_zero(float* p, size_t n, hipStream_t stream);
+
+}  // namespace si
