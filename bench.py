@@ -1,0 +1,289 @@
+#!/usr/bin/env python3
+"""Benchmark of the partitioned FFN/MoE layer on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config mixtral_8x7b] [--split r_gg,r_cg,r_cc]
+
+A *step* is one pass of the whole hot path over one batch of synthetic input: one prompt-phase
+call (T = the config's prefill length) followed by ``--decode-calls`` generation-phase calls of
+the config's decode batch, each on different tokens (so that decode calls touch different experts
+and no weight byte is served from the 256 MB Infinity Cache).  Inputs are resident in HBM before
+the timed region.  The printed JSON line carries
+  value / ms_per_step   whole-step throughput at the config's own GG/CG/CC split
+  roofline              the dominant kernel (most GPU time in the step) against its roofline,
+                        kernel time from HIP events recorded by the library around every launch
+  gg_only               the same step with all weights resident (100/0/0), per-kernel rooflines
+  cpu_baseline          the CPU oracle timed on this machine's host cores on a bounded token sample
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0      # MI355X HBM3E
+MFMA_BF16_PEAK_TF = 2500.0  # dense bf16
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--config", default="mixtral_8x7b")
+    ap.add_argument("--split", default=None, help="r_gg,r_cg,r_cc (default: the config's)")
+    ap.add_argument("--decode-calls", type=int, default=16)
+    ap.add_argument("--n-g", type=int, default=-1, help="prefill tokens on CG' (default: all when r_cc > 0)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-gg-only", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="first run a plain elementwise copy of 1 GiB (reads 1 GiB, writes 1 GiB) three times: "
+                         "the reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE counters")
+    return ap.parse_args()
+
+
+class Workload:
+    """Device-resident inputs of one step and the per-call routing facts needed for byte counts."""
+
+    def __init__(self, cfg, n_decode, oracle_route=None):
+        import torch
+        import synth
+        self.cfg = cfg
+        dev = torch.device("cuda:0")
+        self.xp_bits = synth.make_tokens(cfg, cfg.t_prefill)
+        self.lp = synth.make_router_logits(cfg, self.xp_bits)
+        self.xp = torch.from_numpy(self.xp_bits.view(np.int16)).to(dev)
+        self.lp_dev = torch.from_numpy(self.lp).to(dev) if self.lp is not None else None
+        self.yp = torch.empty((cfg.t_prefill, cfg.d_model), dtype=torch.float32, device=dev)
+        self.dec = []
+        for i in range(n_decode):
+            xb = synth.make_tokens(cfg, cfg.t_decode, stream=100 + i)
+            lg = synth.make_router_logits(cfg, xb)
+            self.dec.append((torch.from_numpy(xb.view(np.int16)).to(dev),
+                             torch.from_numpy(lg).to(dev) if lg is not None else None, lg))
+        self.yd = torch.empty((cfg.t_decode, cfg.d_model), dtype=torch.float32, device=dev)
+
+    @staticmethod
+    def touched(cfg, logits):
+        """Number of routed experts with at least one token (host arithmetic on the inputs only)."""
+        if logits is None:
+            return 1
+        order = np.argsort(-logits, axis=1, kind="stable")[:, :cfg.top_k]
+        return len(np.unique(order))
+
+
+def run_steps(si, layer, wl, n_steps, n_g, stream, collect=None):
+    cfg = wl.cfg
+    for _ in range(n_steps):
+        si.si_layer_forward(layer, wl.xp.data_ptr(), wl.lp_dev.data_ptr() if wl.lp_dev is not None else None,
+                            cfg.t_prefill, n_g, si.SI_PREFILL, wl.yp.data_ptr(), stream=stream)
+        if collect is not None:
+            collect.append(("prefill", si.si_layer_stats(layer)))
+        for xd, ld, _ in wl.dec:
+            si.si_layer_forward(layer, xd.data_ptr(), ld.data_ptr() if ld is not None else None, cfg.t_decode, 0,
+                                si.SI_DECODE, wl.yd.data_ptr(), stream=stream)
+            if collect is not None:
+                collect.append(("decode", si.si_layer_stats(layer)))
+
+
+def measure(si, torch, cfg, w, split, wl, steps, warmup, n_g):
+    """Time `steps` steps (profiling off), then repeat them with per-launch events for kernel times."""
+    shared = tuple(w[k] for k in ("s_gate", "s_up", "s_down")) if cfg.d_ff_shared else None
+    layer = si.si_layer_create(cfg.d_model, cfg.d_ff, cfg.n_experts, cfg.top_k, w["w_gate"], w["w_up"], w["w_down"],
+                               split[0], split[1], split[2], max(cfg.t_prefill, cfg.t_decode),
+                               d_ff_shared=cfg.d_ff_shared, shared=shared)
+    try:
+        info = si.si_layer_split_info(layer)
+        stream = torch.cuda.current_stream().cuda_stream
+        run_steps(si, layer, wl, warmup, n_g, stream)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        run_steps(si, layer, wl, steps, n_g, stream)
+        torch.cuda.synchronize()
+        elapsed = time.perf_counter() - t0
+        # same region again with HIP events around every launch (stream-ordered, on the launch stream)
+        si.si_layer_set_profiling(layer, 1)
+        stats = []
+        run_steps(si, layer, wl, steps, n_g, stream, collect=stats)
+        torch.cuda.synchronize()
+        si.si_layer_set_profiling(layer, 0)
+    finally:
+        si.si_layer_destroy(layer)
+    return elapsed, stats, info
+
+
+def kernel_table(si, cfg, info, wl, stats, steps, n_g):
+    """Per kernel class: launches, mean duration, algorithmic bytes / flops per step, achieved rates.
+
+    Algorithmic work (weight bytes are read once per call, bf16):
+      decode gateup : touched experts x part columns x M x 2 matrices x 2 B
+      decode down   : touched experts x part columns x M x 2 B
+      prefill gateup: (token, expert) pairs x part columns x M x 4 flop ; weight bytes as above
+      prefill down  : pairs x part columns x M x 2 flop
+    Columns of the CC part count only when they run on the GPU (CG', the n_g tokens of X2)."""
+    M, H, Hs, k = cfg.d_model, cfg.d_ff, cfg.d_ff_shared, cfg.top_k
+    gpu_cols = info["n_gg"] + info["n_cg"]
+    gpu_cols_s = info["s_gg"] + info["s_cg"]
+    T = cfg.t_prefill
+    # decode: per call, touched experts
+    dec_bytes_gu = dec_bytes_dn = 0.0
+    for _, _, lg in wl.dec:
+        nt = Workload.touched(cfg, lg)
+        dec_bytes_gu += (nt * gpu_cols + gpu_cols_s) * M * 2 * 2
+        dec_bytes_dn += (nt * gpu_cols + gpu_cols_s) * M * 2
+    ntp = Workload.touched(cfg, wl.lp)
+    cc_cols_gpu = info["n_cc"] if n_g > 0 else 0
+    cc_cols_gpu_s = info["s_cc"] if n_g > 0 else 0
+    pre_w_gu = (ntp * (gpu_cols + cc_cols_gpu) + gpu_cols_s + cc_cols_gpu_s) * M * 2 * 2
+    pre_w_dn = pre_w_gu / 2
+    pairs = T * k
+    flop_gu = (pairs * gpu_cols + T * gpu_cols_s + n_g * k * info["n_cc"] + n_g * info["s_cc"]) * M * 4.0
+    flop_dn = flop_gu / 2
+    work = {"decode_gateup": ("hbm", dec_bytes_gu, 0.0), "decode_down": ("hbm", dec_bytes_dn, 0.0),
+            "prefill_gateup": ("mfma", pre_w_gu, flop_gu), "prefill_down": ("mfma", pre_w_dn, flop_dn)}
+    ms = np.zeros(8)
+    launches = np.zeros(8, dtype=np.int64)
+    for _, st in stats:
+        ms += np.array(st["kernel_ms"])
+        launches += np.array(st["kernel_launches"])
+    out = {}
+    for i, name in enumerate(si.SI_K_NAMES):
+        if launches[i] == 0:
+            continue
+        ent = {"launches_per_step": float(launches[i]) / steps, "ms_per_step": float(ms[i]) / steps,
+               "avg_launch_us": 1e3 * float(ms[i]) / float(launches[i])}
+        if name in work:
+            bound, nbytes, nflop = work[name]
+            sec = ms[i] / steps / 1e3
+            ent["bytes_per_step"] = nbytes
+            ent["GBps"] = nbytes / sec / 1e9
+            if nflop:
+                ent["flop_per_step"] = nflop
+                ent["TFLOPs"] = nflop / sec / 1e12
+                # a GEMM whose arithmetic intensity is below the machine balance is bandwidth bound
+                ai = nflop / nbytes
+                bound = "mfma" if ai >= MFMA_BF16_PEAK_TF * 1e12 / (HBM_PEAK_GBS * 1e9) else "hbm"
+            ent["bound"] = bound
+        out[name] = ent
+    return out
+
+
+def roofline_of(name, ent, traffic=None):
+    if ent["bound"] == "hbm":
+        a, p, unit = ent["GBps"], HBM_PEAK_GBS, "GB/s"
+    else:
+        a, p, unit = ent["TFLOPs"], MFMA_BF16_PEAK_TF, "TFLOP/s"
+    return {"kernel": name, "bound": ent["bound"], "achieved": round(a, 2), "peak": p, "unit": unit,
+            "frac": round(a / p, 4), "traffic": traffic, "avg_launch_us": round(ent["avg_launch_us"], 2),
+            "launches_per_step": ent["launches_per_step"]}
+
+
+def cpu_baseline(cfg, w, wl, seconds):
+    """The oracle, as it stands, on a bounded sample of the step's tokens (prefill tokens, all routed)."""
+    import oracle
+    shared = tuple(w[k] for k in ("s_gate", "s_up", "s_down")) if cfg.d_ff_shared else None
+    threads = oracle.get_threads()
+
+    def run(n):
+        sel = np.linspace(0, cfg.t_prefill - 1, n).astype(np.int32)
+        t0 = time.perf_counter()
+        oracle.layer_forward(wl.xp_bits, w["w_gate"], w["w_up"], w["w_down"], logits=wl.lp, top_k=cfg.top_k,
+                             shared=shared, sel=sel)
+        return time.perf_counter() - t0
+
+    t1 = run(2)
+    n = int(max(2, min(cfg.t_prefill, seconds / max(t1 / 2, 1e-6))))
+    t = run(n)
+    return {"value": round(n / t, 3), "unit": "tokens/s", "cores": threads, "kind": "oracle",
+            "sample": "%d of the %d prefill tokens of the step (routing for all tokens, full fp64 layer output for "
+                      "the sampled ones), %.1f s" % (n, cfg.t_prefill, t)}
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus %d is not supported. "
+              "The printed value is one GPU's throughput." % args.gpus, file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import synth
+    import paper_2411_15715_amd as si
+    si.lib()  # fail loudly if the HIP library is not built
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.add(src, 0.0, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
+    cfg = synth.CONFIGS[args.config]
+    split = tuple(float(v) for v in args.split.split(",")) if args.split else cfg.split
+    n_g = args.n_g if args.n_g >= 0 else (cfg.t_prefill if split[2] > 0 else 0)
+    t0 = time.perf_counter()
+    w = synth.make_weights(cfg, threads=min(16, os.cpu_count() or 8))
+    wl = Workload(cfg, args.decode_calls)
+    t_gen = time.perf_counter() - t0
+    tokens_per_step = cfg.t_prefill + args.decode_calls * cfg.t_decode
+
+    elapsed, stats, info = measure(si, torch, cfg, w, split, wl, args.steps, args.warmup, n_g)
+    ms_per_step = 1e3 * elapsed / args.steps
+    ktab = kernel_table(si, cfg, info, wl, stats, args.steps, n_g)
+    weight_kernels = [k for k in ktab if "bound" in ktab[k]]
+    dominant = max(weight_kernels, key=lambda k: ktab[k]["ms_per_step"])
+    pre = [st for kind, st in stats if kind == "prefill"]
+    dec = [st for kind, st in stats if kind == "decode"]
+    phase = {
+        "prefill_ms": float(np.mean([s["total_ms"] for s in pre])), "decode_ms": float(np.mean([s["total_ms"] for s in dec])),
+        "prefill_tokens_per_s": cfg.t_prefill / (np.mean([s["total_ms"] for s in pre]) / 1e3),
+        "decode_tokens_per_s": cfg.t_decode / (np.mean([s["total_ms"] for s in dec]) / 1e3),
+    }
+    link = None
+    copied = sum(s["bytes_streamed"] for _, s in stats)
+    copy_ms = sum(s["copy_ms"] for _, s in stats)
+    if copied > 0:
+        link = {"GBps": round(copied / (copy_ms / 1e3) / 1e9, 2), "bytes_per_step": copied / args.steps,
+                "copy_ms_per_step": copy_ms / args.steps,
+                "overlap_prefill": float(np.mean([s["overlap"] for s in pre])),
+                "overlap_decode": float(np.mean([s["overlap"] for s in dec])),
+                "cc_ms_per_step": sum(s["cc_ms"] for _, s in stats) / args.steps}
+
+    out = {
+        "metric": "FFN/MoE layer tokens/s (decode+prefill)", "value": round(tokens_per_step / (ms_per_step / 1e3), 2),
+        "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "%s-shaped layer: E=%d top-%d M=%d H=%d%s, step = 1 prefill call of %d tokens + %d decode "
+                               "calls of %d token(s)" % (cfg.name, cfg.n_experts, cfg.top_k, cfg.d_model, cfg.d_ff,
+                                                         (" + shared H=%d" % cfg.d_ff_shared) if cfg.d_ff_shared else "",
+                                                         cfg.t_prefill, args.decode_calls, cfg.t_decode),
+                   "split_gg_cg_cc": list(split), "columns": info, "n_g": n_g, "tokens_per_step": tokens_per_step},
+        "roofline": roofline_of(dominant, ktab[dominant]),
+        "phases": {k: round(v, 4) for k, v in phase.items()},
+        "kernels": {k: {kk: (round(vv, 4) if isinstance(vv, float) else vv) for kk, vv in v.items()} for k, v in ktab.items()},
+        "host_link": link,
+        "input_generation_s": round(t_gen, 1),
+    }
+    if not args.no_gg_only and tuple(split) != (1.0, 0.0, 0.0):
+        e2, stats2, info2 = measure(si, torch, cfg, w, (1.0, 0.0, 0.0), wl, args.steps, args.warmup, 0)
+        k2 = kernel_table(si, cfg, info2, wl, stats2, args.steps, 0)
+        pre2 = [st for kind, st in stats2 if kind == "prefill"]
+        dec2 = [st for kind, st in stats2 if kind == "decode"]
+        out["gg_only"] = {
+            "split_gg_cg_cc": [1.0, 0.0, 0.0], "ms_per_step": round(1e3 * e2 / args.steps, 4),
+            "tokens_per_s": round(tokens_per_step / (e2 / args.steps), 2),
+            "prefill_ms": round(float(np.mean([s["total_ms"] for s in pre2])), 4),
+            "decode_ms": round(float(np.mean([s["total_ms"] for s in dec2])), 4),
+            "rooflines": [roofline_of(k, k2[k]) for k in k2 if "bound" in k2[k]],
+        }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, w, wl, args.cpu_seconds)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -87,6 +87,16 @@ typedef struct {
  * clock) and the bytes it moved.  overlap = max(copy_ms, gpu_ms, cc_ms) / total_ms: 1.0 means the
  * layer took as long as its slowest resource, the objective t_fin = max(tau_G, tau_C) of Section
  * IV-A.2. */
+#define SI_K_ROUTE 0           /* token-assignment kernels */
+#define SI_K_DECODE_GATEUP 1   /* GEMV FC1 + SwiGLU */
+#define SI_K_DECODE_DOWN 2     /* GEMV FC2 */
+#define SI_K_DECODE_COMBINE 3
+#define SI_K_PREFILL_GATEUP 4  /* MFMA FC1 + SwiGLU */
+#define SI_K_PREFILL_DOWN 5    /* MFMA FC2 */
+#define SI_K_PREFILL_COMBINE 6
+#define SI_K_FILL 7
+#define SI_K_COUNT 8
+
 typedef struct {
   float total_ms;     /* first enqueue to last kernel, on the caller's stream */
   float copy_ms;      /* busy time of the host->device weight copies (Stream-C) */
@@ -100,6 +110,8 @@ typedef struct {
   int32_t n_copies;   /* number of staged pieces */
   int32_t n_touched;  /* experts with at least one token (-1 if not known on the host) */
   int32_t path;       /* SI_DECODE or SI_PREFILL actually taken */
+  float kernel_ms[SI_K_COUNT];         /* summed HIP-event time of each kernel class (SI_K_*) */
+  int32_t kernel_launches[SI_K_COUNT]; /* launches of each class */
 } si_stats_t;
 
 /*

@@ -38,7 +38,12 @@ class si_stats_t(ctypes.Structure):
     _fields_ = [("total_ms", ctypes.c_float), ("copy_ms", ctypes.c_float), ("gpu_ms", ctypes.c_float),
                 ("cc_ms", ctypes.c_float), ("route_ms", ctypes.c_float), ("bytes_streamed", ctypes.c_double),
                 ("bytes_gg", ctypes.c_double), ("bytes_cc", ctypes.c_double), ("overlap", ctypes.c_float),
-                ("n_copies", ctypes.c_int32), ("n_touched", ctypes.c_int32), ("path", ctypes.c_int32)]
+                ("n_copies", ctypes.c_int32), ("n_touched", ctypes.c_int32), ("path", ctypes.c_int32),
+                ("kernel_ms", ctypes.c_float * 8), ("kernel_launches", ctypes.c_int32 * 8)]
+
+
+SI_K_NAMES = ["route", "decode_gateup", "decode_down", "decode_combine", "prefill_gateup", "prefill_down",
+              "prefill_combine", "fill"]
 
 
 class ScheInferError(RuntimeError):
@@ -155,7 +160,10 @@ def si_layer_set_profiling(layer, on):
 def si_layer_stats(layer) -> dict:
     st = si_stats_t()
     _check(lib().si_layer_stats(layer, ctypes.byref(st)))
-    return {name: getattr(st, name) for name, _ in si_stats_t._fields_}
+    d = {name: getattr(st, name) for name, _ in si_stats_t._fields_}
+    d["kernel_ms"] = list(st.kernel_ms)
+    d["kernel_launches"] = list(st.kernel_launches)
+    return d
 
 
 def si_repack_chunks(w_gate, w_up, w_down, chunk0, n_chunks):

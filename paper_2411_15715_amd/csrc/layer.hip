@@ -43,7 +43,8 @@ int fail(int code, const char* fmt, ...) {
     if (_e != hipSuccess) return fail(SI_EHIP, "%s failed: %s", #expr, hipGetErrorString(_e));  \
   } while (0)
 
-struct Seg { hipEvent_t a, b; int kind; };  // kind: 0 route, 1 gpu compute, 2 copy
+struct Seg { hipEvent_t a, b; int kind; };  // kind: SI_K_* kernel class, or SEG_COPY
+constexpr int SEG_COPY = SI_K_COUNT;
 
 int split_counts(int H, int g, float r_gg, float r_cg, int* n_gg, int* n_cg, int* n_cc) {
   if (H <= 0 || g <= 0 || H % g != 0) return -1;
@@ -548,7 +549,11 @@ int si_layer_forward(si_layer_t* L, const void* x_dev, const float* logits_dev, 
     if (path == SI_DECODE) {
       wv.col0 = col_base;
       const int cps = is_shared ? (part == 0 ? scps_gg : part == 1 ? scps_cg : scps_cc) : (part == 0 ? cps_gg : part == 1 ? cps_cg : cps_cc);
-      K_TRY(launch_decode_gateup(x, M, L->plan, EX, esel, x2_only, max_touched, wv, L->d_h, L->ldh_dec, stream));
+      {
+        SegScope sc(L, stream, SI_K_DECODE_GATEUP);
+        K_TRY(launch_decode_gateup(x, M, L->plan, EX, esel, x2_only, max_touched, wv, L->d_h, L->ldh_dec, stream));
+      }
+      SegScope sc(L, stream, SI_K_DECODE_DOWN);
       K_TRY(launch_decode_down(L->d_h, L->ldh_dec, M, L->plan, EX, esel, x2_only, max_touched, wv,
                                part * DOWN_SLOTS + part_chunk0 / cps, cps, L->d_part, slot_stride, stream));
     } else {
@@ -556,7 +561,11 @@ int si_layer_forward(si_layer_t* L, const void* x_dev, const float* logits_dev, 
       if (esel >= 0) n_rt = ceil_div(x2_only ? rows_x2(esel) : rows_all(esel), PREFILL_BM);
       else n_rt = tiles_upper;
       const int ldh = n * CHUNK_J;
-      K_TRY(launch_prefill_gateup(x, M, L->plan, esel, x2_only, n_rt, wv, L->d_hact, ldh, stream));
+      {
+        SegScope sc(L, stream, SI_K_PREFILL_GATEUP);
+        K_TRY(launch_prefill_gateup(x, M, L->plan, esel, x2_only, n_rt, wv, L->d_hact, ldh, stream));
+      }
+      SegScope sc(L, stream, SI_K_PREFILL_DOWN);
       K_TRY(launch_prefill_down(L->d_hact, ldh, M, L->plan, esel, x2_only, n_rt, wv, L->d_yp, first_for_rows ? 0 : 1, stream));
     }
     return SI_OK;
@@ -566,9 +575,9 @@ int si_layer_forward(si_layer_t* L, const void* x_dev, const float* logits_dev, 
   // In the prefill path the GG launch overwrites the per-row outputs and every staged piece adds to
   // them; rows without a GG part start from zero.
   {
-    SegScope sc(L, stream, 1);
     int rc;
     if (path == SI_PREFILL) {
+      SegScope sc(L, stream, SI_K_FILL);
       if (L->ch_gg == 0) K_TRY(launch_fill_zero(L->d_yp, (size_t)T * k * M, stream));
       if (L->has_shared && L->sch_gg == 0) K_TRY(launch_fill_zero(L->d_yp + (size_t)T * k * M, (size_t)T * M, stream));
     }
@@ -605,13 +614,12 @@ int si_layer_forward(si_layer_t* L, const void* x_dev, const float* logits_dev, 
           const int slot = (int)(L->piece_counter++ % L->n_stage);
           if (L->slot_used[slot]) HIP_TRY(hipStreamWaitEvent(L->copy_stream, L->ev_free[slot], 0));
           {
-            SegScope sc(L, L->copy_stream, 2);
+            SegScope sc(L, L->copy_stream, SEG_COPY);
             HIP_TRY(hipMemcpyAsync(L->d_stage[slot], hbase + (size_t)(pc0 + c) * ce, (size_t)n * ce * 2, hipMemcpyHostToDevice, L->copy_stream));
           }
           HIP_TRY(hipEventRecord(L->ev_ready[slot], L->copy_stream));
           HIP_TRY(hipStreamWaitEvent(stream, L->ev_ready[slot], 0));
           {
-            SegScope sc(L, stream, 1);
             int rc = run_part(L->d_stage[slot], 0, sh ? 0 : e, sh, 0, n, (pc0 + c) * CHUNK_J, part, c, x2_only, false);
             if (rc) return rc;
           }
@@ -640,7 +648,7 @@ int si_layer_forward(si_layer_t* L, const void* x_dev, const float* logits_dev, 
 
   // ---- merge: Y = Y^CC (or Y^CG') + Y^CG + Y^GG (Eq. 2) and the weighted sum over experts
   {
-    SegScope sc(L, stream, 1);
+    SegScope sc(L, stream, path == SI_DECODE ? SI_K_DECODE_COMBINE : SI_K_PREFILL_COMBINE);
     if (path == SI_DECODE) {
       DecodeCombineArgs a{};
       a.part = L->d_part; a.slot_stride = slot_stride;
@@ -669,12 +677,15 @@ int si_layer_stats(si_layer_t* L, si_stats_t* out) {
     HIP_TRY(hipEventElapsedTime(&ms, L->ev_t0, L->ev_t1));
     st.total_ms = ms;
     st.copy_ms = st.gpu_ms = st.route_ms = 0.f;
+    for (int i = 0; i < SI_K_COUNT; ++i) { st.kernel_ms[i] = 0.f; st.kernel_launches[i] = 0; }
     for (const Seg& s : L->segs) {
       float d = 0.f;
       HIP_TRY(hipEventElapsedTime(&d, s.a, s.b));
-      if (s.kind == 0) { st.route_ms += d; st.gpu_ms += d; }
-      else if (s.kind == 1) st.gpu_ms += d;
-      else st.copy_ms += d;
+      if (s.kind == SEG_COPY) { st.copy_ms += d; continue; }
+      st.gpu_ms += d;
+      st.kernel_ms[s.kind] += d;
+      st.kernel_launches[s.kind] += 1;
+      if (s.kind == SI_K_ROUTE) st.route_ms += d;
     }
     float mx = std::max(st.copy_ms, std::max(st.gpu_ms, st.cc_ms));
     st.overlap = st.total_ms > 0.f ? mx / st.total_ms : 0.f;
