@@ -121,7 +121,8 @@ struct si_layer {
   float* d_part = nullptr;    // decode partials [3*DOWN_SLOTS][rows_dec][M]
   uint16_t* d_hact = nullptr; // prefill activations
   size_t hact_elems = 0;
-  float* d_yp = nullptr;      // prefill per-row outputs [max_T*(k+shared)][M]
+  float* d_yp = nullptr;      // prefill per-row outputs [MAX_KSPLIT][max_T*(k+shared)][M]
+  size_t yp_slab = 0;         // elements per slab
   float* d_ycc = nullptr;     // [max_T][M]
   // pinned host mirrors
   uint16_t* hx = nullptr;
@@ -394,7 +395,8 @@ int si_layer_create(const si_layer_desc_t* desc, const uint16_t* w_gate, const u
     int cols = std::max({L->n_gg, L->s_gg, any_host ? L->stage_chunks * CHUNK_J : 0});
     L->hact_elems = n_rows * (size_t)cols;
     if (T > SI_DECODE_AUTO_T || true) TRY_OR_DESTROY(dev_alloc(&L->d_hact, L->hact_elems));
-    TRY_OR_DESTROY(dev_alloc(&L->d_yp, n_rows * (size_t)M));
+    L->yp_slab = n_rows * (size_t)M;
+    TRY_OR_DESTROY(dev_alloc(&L->d_yp, (size_t)MAX_KSPLIT * L->yp_slab));
   }
   TRY_OR_DESTROY(dev_alloc(&L->d_ycc, (size_t)T * M));
   TRY_OR_DESTROY(pin_alloc(&L->hx, (size_t)T * M));
@@ -535,6 +537,9 @@ int si_layer_forward(si_layer_t* L, const void* x_dev, const float* logits_dev, 
   const int scps_gg = std::max(1, ceil_div(L->sch_gg, DOWN_SLOTS)), scps_cg = std::max(1, ceil_div(L->sch_cg, DOWN_SLOTS)),
             scps_cc = std::max(1, ceil_div(L->sch_cc, DOWN_SLOTS));
   const size_t slot_stride = (size_t)L->rows_dec * M;
+  // k-splits of the prefill down projection: enough blocks to fill 256 CUs when there are few row tiles
+  const int n_ntiles = ceil_div(M, 256);
+  const int split_call = std::min(MAX_KSPLIT, std::max(1, 256 / (std::max(1, ceil_div(T * k, PREFILL_BM)) * n_ntiles)));
   hipError_t ke = hipSuccess;
 #define K_TRY(expr) do { ke = (expr); if (ke != hipSuccess) return fail(SI_EHIP, "%s failed: %s", #expr, hipGetErrorString(ke)); } while (0)
 
@@ -566,7 +571,9 @@ int si_layer_forward(si_layer_t* L, const void* x_dev, const float* logits_dev, 
         K_TRY(launch_prefill_gateup(x, M, L->plan, esel, x2_only, n_rt, wv, L->d_hact, ldh, stream));
       }
       SegScope sc(L, stream, SI_K_PREFILL_DOWN);
-      K_TRY(launch_prefill_down(L->d_hact, ldh, M, L->plan, esel, x2_only, n_rt, wv, L->d_yp, first_for_rows ? 0 : 1, stream));
+      const int split = first_for_rows ? split_call : std::min(split_call, std::max(1, n / 8));
+      K_TRY(launch_prefill_down(L->d_hact, ldh, M, L->plan, esel, x2_only, n_rt, wv, L->d_yp, L->yp_slab, split,
+                                first_for_rows ? 0 : 1, stream));
     }
     return SI_OK;
   };
@@ -578,8 +585,10 @@ int si_layer_forward(si_layer_t* L, const void* x_dev, const float* logits_dev, 
     int rc;
     if (path == SI_PREFILL) {
       SegScope sc(L, stream, SI_K_FILL);
-      if (L->ch_gg == 0) K_TRY(launch_fill_zero(L->d_yp, (size_t)T * k * M, stream));
-      if (L->has_shared && L->sch_gg == 0) K_TRY(launch_fill_zero(L->d_yp + (size_t)T * k * M, (size_t)T * M, stream));
+      for (int q = 0; q < split_call; ++q) {
+        if (L->ch_gg == 0) K_TRY(launch_fill_zero(L->d_yp + q * L->yp_slab, (size_t)T * k * M, stream));
+        if (L->has_shared && L->sch_gg == 0) K_TRY(launch_fill_zero(L->d_yp + q * L->yp_slab + (size_t)T * k * M, (size_t)T * M, stream));
+      }
     }
     if (E == 1) rc = run_part(L->d_gg, 0, 0, 0, 0, L->ch_gg, hch * CHUNK_J, 0, 0, 0, true);
     else rc = run_part(L->d_gg, (size_t)L->ch_gg * ce, -1, 0, 0, L->ch_gg, hch * CHUNK_J, 0, 0, 0, true);
@@ -657,7 +666,7 @@ int si_layer_forward(si_layer_t* L, const void* x_dev, const float* logits_dev, 
       a.ycc = ycc_dev; a.T = T; a.k = k; a.M = M; a.n_x1 = n_x1; a.has_shared = L->has_shared;
       K_TRY(launch_decode_combine(a, L->plan, y_dev, stream));
     } else {
-      K_TRY(launch_prefill_combine(L->d_yp, ycc_dev, T, k, M, n_x1, L->has_shared, L->plan, y_dev, stream));
+      K_TRY(launch_prefill_combine(L->d_yp, L->yp_slab, split_call, ycc_dev, T, k, M, n_x1, L->has_shared, L->plan, y_dev, stream));
     }
   }
   if (L->profiling) HIP_TRY(hipEventRecord(L->ev_t1, stream));

@@ -5,9 +5,13 @@
 // Rows are the expert-sorted (token, slot) pairs of the token assignment; a row tile never
 // crosses an expert.  The gather of x rows is fused into the A-operand load of the first GEMM.
 //
-// LDS tiles hold 64 contraction elements (128 bytes) per row; the 16-byte piece c of row r sits
-// at piece (c ^ (r & 7)) so that both the 128-bit stores (8 lanes per row) and the 128-bit MFMA
-// operand loads (32 rows x 2 pieces per wave) are bank-conflict free.
+// Both GEMMs: one 512-thread block (8 waves, 2 per SIMD) per 256 x 256 output tile, BK = 64,
+// two LDS stages of 64 KB filled by direct global->LDS loads (global_load_lds_dwordx4, no VGPR
+// staging), wave tile 128 x 64 (8 MFMA 32x32x16 per k-step, 128 accumulator registers).
+// LDS rows hold 64 contraction elements (128 bytes); the 16-byte piece c of row r sits at piece
+// c ^ ((r >> 1) & 7): gfx950's LDS has 64 banks, so 16 consecutive rows x 16 bytes must cover 256
+// distinct bytes of bank space for the 128-bit MFMA operand reads to be conflict free (measured:
+// SQ_LDS_BANK_CONFLICT = 0).
 #include "si_internal.h"
 
 namespace si {
@@ -16,12 +20,16 @@ namespace {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+#define SI_GPTR(p) ((const void __attribute__((address_space(1)))*)(p))
+#define SI_LPTR(p) ((void __attribute__((address_space(3)))*)(p))
 
 constexpr int WAVE = 64;
-constexpr int THREADS = 256;
-constexpr int BM = PREFILL_BM;  // 128 rows
+constexpr int THREADS = 512;
+constexpr int BM = PREFILL_BM;  // 256 rows
+constexpr int BN = 256;         // B rows per tile: 128 hidden columns (gate+up) or 256 output columns
 constexpr int BK = 64;
-constexpr int BN2 = 128;        // output columns (m) per block in the down projection
+constexpr int STAGE_BYTES = (BM + BN) * BK * 2;  // 64 KB
+constexpr int LDS_BYTES = 2 * STAGE_BYTES;       // 128 KB
 
 __device__ inline uint16_t f32_to_bf16(float f) {
   uint32_t u = __float_as_uint(f);
@@ -34,7 +42,7 @@ __device__ inline float silu_f(float z) { return z / (1.f + __expf(-z)); }
 __device__ inline bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 
 // swizzled byte offset of 16-byte piece c of row r in a [rows][64] bf16 tile
-__device__ inline int swz(int r, int c) { return r * 128 + ((c ^ (r & 7)) << 4); }
+__device__ inline int swz(int r, int c) { return r * 128 + ((c ^ ((r >> 1) & 7)) << 4); }
 
 // XCD-aware remap: consecutive hardware block ids go round-robin over the 8 XCDs; give each XCD a
 // contiguous range of logical ids so that blocks sharing weights share an L2.
@@ -78,196 +86,234 @@ __device__ inline bool decode_tile(const Plan& p, int expert_sel, int x2_only, i
 }
 
 // ---------------------------------------------------------------------------------------------
-// FC1 + SwiGLU.  Block: 128 rows x 64 hidden columns (one chunk: 64 gate rows + 64 up rows).
-// 4 waves as 2 (rows) x 2 (columns): each wave 64 rows x 32 columns of gate and of up.
+// FC1 + SwiGLU.  Tile: 256 rows x 128 hidden columns (two chunks).  B rows in LDS are ordered so
+// that wave column wc owns hidden columns [32 wc, 32 wc + 32): LDS B row = wc*64 + f*32 + jj with
+// f = 0 the gate row and f = 1 the up row of column 32 wc + jj; SiLU(gate)*up is then formed in
+// registers from the two accumulator tiles of a wave.
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(THREADS) void k_prefill_gateup(const uint16_t* __restrict__ x, int M, Plan p,
-                                                            int expert_sel, int x2_only, int total_blocks,
-                                                            WeightView wv, uint16_t* __restrict__ hact, int ldh) {
-  __shared__ __attribute__((aligned(16))) unsigned char s_a[BM * 128];
-  __shared__ __attribute__((aligned(16))) unsigned char s_g[CHUNK_J * 128];
-  __shared__ __attribute__((aligned(16))) unsigned char s_u[CHUNK_J * 128];
+__global__ __launch_bounds__(THREADS, 1) void k_prefill_gateup(const uint16_t* __restrict__ x, int M, Plan p,
+                                                               int expert_sel, int x2_only, int total_blocks,
+                                                               int n_ctiles, WeightView wv,
+                                                               uint16_t* __restrict__ hact, int ldh) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
   const int L = xcd_remap(blockIdx.x, total_blocks);
-  int cidx;
+  int tc;
   TileInfo ti;
-  if (!decode_tile(p, expert_sel, x2_only, L, wv.n_chunks, cidx, ti)) return;
-  const int tid = threadIdx.x, lane = tid % WAVE, wid = tid / WAVE;
-  const int wr = wid >> 1, wc = wid & 1;
-  const uint16_t* cbase = wv.base + (size_t)ti.e * wv.expert_stride + (size_t)(wv.chunk0 + cidx) * 3 * CHUNK_J * M;
-
-  // global -> register staging: piece c = tid % 8 of rows tid/8 + 32*i
-  const int lc = tid & 7, lr = tid >> 3;
-  const uint16_t* a_src[4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    int row = ti.row0 + lr + 32 * i;
-    row = row < ti.row_end ? row : ti.row_end - 1;
-    a_src[i] = x + (size_t)p.row_token[row] * M + lc * 8;
-  }
-  const uint16_t* g_src = cbase + (size_t)lr * M + lc * 8;
-  const uint16_t* u_src = cbase + (size_t)(CHUNK_J + lr) * M + lc * 8;
-
-  f32x16 accg[2], accu[2];
-#pragma unroll
-  for (int i = 0; i < 2; ++i)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) { accg[i][r] = 0.f; accu[i][r] = 0.f; }
-
-  u32x4 ra[4], rg[2], ru[2];
-  auto load_tiles = [&](int k0) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) ra[i] = *reinterpret_cast<const u32x4*>(a_src[i] + k0);
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      rg[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(g_src + (size_t)32 * i * M + k0));
-      ru[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(u_src + (size_t)32 * i * M + k0));
-    }
-  };
-  load_tiles(0);
-  for (int k0 = 0; k0 < M; k0 += BK) {
-    __syncthreads();
-#pragma unroll
-    for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x4*>(s_a + swz(lr + 32 * i, lc)) = ra[i];
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      *reinterpret_cast<u32x4*>(s_g + swz(lr + 32 * i, lc)) = rg[i];
-      *reinterpret_cast<u32x4*>(s_u + swz(lr + 32 * i, lc)) = ru[i];
-    }
-    __syncthreads();
-    if (k0 + BK < M) load_tiles(k0 + BK);
-#pragma unroll
-    for (int ks = 0; ks < BK / 16; ++ks) {
-      const int pc = ks * 2 + (lane >> 5);
-      bf16x8 fa[2], fg, fu;
-#pragma unroll
-      for (int i = 0; i < 2; ++i)
-        fa[i] = as_bf16x8(*reinterpret_cast<const u32x4*>(s_a + swz(wr * 64 + i * 32 + (lane & 31), pc)));
-      fg = as_bf16x8(*reinterpret_cast<const u32x4*>(s_g + swz(wc * 32 + (lane & 31), pc)));
-      fu = as_bf16x8(*reinterpret_cast<const u32x4*>(s_u + swz(wc * 32 + (lane & 31), pc)));
-#pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        accg[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fg, accg[i], 0, 0, 0);
-        accu[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fu, accu[i], 0, 0, 0);
-      }
-    }
-  }
-  // epilogue: element (row 8*(r/4) + 4*(lane/32) + r%4, column lane%32) of each 32x32 tile
-  const int col = cidx * CHUNK_J + wv.col0 + wc * 32 + (lane & 31);
-#pragma unroll
-  for (int i = 0; i < 2; ++i)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const int row = ti.row0 + wr * 64 + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-      if (row < ti.row_end) hact[(size_t)row * ldh + col] = f32_to_bf16(silu_f(accg[i][r]) * accu[i][r]);
-    }
-}
-
-// ---------------------------------------------------------------------------------------------
-// FC2.  Block: 128 rows x 128 output columns m; contraction over the hidden columns of the launch
-// (one chunk = 64 per step).  4 waves as 2 x 2, each 64 x 64.
-// B operand: the down block of a chunk is [8 groups][M][8 j], i.e. already "8 consecutive k per
-// (group, m)"; the tile is kept in that order in LDS ([group][128 m] x 16 bytes).
-// ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(THREADS) void k_prefill_down(const uint16_t* __restrict__ hact, int ldh, int M, Plan p,
-                                                          int expert_sel, int x2_only, int total_blocks, int n_ntiles,
-                                                          WeightView wv, float* __restrict__ yp, int accumulate) {
-  __shared__ __attribute__((aligned(16))) unsigned char s_a[BM * 128];
-  __shared__ __attribute__((aligned(16))) unsigned char s_b[8 * BN2 * 16];
-  const int L = xcd_remap(blockIdx.x, total_blocks);
-  int nt;
-  TileInfo ti;
-  if (!decode_tile(p, expert_sel, x2_only, L, n_ntiles, nt, ti)) return;
-  const int tid = threadIdx.x, lane = tid % WAVE, wid = tid / WAVE;
-  const int wr = wid >> 1, wc = wid & 1;
-  const int n0 = nt * BN2;
+  if (!decode_tile(p, expert_sel, x2_only, L, n_ctiles, tc, ti)) return;
+  const int tid = threadIdx.x, lane = tid % WAVE, w = tid / WAVE;
+  const int wr = w >> 2, wc = w & 3;
   const uint16_t* ebase = wv.base + (size_t)ti.e * wv.expert_stride;
 
-  const int lc = tid & 7, lr = tid >> 3;
+  // loader: wave w fills LDS rows w*32 + i*8 + lane/8 (i < 4) of A and of B; lane%8 is the slot
+  // inside the 128-byte row, holding logical piece slot ^ ((row >> 1) & 7)
+  const int lrow = lane >> 3, lpp = lane & 7;
+  const int lc0 = lpp ^ (lrow >> 1);  // even i; odd i uses lc0 ^ 4
   const uint16_t* a_src[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    int row = ti.row0 + lr + 32 * i;
+    int row = ti.row0 + w * 32 + i * 8 + lrow;
     row = row < ti.row_end ? row : ti.row_end - 1;
-    a_src[i] = hact + (size_t)row * ldh + wv.col0 + lc * 8;
+    a_src[i] = x + (size_t)p.row_token[row] * M + (((i & 1) ? (lc0 ^ 4) : lc0) * 8);
   }
-  // B staging: 8 groups x 128 m pieces of 16 bytes; thread handles m = tid % 128, groups tid/128 + 2*i
-  const int bn = tid & 127, bg = tid >> 7;
-  const int bm_src = min(n0 + bn, M - 1);
+  // B: LDS row w*32 + i*8 + lrow  ->  chunk 2*tc + w/4, f = w%2, column-in-chunk ((w/2)%2)*32 + i*8 + lrow
+  const int chunk_rel = min(2 * tc + (w >> 2), wv.n_chunks - 1);
+  const uint16_t* b_src = ebase + (size_t)(wv.chunk0 + chunk_rel) * 3 * CHUNK_J * M +
+                          (size_t)((w & 1) * CHUNK_J + ((w >> 1) & 1) * 32 + lrow) * M;
 
-  f32x16 acc[2][2];
+  f32x16 acc[4][2];
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < 4; ++i)
 #pragma unroll
     for (int j = 0; j < 2; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  u32x4 ra[4], rb[4];
-  auto load_tiles = [&](int c) {
-    const uint16_t* dblk = ebase + (size_t)(wv.chunk0 + c) * 3 * CHUNK_J * M + (size_t)2 * CHUNK_J * M;
+  auto issue = [&](int stage, int k0) {
+    unsigned char* sa = lds + stage * STAGE_BYTES + w * 4096;
+    unsigned char* sb = sa + BM * 128;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) ra[i] = *reinterpret_cast<const u32x4*>(a_src[i] + c * CHUNK_J);
+    for (int i = 0; i < 4; ++i) {
+      __builtin_amdgcn_global_load_lds(SI_GPTR(a_src[i] + k0), SI_LPTR(sa + i * 1024), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds(SI_GPTR(b_src + (size_t)i * 8 * M + k0 + (((i & 1) ? (lc0 ^ 4) : lc0) * 8)),
+                                       SI_LPTR(sb + i * 1024), 16, 0, 0);
+    }
+  };
+  bf16x8 fa[2][4], fb[2][2];
+  auto ldfrag = [&](int stage, int ks, int buf) {
+    const unsigned char* sa = lds + stage * STAGE_BYTES;
+    const unsigned char* sb = sa + BM * 128;
+    const int pc = ks * 2 + (lane >> 5);
 #pragma unroll
     for (int i = 0; i < 4; ++i)
-      rb[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(dblk + ((size_t)(bg + 2 * i) * M + bm_src) * 8));
+      fa[buf][i] = as_bf16x8(*reinterpret_cast<const u32x4*>(sa + swz(wr * 128 + i * 32 + (lane & 31), pc)));
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+      fb[buf][j] = as_bf16x8(*reinterpret_cast<const u32x4*>(sb + swz(wc * 64 + j * 32 + (lane & 31), pc)));
   };
-  load_tiles(0);
-  for (int c = 0; c < wv.n_chunks; ++c) {
-    __syncthreads();
+  auto mma = [&](int buf) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x4*>(s_a + swz(lr + 32 * i, lc)) = ra[i];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x4*>(s_b + ((bg + 2 * i) * BN2 + bn) * 16) = rb[i];
-    __syncthreads();
-    if (c + 1 < wv.n_chunks) load_tiles(c + 1);
-#pragma unroll
-    for (int ks = 0; ks < BK / 16; ++ks) {
-      const int pc = ks * 2 + (lane >> 5);
-      bf16x8 fa[2], fb[2];
-#pragma unroll
-      for (int i = 0; i < 2; ++i)
-        fa[i] = as_bf16x8(*reinterpret_cast<const u32x4*>(s_a + swz(wr * 64 + i * 32 + (lane & 31), pc)));
+    for (int i = 0; i < 4; ++i)
 #pragma unroll
       for (int j = 0; j < 2; ++j)
-        fb[j] = as_bf16x8(*reinterpret_cast<const u32x4*>(s_b + (pc * BN2 + wc * 64 + j * 32 + (lane & 31)) * 16));
-#pragma unroll
-      for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
-    }
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[buf][i], fb[buf][j], acc[i][j], 0, 0, 0);
+  };
+  const int nk = M / BK;
+  issue(0, 0);
+  for (int it = 0; it < nk; ++it) {
+    const int s = it & 1;
+    __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): this wave's part of the tile has landed
+    __syncthreads();                     // ... and everybody's; all reads of the other stage are done
+    if (it + 1 < nk) issue(s ^ 1, (it + 1) * BK);
+    ldfrag(s, 0, 0);
+    ldfrag(s, 1, 1); mma(0);
+    ldfrag(s, 2, 0); mma(1);
+    ldfrag(s, 3, 1); mma(0);
+    mma(1);
   }
+  // epilogue: element (row 8*(r/4) + 4*(lane/32) + r%4, column lane%32) of each 32x32 tile;
+  // acc[i][0] is the gate tile and acc[i][1] the up tile of the same 32 hidden columns
+  const int jl = wc * 32 + (lane & 31);  // hidden column inside the 128-column tile
+  if (2 * tc + (jl >> 6) < wv.n_chunks) {
+    const int col = wv.col0 + tc * 128 + jl;
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int row = ti.row0 + wr * 128 + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+        if (row < ti.row_end) hact[(size_t)row * ldh + col] = f32_to_bf16(silu_f(acc[i][0][r]) * acc[i][1][r]);
+      }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// FC2.  Tile: 256 rows x 256 output columns m; contraction over the hidden columns of this
+// k-split's chunk range (one chunk = 64 per step).  B operand: the down block of a chunk is
+// [8 groups][M][8 j], i.e. already "8 consecutive k per (group, m)"; it is kept in that order in
+// LDS ([group][256 m] x 16 bytes), read conflict free by consecutive lanes.
+// Output slab `split` of yp: rows x M fp32; overwritten or accumulated.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(THREADS, 1) void k_prefill_down(const uint16_t* __restrict__ hact, int ldh, int M, Plan p,
+                                                             int expert_sel, int x2_only, int total_blocks,
+                                                             int n_ntiles, int n_split, WeightView wv,
+                                                             float* __restrict__ yp, size_t slab_stride,
+                                                             int accumulate) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+  const int L = xcd_remap(blockIdx.x, total_blocks);
+  int inner;
+  TileInfo ti;
+  if (!decode_tile(p, expert_sel, x2_only, L, n_ntiles * n_split, inner, ti)) return;
+  const int nt = inner % n_ntiles, split = inner / n_ntiles;
+  const int c_begin = (int)((long)wv.n_chunks * split / n_split), c_end = (int)((long)wv.n_chunks * (split + 1) / n_split);
+  const int tid = threadIdx.x, lane = tid % WAVE, w = tid / WAVE;
+  const int wr = w >> 2, wc = w & 3;
+  const int n0 = nt * BN;
+  const uint16_t* ebase = wv.base + (size_t)ti.e * wv.expert_stride;
+  float* out = yp + (size_t)split * slab_stride;
+
+  const int lrow = lane >> 3, lpp = lane & 7;
+  const int lc0 = lpp ^ (lrow >> 1);
+  const uint16_t* a_src[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    int row = ti.row0 + w * 32 + i * 8 + lrow;
+    row = row < ti.row_end ? row : ti.row_end - 1;
+    a_src[i] = hact + (size_t)row * ldh + wv.col0 + (((i & 1) ? (lc0 ^ 4) : lc0) * 8);
+  }
+  // B: wave w loads group g = w of the chunk's down block, 4 x 64 output columns
+  size_t b_off[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) b_off[i] = ((size_t)w * M + min(n0 + i * 64 + lane, M - 1)) * 8;
+
+  f32x16 acc[4][2];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  auto issue = [&](int stage, int c) {
+    unsigned char* sa = lds + stage * STAGE_BYTES + w * 4096;
+    unsigned char* sb = lds + stage * STAGE_BYTES + BM * 128 + w * 4096;
+    const uint16_t* dblk = ebase + (size_t)(wv.chunk0 + c) * 3 * CHUNK_J * M + (size_t)2 * CHUNK_J * M;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      __builtin_amdgcn_global_load_lds(SI_GPTR(a_src[i] + c * CHUNK_J), SI_LPTR(sa + i * 1024), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds(SI_GPTR(dblk + b_off[i]), SI_LPTR(sb + i * 1024), 16, 0, 0);
+    }
+  };
+  bf16x8 fa[2][4], fb[2][2];
+  auto ldfrag = [&](int stage, int ks, int buf) {
+    const unsigned char* sa = lds + stage * STAGE_BYTES;
+    const unsigned char* sb = sa + BM * 128;
+    const int pc = ks * 2 + (lane >> 5);
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      fa[buf][i] = as_bf16x8(*reinterpret_cast<const u32x4*>(sa + swz(wr * 128 + i * 32 + (lane & 31), pc)));
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+      fb[buf][j] = as_bf16x8(*reinterpret_cast<const u32x4*>(sb + (pc * BN + wc * 64 + j * 32 + (lane & 31)) * 16));
+  };
+  auto mma = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[buf][i], fb[buf][j], acc[i][j], 0, 0, 0);
+  };
+  if (c_begin < c_end) issue(0, c_begin);
+  for (int c = c_begin; c < c_end; ++c) {
+    const int s = (c - c_begin) & 1;
+    __builtin_amdgcn_s_waitcnt(0x0f70);
+    __syncthreads();
+    if (c + 1 < c_end) issue(s ^ 1, c + 1);
+    ldfrag(s, 0, 0);
+    ldfrag(s, 1, 1); mma(0);
+    ldfrag(s, 2, 0); mma(1);
+    ldfrag(s, 3, 1); mma(0);
+    mma(1);
+  }
+  if (c_begin >= c_end && accumulate) return;  // nothing to add
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
       const int m = n0 + wc * 64 + j * 32 + (lane & 31);
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const int row = ti.row0 + wr * 64 + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+        const int row = ti.row0 + wr * 128 + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
         if (row < ti.row_end && m < M) {
-          float* dst = yp + (size_t)row * M + m;
+          float* dst = out + (size_t)row * M + m;
           *dst = accumulate ? *dst + acc[i][j][r] : acc[i][j][r];
         }
       }
     }
 }
 
-__global__ __launch_bounds__(256) void k_prefill_combine(const float* __restrict__ yp, const float* __restrict__ ycc,
-                                                         int T, int k, int M, int n_x1, int has_shared, Plan p,
-                                                         float* __restrict__ y) {
+__global__ __launch_bounds__(256) void k_prefill_combine(const float* __restrict__ yp, size_t slab_stride, int n_split,
+                                                         const float* __restrict__ ycc, int T, int k, int M, int n_x1,
+                                                         int has_shared, Plan p, float* __restrict__ y) {
   const int t = blockIdx.y;
   const int m4 = blockIdx.x * 256 + threadIdx.x;
   if (m4 * 4 >= M) return;
   float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
   for (int s = 0; s < k; ++s) {
     const float wgt = p.w[t * k + s];
-    const float4 v = reinterpret_cast<const float4*>(yp + (size_t)p.inv[t * k + s] * M)[m4];
+    const float* row = yp + (size_t)p.inv[t * k + s] * M;
+    float4 v = reinterpret_cast<const float4*>(row)[m4];
+    for (int q = 1; q < n_split; ++q) {
+      const float4 v2 = reinterpret_cast<const float4*>(row + (size_t)q * slab_stride)[m4];
+      v.x += v2.x; v.y += v2.y; v.z += v2.z; v.w += v2.w;
+    }
     acc.x = fmaf(wgt, v.x, acc.x); acc.y = fmaf(wgt, v.y, acc.y);
     acc.z = fmaf(wgt, v.z, acc.z); acc.w = fmaf(wgt, v.w, acc.w);
   }
   if (has_shared) {
-    const float4 v = reinterpret_cast<const float4*>(yp + (size_t)(T * k + t) * M)[m4];
-    acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+    const float* row = yp + (size_t)(T * k + t) * M;
+    for (int q = 0; q < n_split; ++q) {
+      const float4 v = reinterpret_cast<const float4*>(row + (size_t)q * slab_stride)[m4];
+      acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+    }
   }
   if (ycc && t < n_x1) {
     const float4 v = reinterpret_cast<const float4*>(ycc + (size_t)t * M)[m4];
@@ -284,32 +330,47 @@ __global__ void k_fill_zero(float* __restrict__ p, size_t n) {
 
 }  // namespace
 
+static hipError_t ensure_lds_attr() {
+  static hipError_t st = [] {
+    hipError_t e = hipFuncSetAttribute((const void*)k_prefill_gateup, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+    if (e != hipSuccess) return e;
+    return hipFuncSetAttribute((const void*)k_prefill_down, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+  }();
+  return st;
+}
+
 hipError_t launch_prefill_gateup(const uint16_t* x, int M, const Plan& plan, int expert_sel, int x2_only,
                                  int n_row_tiles, const WeightView& wv, uint16_t* hact, int ldh,
                                  hipStream_t stream) {
   if (wv.n_chunks <= 0 || n_row_tiles <= 0) return hipSuccess;
-  const int total = n_row_tiles * wv.n_chunks;
-  hipLaunchKernelGGL(k_prefill_gateup, dim3((total + 7) / 8 * 8), dim3(THREADS), 0, stream, x, M, plan, expert_sel,
-                     x2_only, (total + 7) / 8 * 8, wv, hact, ldh);
+  hipError_t e = ensure_lds_attr();
+  if (e != hipSuccess) return e;
+  const int n_ctiles = (wv.n_chunks + 1) / 2;
+  const int total = (n_row_tiles * n_ctiles + 7) / 8 * 8;
+  hipLaunchKernelGGL(k_prefill_gateup, dim3(total), dim3(THREADS), LDS_BYTES, stream, x, M, plan, expert_sel, x2_only,
+                     total, n_ctiles, wv, hact, ldh);
   return hipGetLastError();
 }
 
 hipError_t launch_prefill_down(const uint16_t* hact, int ldh, int M, const Plan& plan, int expert_sel, int x2_only,
-                               int n_row_tiles, const WeightView& wv, float* yp, int accumulate,
-                               hipStream_t stream) {
+                               int n_row_tiles, const WeightView& wv, float* yp, size_t slab_stride, int n_split,
+                               int accumulate, hipStream_t stream) {
   if (wv.n_chunks <= 0 || n_row_tiles <= 0) return hipSuccess;
-  const int n_ntiles = (M + BN2 - 1) / BN2;
-  const int total = n_row_tiles * n_ntiles;
-  hipLaunchKernelGGL(k_prefill_down, dim3((total + 7) / 8 * 8), dim3(THREADS), 0, stream, hact, ldh, M, plan,
-                     expert_sel, x2_only, (total + 7) / 8 * 8, n_ntiles, wv, yp, accumulate);
+  hipError_t e = ensure_lds_attr();
+  if (e != hipSuccess) return e;
+  const int n_ntiles = (M + BN - 1) / BN;
+  const int total = (n_row_tiles * n_ntiles * n_split + 7) / 8 * 8;
+  hipLaunchKernelGGL(k_prefill_down, dim3(total), dim3(THREADS), LDS_BYTES, stream, hact, ldh, M, plan, expert_sel,
+                     x2_only, total, n_ntiles, n_split, wv, yp, slab_stride, accumulate);
   return hipGetLastError();
 }
 
-hipError_t launch_prefill_combine(const float* yp, const float* ycc, int T, int k, int M, int n_x1, int has_shared,
-                                  const Plan& plan, float* y, hipStream_t stream) {
+hipError_t launch_prefill_combine(const float* yp, size_t slab_stride, int n_split, const float* ycc, int T, int k, int M,
+                                  int n_x1, int has_shared, const Plan& plan, float* y, hipStream_t stream) {
   if (T <= 0) return hipSuccess;
   dim3 grid((M / 4 + 255) / 256, T);
-  hipLaunchKernelGGL(k_prefill_combine, grid, dim3(256), 0, stream, yp, ycc, T, k, M, n_x1, has_shared, plan, y);
+  hipLaunchKernelGGL(k_prefill_combine, grid, dim3(256), 0, stream, yp, slab_stride, n_split, ycc, T, k, M, n_x1,
+                     has_shared, plan, y);
   return hipGetLastError();
 }
 

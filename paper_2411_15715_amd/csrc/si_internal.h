@@ -23,7 +23,8 @@ inline size_t chunk_bytes(int M) { return chunk_elems(M) * 2; }
 
 constexpr int MAX_EXPERTS = 256;      // routed experts (a shared expert adds one more table entry)
 constexpr int ROUTE_THREADS = 1024;   // block size of the assignment kernel
-constexpr int PREFILL_BM = 128;       // token rows per GEMM tile (row-tile table granularity)
+constexpr int PREFILL_BM = 256;       // token rows per GEMM tile (row-tile table granularity)
+constexpr int MAX_KSPLIT = 4;         // k-splits (output slabs) of the prefill down projection
 constexpr int DECODE_TB = 4;          // tokens handled per weight pass in the GEMV kernels
 constexpr int DOWN_SLOTS = 16;        // j-splits of the decode down projection per part
 
@@ -94,13 +95,14 @@ hipError_t launch_decode_combine(const DecodeCombineArgs& a, const Plan& plan, f
 hipError_t launch_prefill_gateup(const uint16_t* x, int M, const Plan& plan, int expert_sel, int x2_only,
                                  int n_row_tiles, const WeightView& wv, uint16_t* hact, int ldh,
                                  hipStream_t stream);
-// Yp[row][m] (fp32) (+)= Hact[row][:] . Wd[chunks][m]
+// Yp[split][row][m] (fp32) (+)= Hact[row][chunks of the split] . Wd[chunks][m]; the chunk range of the launch is
+// cut into n_split equal parts, each with its own output slab (summed by the combine kernel)
 hipError_t launch_prefill_down(const uint16_t* hact, int ldh, int M, const Plan& plan, int expert_sel,
-                               int x2_only, int n_row_tiles, const WeightView& wv, float* yp, int accumulate,
-                               hipStream_t stream);
+                               int x2_only, int n_row_tiles, const WeightView& wv, float* yp, size_t slab_stride,
+                               int n_split, int accumulate, hipStream_t stream);
 // y[t][m] = sum_s w[t][s]*Yp[inv[t*k+s]][m] + Yp[T*k+t][m] (shared) + ycc[t][m] (X1 rows)
-hipError_t launch_prefill_combine(const float* yp, const float* ycc, int T, int k, int M, int n_x1,
-                                  int has_shared, const Plan& plan, float* y, hipStream_t stream);
+hipError_t launch_prefill_combine(const float* yp, size_t slab_stride, int n_split, const float* ycc, int T, int k,
+                                  int M, int n_x1, int has_shared, const Plan& plan, float* y, hipStream_t stream);
 hipError_t launch_fill_zero(float* p, size_t n, hipStream_t stream);
 
 }  // namespace si
