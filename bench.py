@@ -106,6 +106,21 @@ def measure(si, torch, cfg, w, split, wl, steps, warmup, n_g):
         run_steps(si, layer, wl, steps, n_g, stream)
         torch.cuda.synchronize()
         elapsed = time.perf_counter() - t0
+        # per-phase call time without any event inside the library (back-to-back calls, one sync)
+        reps = max(2, steps)
+        t1 = time.perf_counter()
+        for _ in range(reps):
+            for xd, ld, _lg in wl.dec:
+                si.si_layer_forward(layer, xd.data_ptr(), ld.data_ptr() if ld is not None else None, cfg.t_decode, 0,
+                                    si.SI_DECODE, wl.yd.data_ptr(), stream=stream)
+        torch.cuda.synchronize()
+        t_dec = (time.perf_counter() - t1) / (reps * len(wl.dec))
+        t1 = time.perf_counter()
+        for _ in range(reps):
+            si.si_layer_forward(layer, wl.xp.data_ptr(), wl.lp_dev.data_ptr() if wl.lp_dev is not None else None,
+                                cfg.t_prefill, n_g, si.SI_PREFILL, wl.yp.data_ptr(), stream=stream)
+        torch.cuda.synchronize()
+        t_pre = (time.perf_counter() - t1) / reps
         # same region again with HIP events around every launch (stream-ordered, on the launch stream)
         si.si_layer_set_profiling(layer, 1)
         stats = []
@@ -114,7 +129,7 @@ def measure(si, torch, cfg, w, split, wl, steps, warmup, n_g):
         si.si_layer_set_profiling(layer, 0)
     finally:
         si.si_layer_destroy(layer)
-    return elapsed, stats, info
+    return elapsed, stats, info, {"decode_call_us": 1e6 * t_dec, "prefill_call_us": 1e6 * t_pre}
 
 
 def kernel_table(si, cfg, info, wl, stats, steps, n_g):
@@ -231,7 +246,7 @@ def main():
     t_gen = time.perf_counter() - t0
     tokens_per_step = cfg.t_prefill + args.decode_calls * cfg.t_decode
 
-    elapsed, stats, info = measure(si, torch, cfg, w, split, wl, args.steps, args.warmup, n_g)
+    elapsed, stats, info, calls = measure(si, torch, cfg, w, split, wl, args.steps, args.warmup, n_g)
     ms_per_step = 1e3 * elapsed / args.steps
     ktab = kernel_table(si, cfg, info, wl, stats, args.steps, n_g)
     weight_kernels = [k for k in ktab if "bound" in ktab[k]]
@@ -239,6 +254,7 @@ def main():
     pre = [st for kind, st in stats if kind == "prefill"]
     dec = [st for kind, st in stats if kind == "decode"]
     phase = {
+        "decode_call_us": calls["decode_call_us"], "prefill_call_us": calls["prefill_call_us"],
         "prefill_ms": float(np.mean([s["total_ms"] for s in pre])), "decode_ms": float(np.mean([s["total_ms"] for s in dec])),
         "prefill_tokens_per_s": cfg.t_prefill / (np.mean([s["total_ms"] for s in pre]) / 1e3),
         "decode_tokens_per_s": cfg.t_decode / (np.mean([s["total_ms"] for s in dec]) / 1e3),
@@ -269,13 +285,14 @@ def main():
         "input_generation_s": round(t_gen, 1),
     }
     if not args.no_gg_only and tuple(split) != (1.0, 0.0, 0.0):
-        e2, stats2, info2 = measure(si, torch, cfg, w, (1.0, 0.0, 0.0), wl, args.steps, args.warmup, 0)
+        e2, stats2, info2, calls2 = measure(si, torch, cfg, w, (1.0, 0.0, 0.0), wl, args.steps, args.warmup, 0)
         k2 = kernel_table(si, cfg, info2, wl, stats2, args.steps, 0)
         pre2 = [st for kind, st in stats2 if kind == "prefill"]
         dec2 = [st for kind, st in stats2 if kind == "decode"]
         out["gg_only"] = {
             "split_gg_cg_cc": [1.0, 0.0, 0.0], "ms_per_step": round(1e3 * e2 / args.steps, 4),
             "tokens_per_s": round(tokens_per_step / (e2 / args.steps), 2),
+            "decode_call_us": round(calls2["decode_call_us"], 2), "prefill_call_us": round(calls2["prefill_call_us"], 2),
             "prefill_ms": round(float(np.mean([s["total_ms"] for s in pre2])), 4),
             "decode_ms": round(float(np.mean([s["total_ms"] for s in dec2])), 4),
             "rooflines": [roofline_of(k, k2[k]) for k in k2 if "bound" in k2[k]],

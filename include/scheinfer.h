@@ -64,7 +64,7 @@ typedef struct {
   int32_t max_tokens;  /* largest T a forward call may pass; sizes the workspaces */
   int32_t cc_threads;  /* host threads for the CC part; 0 -> min(16, hardware threads) */
   int32_t device;      /* HIP device ordinal */
-  int32_t stage_mib;   /* size of one staging buffer for CG copies in MiB; 0 -> 64 */
+  int32_t stage_mib;   /* size of one staging buffer for CG copies in MiB; 0 -> 256 */
   int32_t n_stage;     /* number of staging buffers (>= 2); 0 -> 2 (double buffering) */
 } si_layer_desc_t;
 

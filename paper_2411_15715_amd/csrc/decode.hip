@@ -42,10 +42,11 @@ __device__ inline bool block_rows(const Plan& p, int expert_sel, int x2_only, in
   return r1 > r0;
 }
 
+template <int TB>
 __global__ __launch_bounds__(GU_THREADS) void k_decode_gateup(const uint16_t* __restrict__ x, int M, Plan p,
                                                               int expert_sel, int x2_only, WeightView wv,
                                                               float* __restrict__ h, int ldh) {
-  extern __shared__ u32x4 s_x[];  // [DECODE_TB][M/8] bf16 x 8
+  extern __shared__ u32x4 s_x[];  // [TB][M/8] bf16 x 8
   int e, r0, r1;
   if (!block_rows(p, expert_sel, x2_only, blockIdx.y, e, r0, r1)) return;
   const int tid = threadIdx.x, lane = tid % WAVE, wid = tid / WAVE;
@@ -58,8 +59,8 @@ __global__ __launch_bounds__(GU_THREADS) void k_decode_gateup(const uint16_t* __
   const u32x4* urow = reinterpret_cast<const u32x4*>(cbase + (size_t)(CHUNK_J + jj0) * M);
   const int jcol = wv.col0 + (blockIdx.x / blocks_per_chunk) * CHUNK_J + jj0;
 
-  for (int rb = r0; rb < r1; rb += DECODE_TB) {
-    const int nt = min(DECODE_TB, r1 - rb);
+  for (int rb = r0; rb < r1; rb += TB) {
+    const int nt = min(TB, r1 - rb);
     __syncthreads();
     for (int i = tid; i < nt * M8; i += GU_THREADS) {
       int tb = i / M8, c = i % M8;
@@ -67,11 +68,11 @@ __global__ __launch_bounds__(GU_THREADS) void k_decode_gateup(const uint16_t* __
       s_x[tb * M8 + c] = reinterpret_cast<const u32x4*>(x + (size_t)tok * M)[c];
     }
     __syncthreads();
-    float ag[GU_JPW][DECODE_TB], au[GU_JPW][DECODE_TB];
+    float ag[GU_JPW][TB], au[GU_JPW][TB];
 #pragma unroll
     for (int j = 0; j < GU_JPW; ++j)
 #pragma unroll
-      for (int tb = 0; tb < DECODE_TB; ++tb) { ag[j][tb] = 0.f; au[j][tb] = 0.f; }
+      for (int tb = 0; tb < TB; ++tb) { ag[j][tb] = 0.f; au[j][tb] = 0.f; }
     for (int c = lane; c < M8; c += WAVE) {
       u32x4 wg[GU_JPW], wu[GU_JPW];
 #pragma unroll
@@ -80,7 +81,7 @@ __global__ __launch_bounds__(GU_THREADS) void k_decode_gateup(const uint16_t* __
         wu[j] = __builtin_nontemporal_load(urow + (size_t)j * M8 + c);
       }
 #pragma unroll
-      for (int tb = 0; tb < DECODE_TB; ++tb) {
+      for (int tb = 0; tb < TB; ++tb) {
         if (tb < nt) {
           u32x4 xv = s_x[tb * M8 + c];
           float xf[8] = {bf_lo(xv.x), bf_hi(xv.x), bf_lo(xv.y), bf_hi(xv.y),
@@ -104,7 +105,7 @@ __global__ __launch_bounds__(GU_THREADS) void k_decode_gateup(const uint16_t* __
 #pragma unroll
     for (int j = 0; j < GU_JPW; ++j)
 #pragma unroll
-      for (int tb = 0; tb < DECODE_TB; ++tb) {
+      for (int tb = 0; tb < TB; ++tb) {
         if (tb < nt) {
           float g = wave_sum(ag[j][tb]);
           float u = wave_sum(au[j][tb]);
@@ -114,6 +115,7 @@ __global__ __launch_bounds__(GU_THREADS) void k_decode_gateup(const uint16_t* __
   }
 }
 
+template <int TB>
 __global__ __launch_bounds__(DN_THREADS) void k_decode_down(const float* __restrict__ h, int ldh, int M, Plan p,
                                                             int expert_sel, int x2_only, WeightView wv, int slot0,
                                                             int chunks_per_slot, float* __restrict__ part,
@@ -130,21 +132,21 @@ __global__ __launch_bounds__(DN_THREADS) void k_decode_down(const float* __restr
   const uint16_t* ebase = wv.base + (size_t)e * wv.expert_stride;
   float* out = part + (size_t)(slot0 + s) * slot_stride;
 
-  extern __shared__ float s_h[];  // [DECODE_TB][n_j] activations of this slot
+  extern __shared__ float s_h[];  // [TB][n_j] activations of this slot
   const int n_j = (c_end - c_begin) * CHUNK_J;
   const int jbase = wv.col0 + c_begin * CHUNK_J;
 
-  for (int rb = r0; rb < r1; rb += DECODE_TB) {
-    const int nt = min(DECODE_TB, r1 - rb);
+  for (int rb = r0; rb < r1; rb += TB) {
+    const int nt = min(TB, r1 - rb);
     __syncthreads();
     for (int i = threadIdx.x; i < nt * n_j; i += DN_THREADS) {
       int tb = i / n_j, j = i % n_j;
       s_h[tb * n_j + j] = h[(size_t)(rb + tb) * ldh + jbase + j];
     }
     __syncthreads();
-    float acc[DECODE_TB];
+    float acc[TB];
 #pragma unroll
-    for (int tb = 0; tb < DECODE_TB; ++tb) acc[tb] = 0.f;
+    for (int tb = 0; tb < TB; ++tb) acc[tb] = 0.f;
     for (int c = c_begin; c < c_end; ++c) {
       const u32x4* dblk = reinterpret_cast<const u32x4*>(ebase + (size_t)(wv.chunk0 + c) * 3 * CHUNK_J * M +
                                                          (size_t)2 * CHUNK_J * M);
@@ -152,7 +154,7 @@ __global__ __launch_bounds__(DN_THREADS) void k_decode_down(const float* __restr
 #pragma unroll
       for (int q = 0; q < 8; ++q) wd[q] = __builtin_nontemporal_load(dblk + (size_t)q * M + mm);
 #pragma unroll
-      for (int tb = 0; tb < DECODE_TB; ++tb) {
+      for (int tb = 0; tb < TB; ++tb) {
         if (tb < nt) {
           const float4* hr = reinterpret_cast<const float4*>(s_h + tb * n_j + (c - c_begin) * CHUNK_J);
           float a = acc[tb];
@@ -170,67 +172,84 @@ __global__ __launch_bounds__(DN_THREADS) void k_decode_down(const float* __restr
     }
     if (active) {
 #pragma unroll
-      for (int tb = 0; tb < DECODE_TB; ++tb)
+      for (int tb = 0; tb < TB; ++tb)
         if (tb < nt) out[(size_t)(rb + tb) * M + m] = acc[tb];
     }
   }
 }
 
-__global__ __launch_bounds__(256) void k_decode_combine(DecodeCombineArgs a, Plan p, float* __restrict__ y) {
+// One thread per 4 output columns of one token.  The slot partials of a row are independent loads
+// (issued together, then summed in slot order, so the result is deterministic).
+__global__ __launch_bounds__(64) void k_decode_combine(DecodeCombineArgs a, Plan p, float* __restrict__ y) {
   const int t = blockIdx.y;
-  const int m = blockIdx.x * 256 + threadIdx.x;
-  if (m >= a.M) return;
+  const int m4 = blockIdx.x * 64 + threadIdx.x;
+  if (m4 * 4 >= a.M) return;
   const bool is_x2 = t >= a.n_x1;
-  float acc = 0.f;
+  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
   const int n_terms = a.k + (a.has_shared ? 1 : 0);
   for (int s = 0; s < n_terms; ++s) {
     int row;
     float wgt;
     if (s < a.k) { row = p.inv[t * a.k + s]; wgt = p.w[t * a.k + s]; }
     else { row = a.T * a.k + t; wgt = 1.f; }
-    const int ngg = s < a.k ? a.n_slots_gg : a.s_slots_gg, ncg = s < a.k ? a.n_slots_cg : a.s_slots_cg,
-              ncc = s < a.k ? a.n_slots_cc : a.s_slots_cc;
-    float v = 0.f;
-    for (int q = 0; q < ngg; ++q) v += a.part[(size_t)(0 * DOWN_SLOTS + q) * a.slot_stride + (size_t)row * a.M + m];
-    for (int q = 0; q < ncg; ++q) v += a.part[(size_t)(1 * DOWN_SLOTS + q) * a.slot_stride + (size_t)row * a.M + m];
-    if (is_x2)
-      for (int q = 0; q < ncc; ++q) v += a.part[(size_t)(2 * DOWN_SLOTS + q) * a.slot_stride + (size_t)row * a.M + m];
-    acc = fmaf(wgt, v, acc);
+    const int n_part[3] = {s < a.k ? a.n_slots_gg : a.s_slots_gg, s < a.k ? a.n_slots_cg : a.s_slots_cg,
+                           is_x2 ? (s < a.k ? a.n_slots_cc : a.s_slots_cc) : 0};
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+    for (int part = 0; part < 3; ++part) {
+      const float* base = a.part + (size_t)(part * DOWN_SLOTS) * a.slot_stride + (size_t)row * a.M;
+      float4 tmp[DOWN_SLOTS];
+#pragma unroll
+      for (int q = 0; q < DOWN_SLOTS; ++q)
+        tmp[q] = q < n_part[part] ? reinterpret_cast<const float4*>(base + (size_t)q * a.slot_stride)[m4]
+                                  : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+      for (int q = 0; q < DOWN_SLOTS; ++q) { v.x += tmp[q].x; v.y += tmp[q].y; v.z += tmp[q].z; v.w += tmp[q].w; }
+    }
+    acc.x = fmaf(wgt, v.x, acc.x); acc.y = fmaf(wgt, v.y, acc.y);
+    acc.z = fmaf(wgt, v.z, acc.z); acc.w = fmaf(wgt, v.w, acc.w);
   }
-  if (!is_x2 && a.ycc) acc += a.ycc[(size_t)t * a.M + m];
-  y[(size_t)t * a.M + m] = acc;
+  if (!is_x2 && a.ycc) {
+    const float4 c = reinterpret_cast<const float4*>(a.ycc + (size_t)t * a.M)[m4];
+    acc.x += c.x; acc.y += c.y; acc.z += c.z; acc.w += c.w;
+  }
+  reinterpret_cast<float4*>(y + (size_t)t * a.M)[m4] = acc;
 }
 
 }  // namespace
 
-hipError_t launch_decode_gateup(const uint16_t* x, int M, const Plan& plan, int EX, int expert_sel, int x2_only,
+static int pick_tb(int tb_hint) { return tb_hint <= 1 ? 1 : (tb_hint <= 2 ? 2 : 4); }
+
+hipError_t launch_decode_gateup(const uint16_t* x, int M, const Plan& plan, int tb_hint, int expert_sel, int x2_only,
                                 int max_touched, const WeightView& wv, float* h, int ldh, hipStream_t stream) {
-  (void)EX;
   if (wv.n_chunks <= 0) return hipSuccess;
   dim3 grid(wv.n_chunks * (CHUNK_J / GU_JPB), expert_sel >= 0 ? 1 : max_touched);
-  size_t lds = (size_t)DECODE_TB * M * 2;
-  hipLaunchKernelGGL(k_decode_gateup, grid, dim3(GU_THREADS), lds, stream, x, M, plan, expert_sel, x2_only, wv, h,
-                     ldh);
+  const int tb = pick_tb(tb_hint);
+  size_t lds = (size_t)tb * M * 2;
+  if (tb == 1) hipLaunchKernelGGL(k_decode_gateup<1>, grid, dim3(GU_THREADS), lds, stream, x, M, plan, expert_sel, x2_only, wv, h, ldh);
+  else if (tb == 2) hipLaunchKernelGGL(k_decode_gateup<2>, grid, dim3(GU_THREADS), lds, stream, x, M, plan, expert_sel, x2_only, wv, h, ldh);
+  else hipLaunchKernelGGL(k_decode_gateup<4>, grid, dim3(GU_THREADS), lds, stream, x, M, plan, expert_sel, x2_only, wv, h, ldh);
   return hipGetLastError();
 }
 
-hipError_t launch_decode_down(const float* h, int ldh, int M, const Plan& plan, int EX, int expert_sel, int x2_only,
+hipError_t launch_decode_down(const float* h, int ldh, int M, const Plan& plan, int tb_hint, int expert_sel, int x2_only,
                               int max_touched, const WeightView& wv, int slot0, int chunks_per_slot, float* part,
                               size_t slot_stride, hipStream_t stream) {
-  (void)EX;
   if (wv.n_chunks <= 0) return hipSuccess;
   int n_slots = (wv.n_chunks + chunks_per_slot - 1) / chunks_per_slot;
   dim3 grid((M + DN_THREADS - 1) / DN_THREADS, n_slots, expert_sel >= 0 ? 1 : max_touched);
-  size_t lds = (size_t)DECODE_TB * chunks_per_slot * CHUNK_J * sizeof(float);
-  hipLaunchKernelGGL(k_decode_down, grid, dim3(DN_THREADS), lds, stream, h, ldh, M, plan, expert_sel, x2_only, wv,
-                     slot0, chunks_per_slot, part, slot_stride);
+  const int tb = pick_tb(tb_hint);
+  size_t lds = (size_t)tb * chunks_per_slot * CHUNK_J * sizeof(float);
+  if (tb == 1) hipLaunchKernelGGL(k_decode_down<1>, grid, dim3(DN_THREADS), lds, stream, h, ldh, M, plan, expert_sel, x2_only, wv, slot0, chunks_per_slot, part, slot_stride);
+  else if (tb == 2) hipLaunchKernelGGL(k_decode_down<2>, grid, dim3(DN_THREADS), lds, stream, h, ldh, M, plan, expert_sel, x2_only, wv, slot0, chunks_per_slot, part, slot_stride);
+  else hipLaunchKernelGGL(k_decode_down<4>, grid, dim3(DN_THREADS), lds, stream, h, ldh, M, plan, expert_sel, x2_only, wv, slot0, chunks_per_slot, part, slot_stride);
   return hipGetLastError();
 }
 
 hipError_t launch_decode_combine(const DecodeCombineArgs& a, const Plan& plan, float* y, hipStream_t stream) {
   if (a.T <= 0) return hipSuccess;
-  dim3 grid((a.M + 255) / 256, a.T);
-  hipLaunchKernelGGL(k_decode_combine, grid, dim3(256), 0, stream, a, plan, y);
+  dim3 grid((a.M / 4 + 63) / 64, a.T);
+  hipLaunchKernelGGL(k_decode_combine, grid, dim3(64), 0, stream, a, plan, y);
   return hipGetLastError();
 }
 

@@ -347,7 +347,7 @@ int si_layer_create(const si_layer_desc_t* desc, const uint16_t* w_gate, const u
   L->n_stage = desc->n_stage == 0 ? 2 : desc->n_stage;
   const bool any_host = hch + shch > 0;
   if (any_host) {
-    size_t stage_bytes = (size_t)(desc->stage_mib == 0 ? 64 : desc->stage_mib) << 20;
+    size_t stage_bytes = (size_t)(desc->stage_mib == 0 ? 256 : desc->stage_mib) << 20;
     int sc = (int)std::max<size_t>(1, stage_bytes / (ce * 2));
     // a decode piece must hold whole down-projection slots
     int cps_max = std::max({ceil_div(L->ch_cg, DOWN_SLOTS), ceil_div(L->ch_cc, DOWN_SLOTS), ceil_div(L->sch_cg, DOWN_SLOTS), ceil_div(L->sch_cc, DOWN_SLOTS), 1});
@@ -369,7 +369,7 @@ int si_layer_create(const si_layer_desc_t* desc, const uint16_t* w_gate, const u
 
   // ---- workspaces
   const size_t n_pairs = (size_t)T * k, n_rows = n_pairs + (L->has_shared ? T : 0);
-  L->max_tiles = (int)(n_rows / PREFILL_BM) + L->EX + 2;
+  L->max_tiles = (int)(n_rows / 64) + L->EX + 2;  // row-tile tables for the smallest tile (64 rows)
   {
     size_t ints = 0;
     auto take = [&](size_t n) { size_t o = ints; ints += (n + 3) / 4 * 4; return o; };
@@ -445,7 +445,7 @@ int si_route(const float* logits_dev, int32_t T, int32_t E, int32_t k, const si_
   }
   p.idx = out->idx ? out->idx : tmp;
   p.w = out->w ? out->w : reinterpret_cast<float*>(tmp + n);
-  hipError_t e = launch_route(logits_dev, T, E, k, 0, 0, PREFILL_BM, p, u, s);
+  hipError_t e = launch_route(logits_dev, T, E, k, 0, 0, PREFILL_BM_MAX, p, u, s);
   if (tmp) (void)hipFreeAsync(tmp, s);
   if (e != hipSuccess) return fail(SI_EHIP, "route launch failed: %s", hipGetErrorString(e));
   return SI_OK;
@@ -479,6 +479,9 @@ int si_layer_forward(si_layer_t* L, const void* x_dev, const float* logits_dev, 
   const bool need_sync = need_cc || need_counts;
   const auto wall0 = std::chrono::steady_clock::now();
 
+  // rows per GEMM tile: 256 when experts have many rows (MFMA bound), smaller when the GEMM only streams weights
+  auto pick_bm = [](int rows) { return rows >= 192 ? 256 : (rows >= 96 ? 128 : 64); };
+  const int bm_call = pick_bm(ceil_div(T * k, E));
   L->ev_used = 0;
   L->segs.clear();
   si_stats_t st{};
@@ -491,7 +494,7 @@ int si_layer_forward(si_layer_t* L, const void* x_dev, const float* logits_dev, 
   if (rout) u = RouteOut{rout->idx, rout->w, rout->count, rout->off, rout->perm, rout->inv};
   {
     SegScope sc(L, stream, 0);
-    hipError_t e = launch_route(E > 1 ? logits_dev : nullptr, T, E, k, L->has_shared, n_g, PREFILL_BM, L->plan, u, stream);
+    hipError_t e = launch_route(E > 1 ? logits_dev : nullptr, T, E, k, L->has_shared, n_g, bm_call, L->plan, u, stream);
     if (e != hipSuccess) return fail(SI_EHIP, "route launch failed: %s", hipGetErrorString(e));
   }
   // ---- hand-off to the host: X1 and the assignment (Section III-B: "X1 will be additionally
@@ -531,7 +534,7 @@ int si_layer_forward(si_layer_t* L, const void* x_dev, const float* logits_dev, 
   auto rows_all = [&](int e) { return need_sync ? L->hcount[e] : T; };
   auto rows_x2 = [&](int e) { return need_sync ? L->hcount[e] - L->hcount[EX + e] : n_g; };
   const int max_touched = std::min(EX, T * k + L->has_shared);
-  const int tiles_upper = (T * k) / PREFILL_BM + E;  // bound on the routed row tiles
+  const int tiles_upper = (T * k) / bm_call + E;  // bound on the routed row tiles
   const int cps_gg = std::max(1, ceil_div(L->ch_gg, DOWN_SLOTS)), cps_cg = std::max(1, ceil_div(L->ch_cg, DOWN_SLOTS)),
             cps_cc = std::max(1, ceil_div(L->ch_cc, DOWN_SLOTS));
   const int scps_gg = std::max(1, ceil_div(L->sch_gg, DOWN_SLOTS)), scps_cg = std::max(1, ceil_div(L->sch_cg, DOWN_SLOTS)),
@@ -539,7 +542,7 @@ int si_layer_forward(si_layer_t* L, const void* x_dev, const float* logits_dev, 
   const size_t slot_stride = (size_t)L->rows_dec * M;
   // k-splits of the prefill down projection: enough blocks to fill 256 CUs when there are few row tiles
   const int n_ntiles = ceil_div(M, 256);
-  const int split_call = std::min(MAX_KSPLIT, std::max(1, 256 / (std::max(1, ceil_div(T * k, PREFILL_BM)) * n_ntiles)));
+  const int split_call = std::min(MAX_KSPLIT, std::max(1, 256 / (std::max(1, ceil_div(T * k, bm_call)) * n_ntiles)));
   hipError_t ke = hipSuccess;
 #define K_TRY(expr) do { ke = (expr); if (ke != hipSuccess) return fail(SI_EHIP, "%s failed: %s", #expr, hipGetErrorString(ke)); } while (0)
 
@@ -556,23 +559,29 @@ int si_layer_forward(si_layer_t* L, const void* x_dev, const float* logits_dev, 
       const int cps = is_shared ? (part == 0 ? scps_gg : part == 1 ? scps_cg : scps_cc) : (part == 0 ? cps_gg : part == 1 ? cps_cg : cps_cc);
       {
         SegScope sc(L, stream, SI_K_DECODE_GATEUP);
-        K_TRY(launch_decode_gateup(x, M, L->plan, EX, esel, x2_only, max_touched, wv, L->d_h, L->ldh_dec, stream));
+        K_TRY(launch_decode_gateup(x, M, L->plan, T, esel, x2_only, max_touched, wv, L->d_h, L->ldh_dec, stream));
       }
       SegScope sc(L, stream, SI_K_DECODE_DOWN);
-      K_TRY(launch_decode_down(L->d_h, L->ldh_dec, M, L->plan, EX, esel, x2_only, max_touched, wv,
+      K_TRY(launch_decode_down(L->d_h, L->ldh_dec, M, L->plan, T, esel, x2_only, max_touched, wv,
                                part * DOWN_SLOTS + part_chunk0 / cps, cps, L->d_part, slot_stride, stream));
     } else {
-      int n_rt;
-      if (esel >= 0) n_rt = ceil_div(x2_only ? rows_x2(esel) : rows_all(esel), PREFILL_BM);
-      else n_rt = tiles_upper;
+      int n_rt, bm;
+      if (esel >= 0) {
+        const int rows = x2_only ? rows_x2(esel) : rows_all(esel);
+        bm = pick_bm(rows);
+        n_rt = ceil_div(rows, bm);
+      } else {
+        bm = bm_call;
+        n_rt = tiles_upper;
+      }
       const int ldh = n * CHUNK_J;
       {
         SegScope sc(L, stream, SI_K_PREFILL_GATEUP);
-        K_TRY(launch_prefill_gateup(x, M, L->plan, esel, x2_only, n_rt, wv, L->d_hact, ldh, stream));
+        K_TRY(launch_prefill_gateup(x, M, L->plan, bm, esel, x2_only, n_rt, wv, L->d_hact, ldh, stream));
       }
       SegScope sc(L, stream, SI_K_PREFILL_DOWN);
       const int split = first_for_rows ? split_call : std::min(split_call, std::max(1, n / 8));
-      K_TRY(launch_prefill_down(L->d_hact, ldh, M, L->plan, esel, x2_only, n_rt, wv, L->d_yp, L->yp_slab, split,
+      K_TRY(launch_prefill_down(L->d_hact, ldh, M, L->plan, bm, esel, x2_only, n_rt, wv, L->d_yp, L->yp_slab, split,
                                 first_for_rows ? 0 : 1, stream));
     }
     return SI_OK;

@@ -5,9 +5,9 @@
 // Rows are the expert-sorted (token, slot) pairs of the token assignment; a row tile never
 // crosses an expert.  The gather of x rows is fused into the A-operand load of the first GEMM.
 //
-// Both GEMMs: one 512-thread block (8 waves, 2 per SIMD) per 256 x 256 output tile, BK = 64,
-// two LDS stages of 64 KB filled by direct global->LDS loads (global_load_lds_dwordx4, no VGPR
-// staging), wave tile 128 x 64 (8 MFMA 32x32x16 per k-step, 128 accumulator registers).
+// Both GEMMs: one 512-thread block (8 waves, 2 per SIMD) per BM x 256 output tile (BM = 256, 128 or
+// 64 rows), BK = 64, a ring of LDS stages filled by direct global->LDS loads (global_load_lds_dwordx4,
+// no VGPR staging), wave tile (BM/2) x 64.
 // LDS rows hold 64 contraction elements (128 bytes); the 16-byte piece c of row r sits at piece
 // c ^ ((r >> 1) & 7): gfx950's LDS has 64 banks, so 16 consecutive rows x 16 bytes must cover 256
 // distinct bytes of bank space for the 128-bit MFMA operand reads to be conflict free (measured:
@@ -23,13 +23,26 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 #define SI_GPTR(p) ((const void __attribute__((address_space(1)))*)(p))
 #define SI_LPTR(p) ((void __attribute__((address_space(3)))*)(p))
 
+#ifndef SI_ROTK
+#define SI_ROTK 0
+#endif
 constexpr int WAVE = 64;
 constexpr int THREADS = 512;
-constexpr int BM = PREFILL_BM;  // 256 rows
-constexpr int BN = 256;         // B rows per tile: 128 hidden columns (gate+up) or 256 output columns
+constexpr int BN = 256;  // B rows per tile: 128 hidden columns (gate+up) or 256 output columns
 constexpr int BK = 64;
-constexpr int STAGE_BYTES = (BM + BN) * BK * 2;  // 64 KB
-constexpr int LDS_BYTES = 2 * STAGE_BYTES;       // 128 KB
+constexpr int B_BYTES = BN * BK * 2;  // 32 KB
+
+// Tile shapes.  BM rows per tile: 256 for the MFMA-bound regime (many rows per expert), 128 / 64 when an
+// expert has few rows and the GEMM is bound by streaming its weights: smaller A tiles leave LDS for a
+// deeper ring of stages, i.e. more weight bytes in flight per CU.
+template <int BM> struct Shape {
+  static constexpr int NST = BM == 256 ? 2 : 3;          // LDS stages
+  static constexpr int STAGE = BM * 128 + B_BYTES;        // bytes per stage
+  static constexpr int LDS = NST * STAGE;                 // 128 KB, 144 KB, 120 KB
+  static constexpr int FA = BM / 64;                      // A fragments (32 rows each) per wave
+  static constexpr int ALD = BM / 64;                     // A load instructions per wave per stage
+  static constexpr int LPW = ALD + 4;                     // load instructions per wave per stage
+};
 
 __device__ inline uint16_t f32_to_bf16(float f) {
   uint32_t u = __float_as_uint(f);
@@ -44,6 +57,22 @@ __device__ inline bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, 
 // swizzled byte offset of 16-byte piece c of row r in a [rows][64] bf16 tile
 __device__ inline int swz(int r, int c) { return r * 128 + ((c ^ ((r >> 1) & 7)) << 4); }
 
+// s_waitcnt vmcnt(n) only (lgkmcnt / expcnt untouched); n < 64
+template <int N> __device__ inline void wait_vmcnt() {
+  __builtin_amdgcn_s_waitcnt(0x0f70 | (N & 0xf) | (((N >> 4) & 3) << 14));
+}
+
+// Workgroup barrier WITHOUT the memory fence of __syncthreads(): the fence would drain every outstanding
+// global->LDS load (s_waitcnt vmcnt(0)) and so defeat the multi-stage ring.  What has to be visible
+// after the barrier is (a) each wave's own direct-to-LDS loads of the tile about to be read, which the
+// wave itself waited for with wait_vmcnt<> just before, and (b) nothing else: fragments read from the
+// slot about to be refilled were consumed by MFMAs earlier in program order.
+__device__ inline void block_barrier() {
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+}
+
 // XCD-aware remap: consecutive hardware block ids go round-robin over the 8 XCDs; give each XCD a
 // contiguous range of logical ids so that blocks sharing weights share an L2.
 __device__ inline int xcd_remap(int b, int total) {
@@ -54,7 +83,8 @@ __device__ inline int xcd_remap(int b, int total) {
 struct TileInfo { int e, row0, row_end; };
 
 // logical id L -> (expert, inner index, row tile) with the row tile varying fastest inside an
-// expert: L / n_inner indexes the row-tile table, which yields the expert.
+// expert: L / n_inner indexes the row-tile table (built for the same BM), which yields the expert.
+template <int BM>
 __device__ inline bool decode_tile(const Plan& p, int expert_sel, int x2_only, int L, int n_inner, int& inner,
                                    TileInfo& ti) {
   int e, first, nrt, start, end;
@@ -86,124 +116,143 @@ __device__ inline bool decode_tile(const Plan& p, int expert_sel, int x2_only, i
 }
 
 // ---------------------------------------------------------------------------------------------
-// FC1 + SwiGLU.  Tile: 256 rows x 128 hidden columns (two chunks).  B rows in LDS are ordered so
+// The two GEMM kernels share their main loop.  8 waves as 2 (rows) x 4 (B-row quarters of 64);
+// wave tile (BM/2) x 64: FA A-fragments x 2 B-fragments of v_mfma_f32_32x32x16_bf16.
+// Ring of NST stages: the loads of k-tile it + NST - 1 are issued right after the barrier of
+// iteration it (the slot was last read in iteration it - 1); the wait at the top leaves the
+// (NST - 2) younger tiles in flight.
+// ---------------------------------------------------------------------------------------------
+#define SI_GEMM_MAIN_LOOP(NK, ISSUE, BFRAG_OFF)                                                                  \
+  f32x16 acc[S::FA][2];                                                                                          \
+  _Pragma("unroll") for (int i = 0; i < S::FA; ++i) _Pragma("unroll") for (int j = 0; j < 2; ++j)                \
+      _Pragma("unroll") for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;                                         \
+  bf16x8 fa[2][S::FA], fb[2][2];                                                                                 \
+  auto ldfrag = [&](int stage, int ks, int buf) {                                                                \
+    const unsigned char* sa = lds + stage * S::STAGE;                                                            \
+    const unsigned char* sb = sa + BM * 128;                                                                     \
+    const int pc = ks * 2 + (lane >> 5);                                                                         \
+    _Pragma("unroll") for (int i = 0; i < S::FA; ++i) fa[buf][i] = as_bf16x8(                                    \
+        *reinterpret_cast<const u32x4*>(sa + swz(wr * (BM / 2) + i * 32 + (lane & 31), pc)));                    \
+    _Pragma("unroll") for (int j = 0; j < 2; ++j) fb[buf][j] = as_bf16x8(                                        \
+        *reinterpret_cast<const u32x4*>(sb + BFRAG_OFF(wc * 64 + j * 32 + (lane & 31), pc)));                    \
+  };                                                                                                             \
+  auto mma = [&](int buf) {                                                                                      \
+    _Pragma("unroll") for (int i = 0; i < S::FA; ++i) _Pragma("unroll") for (int j = 0; j < 2; ++j)              \
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[buf][i], fb[buf][j], acc[i][j], 0, 0, 0);         \
+  };                                                                                                             \
+  {                                                                                                              \
+    const int nk_ = (NK);                                                                                        \
+    _Pragma("unroll") for (int s0 = 0; s0 < S::NST - 1; ++s0) if (s0 < nk_) ISSUE(s0, s0);                       \
+    int st = 0, fill = S::NST - 1;                                                                               \
+    for (int it = 0; it < nk_; ++it) {                                                                           \
+      if (it + S::NST - 2 < nk_) wait_vmcnt<(S::NST - 2) * S::LPW>();                                            \
+      else wait_vmcnt<0>();                                                                                      \
+      block_barrier();                                                                                           \
+      if (it + S::NST - 1 < nk_) ISSUE(fill, it + S::NST - 1);                                                   \
+      ldfrag(st, 0, 0);                                                                                          \
+      ldfrag(st, 1, 1); mma(0);                                                                                  \
+      ldfrag(st, 2, 0); mma(1);                                                                                  \
+      ldfrag(st, 3, 1); mma(0);                                                                                  \
+      mma(1);                                                                                                    \
+      st = st + 1 == S::NST ? 0 : st + 1;                                                                        \
+      fill = fill + 1 == S::NST ? 0 : fill + 1;                                                                  \
+    }                                                                                                            \
+  }
+
+#define SI_BOFF_SWZ(row, pc) swz((row), (pc))
+#define SI_BOFF_K8(col, pc) (((pc) * BN + (col)) * 16)
+
+// ---------------------------------------------------------------------------------------------
+// FC1 + SwiGLU.  Tile: BM rows x 128 hidden columns (two chunks).  B rows in LDS are ordered so
 // that wave column wc owns hidden columns [32 wc, 32 wc + 32): LDS B row = wc*64 + f*32 + jj with
 // f = 0 the gate row and f = 1 the up row of column 32 wc + jj; SiLU(gate)*up is then formed in
 // registers from the two accumulator tiles of a wave.
 // ---------------------------------------------------------------------------------------------
+template <int BM>
 __global__ __launch_bounds__(THREADS, 1) void k_prefill_gateup(const uint16_t* __restrict__ x, int M, Plan p,
                                                                int expert_sel, int x2_only, int total_blocks,
                                                                int n_ctiles, WeightView wv,
                                                                uint16_t* __restrict__ hact, int ldh) {
+  using S = Shape<BM>;
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
   const int L = xcd_remap(blockIdx.x, total_blocks);
   int tc;
   TileInfo ti;
-  if (!decode_tile(p, expert_sel, x2_only, L, n_ctiles, tc, ti)) return;
+  if (!decode_tile<BM>(p, expert_sel, x2_only, L, n_ctiles, tc, ti)) return;
   const int tid = threadIdx.x, lane = tid % WAVE, w = tid / WAVE;
   const int wr = w >> 2, wc = w & 3;
   const uint16_t* ebase = wv.base + (size_t)ti.e * wv.expert_stride;
 
-  // loader: wave w fills LDS rows w*32 + i*8 + lane/8 (i < 4) of A and of B; lane%8 is the slot
-  // inside the 128-byte row, holding logical piece slot ^ ((row >> 1) & 7)
+  // loader: a wave instruction fills 8 LDS rows (1 KB); lane/8 is the row, lane%8 the slot inside the
+  // 128-byte row, which holds logical piece slot ^ ((row >> 1) & 7)
   const int lrow = lane >> 3, lpp = lane & 7;
-  const int lc0 = lpp ^ (lrow >> 1);  // even i; odd i uses lc0 ^ 4
-  const uint16_t* a_src[4];
+  const uint16_t* a_src[S::ALD];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    int row = ti.row0 + w * 32 + i * 8 + lrow;
+  for (int i = 0; i < S::ALD; ++i) {
+    const int lr = w * (BM / 8) + i * 8 + lrow;  // LDS row of the A tile
+    int row = ti.row0 + lr;
     row = row < ti.row_end ? row : ti.row_end - 1;
-    a_src[i] = x + (size_t)p.row_token[row] * M + (((i & 1) ? (lc0 ^ 4) : lc0) * 8);
+    a_src[i] = x + (size_t)p.row_token[row] * M + ((lpp ^ ((lr >> 1) & 7)) * 8);
   }
   // B: LDS row w*32 + i*8 + lrow  ->  chunk 2*tc + w/4, f = w%2, column-in-chunk ((w/2)%2)*32 + i*8 + lrow
   const int chunk_rel = min(2 * tc + (w >> 2), wv.n_chunks - 1);
   const uint16_t* b_src = ebase + (size_t)(wv.chunk0 + chunk_rel) * 3 * CHUNK_J * M +
                           (size_t)((w & 1) * CHUNK_J + ((w >> 1) & 1) * 32 + lrow) * M;
+  const int lc0 = lpp ^ (lrow >> 1);  // B piece for even i; odd i uses lc0 ^ 4
+  const int nk_total = M / BK;
+  const int rot = SI_ROTK ? (int)(((unsigned)L * 2654435761u >> 8) % (unsigned)nk_total) : 0;
 
-  f32x16 acc[4][2];
+  auto issue = [&](int stage, int kt) {
+    unsigned char* sa = lds + stage * S::STAGE + w * (BM / 8) * 128;
+    unsigned char* sb = lds + stage * S::STAGE + BM * 128 + w * 4096;
+    int kr = kt + rot; if (kr >= nk_total) kr -= nk_total;
+    const int k0 = kr * BK;
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-
-  auto issue = [&](int stage, int k0) {
-    unsigned char* sa = lds + stage * STAGE_BYTES + w * 4096;
-    unsigned char* sb = sa + BM * 128;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < S::ALD; ++i)
       __builtin_amdgcn_global_load_lds(SI_GPTR(a_src[i] + k0), SI_LPTR(sa + i * 1024), 16, 0, 0);
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
       __builtin_amdgcn_global_load_lds(SI_GPTR(b_src + (size_t)i * 8 * M + k0 + (((i & 1) ? (lc0 ^ 4) : lc0) * 8)),
                                        SI_LPTR(sb + i * 1024), 16, 0, 0);
-    }
   };
-  bf16x8 fa[2][4], fb[2][2];
-  auto ldfrag = [&](int stage, int ks, int buf) {
-    const unsigned char* sa = lds + stage * STAGE_BYTES;
-    const unsigned char* sb = sa + BM * 128;
-    const int pc = ks * 2 + (lane >> 5);
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-      fa[buf][i] = as_bf16x8(*reinterpret_cast<const u32x4*>(sa + swz(wr * 128 + i * 32 + (lane & 31), pc)));
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
-      fb[buf][j] = as_bf16x8(*reinterpret_cast<const u32x4*>(sb + swz(wc * 64 + j * 32 + (lane & 31), pc)));
-  };
-  auto mma = [&](int buf) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-      for (int j = 0; j < 2; ++j)
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[buf][i], fb[buf][j], acc[i][j], 0, 0, 0);
-  };
-  const int nk = M / BK;
-  issue(0, 0);
-  for (int it = 0; it < nk; ++it) {
-    const int s = it & 1;
-    __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): this wave's part of the tile has landed
-    __syncthreads();                     // ... and everybody's; all reads of the other stage are done
-    if (it + 1 < nk) issue(s ^ 1, (it + 1) * BK);
-    ldfrag(s, 0, 0);
-    ldfrag(s, 1, 1); mma(0);
-    ldfrag(s, 2, 0); mma(1);
-    ldfrag(s, 3, 1); mma(0);
-    mma(1);
-  }
+  SI_GEMM_MAIN_LOOP(M / BK, issue, SI_BOFF_SWZ)
   // epilogue: element (row 8*(r/4) + 4*(lane/32) + r%4, column lane%32) of each 32x32 tile;
   // acc[i][0] is the gate tile and acc[i][1] the up tile of the same 32 hidden columns
   const int jl = wc * 32 + (lane & 31);  // hidden column inside the 128-column tile
   if (2 * tc + (jl >> 6) < wv.n_chunks) {
     const int col = wv.col0 + tc * 128 + jl;
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < S::FA; ++i)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const int row = ti.row0 + wr * 128 + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+        const int row = ti.row0 + wr * (BM / 2) + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
         if (row < ti.row_end) hact[(size_t)row * ldh + col] = f32_to_bf16(silu_f(acc[i][0][r]) * acc[i][1][r]);
       }
   }
 }
 
 // ---------------------------------------------------------------------------------------------
-// FC2.  Tile: 256 rows x 256 output columns m; contraction over the hidden columns of this
+// FC2.  Tile: BM rows x 256 output columns m; contraction over the hidden columns of this
 // k-split's chunk range (one chunk = 64 per step).  B operand: the down block of a chunk is
 // [8 groups][M][8 j], i.e. already "8 consecutive k per (group, m)"; it is kept in that order in
 // LDS ([group][256 m] x 16 bytes), read conflict free by consecutive lanes.
 // Output slab `split` of yp: rows x M fp32; overwritten or accumulated.
 // ---------------------------------------------------------------------------------------------
+template <int BM>
 __global__ __launch_bounds__(THREADS, 1) void k_prefill_down(const uint16_t* __restrict__ hact, int ldh, int M, Plan p,
                                                              int expert_sel, int x2_only, int total_blocks,
                                                              int n_ntiles, int n_split, WeightView wv,
                                                              float* __restrict__ yp, size_t slab_stride,
                                                              int accumulate) {
+  using S = Shape<BM>;
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
   const int L = xcd_remap(blockIdx.x, total_blocks);
   int inner;
   TileInfo ti;
-  if (!decode_tile(p, expert_sel, x2_only, L, n_ntiles * n_split, inner, ti)) return;
+  if (!decode_tile<BM>(p, expert_sel, x2_only, L, n_ntiles * n_split, inner, ti)) return;
   const int nt = inner % n_ntiles, split = inner / n_ntiles;
   const int c_begin = (int)((long)wv.n_chunks * split / n_split), c_end = (int)((long)wv.n_chunks * (split + 1) / n_split);
+  if (c_begin >= c_end && accumulate) return;  // nothing to add
   const int tid = threadIdx.x, lane = tid % WAVE, w = tid / WAVE;
   const int wr = w >> 2, wc = w & 3;
   const int n0 = nt * BN;
@@ -211,83 +260,54 @@ __global__ __launch_bounds__(THREADS, 1) void k_prefill_down(const uint16_t* __r
   float* out = yp + (size_t)split * slab_stride;
 
   const int lrow = lane >> 3, lpp = lane & 7;
-  const int lc0 = lpp ^ (lrow >> 1);
-  const uint16_t* a_src[4];
+  const uint16_t* a_src[S::ALD];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    int row = ti.row0 + w * 32 + i * 8 + lrow;
+  for (int i = 0; i < S::ALD; ++i) {
+    const int lr = w * (BM / 8) + i * 8 + lrow;
+    int row = ti.row0 + lr;
     row = row < ti.row_end ? row : ti.row_end - 1;
-    a_src[i] = hact + (size_t)row * ldh + wv.col0 + (((i & 1) ? (lc0 ^ 4) : lc0) * 8);
+    a_src[i] = hact + (size_t)row * ldh + wv.col0 + ((lpp ^ ((lr >> 1) & 7)) * 8);
   }
   // B: wave w loads group g = w of the chunk's down block, 4 x 64 output columns
   size_t b_off[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) b_off[i] = ((size_t)w * M + min(n0 + i * 64 + lane, M - 1)) * 8;
 
-  f32x16 acc[4][2];
-#pragma unroll
-  for (int i = 0; i < 4; ++i)
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-
-  auto issue = [&](int stage, int c) {
-    unsigned char* sa = lds + stage * STAGE_BYTES + w * 4096;
-    unsigned char* sb = lds + stage * STAGE_BYTES + BM * 128 + w * 4096;
+  auto issue = [&](int stage, int kt) {
+    unsigned char* sa = lds + stage * S::STAGE + w * (BM / 8) * 128;
+    unsigned char* sb = lds + stage * S::STAGE + BM * 128 + w * 4096;
+    const int c = c_begin + kt;
     const uint16_t* dblk = ebase + (size_t)(wv.chunk0 + c) * 3 * CHUNK_J * M + (size_t)2 * CHUNK_J * M;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < S::ALD; ++i)
       __builtin_amdgcn_global_load_lds(SI_GPTR(a_src[i] + c * CHUNK_J), SI_LPTR(sa + i * 1024), 16, 0, 0);
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
       __builtin_amdgcn_global_load_lds(SI_GPTR(dblk + b_off[i]), SI_LPTR(sb + i * 1024), 16, 0, 0);
-    }
   };
-  bf16x8 fa[2][4], fb[2][2];
-  auto ldfrag = [&](int stage, int ks, int buf) {
-    const unsigned char* sa = lds + stage * STAGE_BYTES;
-    const unsigned char* sb = sa + BM * 128;
-    const int pc = ks * 2 + (lane >> 5);
+  if (c_begin < c_end) {
+    SI_GEMM_MAIN_LOOP(c_end - c_begin, issue, SI_BOFF_K8)
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
-      fa[buf][i] = as_bf16x8(*reinterpret_cast<const u32x4*>(sa + swz(wr * 128 + i * 32 + (lane & 31), pc)));
+    for (int i = 0; i < S::FA; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
-      fb[buf][j] = as_bf16x8(*reinterpret_cast<const u32x4*>(sb + (pc * BN + wc * 64 + j * 32 + (lane & 31)) * 16));
-  };
-  auto mma = [&](int buf) {
+      for (int j = 0; j < 2; ++j) {
+        const int m = n0 + wc * 64 + j * 32 + (lane & 31);
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-      for (int j = 0; j < 2; ++j)
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[buf][i], fb[buf][j], acc[i][j], 0, 0, 0);
-  };
-  if (c_begin < c_end) issue(0, c_begin);
-  for (int c = c_begin; c < c_end; ++c) {
-    const int s = (c - c_begin) & 1;
-    __builtin_amdgcn_s_waitcnt(0x0f70);
-    __syncthreads();
-    if (c + 1 < c_end) issue(s ^ 1, c + 1);
-    ldfrag(s, 0, 0);
-    ldfrag(s, 1, 1); mma(0);
-    ldfrag(s, 2, 0); mma(1);
-    ldfrag(s, 3, 1); mma(0);
-    mma(1);
-  }
-  if (c_begin >= c_end && accumulate) return;  // nothing to add
-#pragma unroll
-  for (int i = 0; i < 4; ++i)
-#pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      const int m = n0 + wc * 64 + j * 32 + (lane & 31);
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int row = ti.row0 + wr * 128 + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-        if (row < ti.row_end && m < M) {
-          float* dst = out + (size_t)row * M + m;
-          *dst = accumulate ? *dst + acc[i][j][r] : acc[i][j][r];
+        for (int r = 0; r < 16; ++r) {
+          const int row = ti.row0 + wr * (BM / 2) + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+          if (row < ti.row_end && m < M) {
+            float* dst = out + (size_t)row * M + m;
+            *dst = accumulate ? *dst + acc[i][j][r] : acc[i][j][r];
+          }
         }
       }
+  } else {
+    // an empty k-split of an overwriting launch still has to define its slab
+    for (int i = tid; i < BM * BN; i += THREADS) {
+      const int row = ti.row0 + i / BN, m = n0 + i % BN;
+      if (row < ti.row_end && m < M) out[(size_t)row * M + m] = 0.f;
     }
+  }
 }
 
 __global__ __launch_bounds__(256) void k_prefill_combine(const float* __restrict__ yp, size_t slab_stride, int n_split,
@@ -330,16 +350,23 @@ __global__ void k_fill_zero(float* __restrict__ p, size_t n) {
 
 }  // namespace
 
+template <int BM> static hipError_t set_lds_attr() {
+  hipError_t e = hipFuncSetAttribute((const void*)k_prefill_gateup<BM>, hipFuncAttributeMaxDynamicSharedMemorySize, Shape<BM>::LDS);
+  if (e != hipSuccess) return e;
+  return hipFuncSetAttribute((const void*)k_prefill_down<BM>, hipFuncAttributeMaxDynamicSharedMemorySize, Shape<BM>::LDS);
+}
+
 static hipError_t ensure_lds_attr() {
   static hipError_t st = [] {
-    hipError_t e = hipFuncSetAttribute((const void*)k_prefill_gateup, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
-    if (e != hipSuccess) return e;
-    return hipFuncSetAttribute((const void*)k_prefill_down, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+    hipError_t e = set_lds_attr<256>();
+    if (e == hipSuccess) e = set_lds_attr<128>();
+    if (e == hipSuccess) e = set_lds_attr<64>();
+    return e;
   }();
   return st;
 }
 
-hipError_t launch_prefill_gateup(const uint16_t* x, int M, const Plan& plan, int expert_sel, int x2_only,
+hipError_t launch_prefill_gateup(const uint16_t* x, int M, const Plan& plan, int bm, int expert_sel, int x2_only,
                                  int n_row_tiles, const WeightView& wv, uint16_t* hact, int ldh,
                                  hipStream_t stream) {
   if (wv.n_chunks <= 0 || n_row_tiles <= 0) return hipSuccess;
@@ -347,21 +374,33 @@ hipError_t launch_prefill_gateup(const uint16_t* x, int M, const Plan& plan, int
   if (e != hipSuccess) return e;
   const int n_ctiles = (wv.n_chunks + 1) / 2;
   const int total = (n_row_tiles * n_ctiles + 7) / 8 * 8;
-  hipLaunchKernelGGL(k_prefill_gateup, dim3(total), dim3(THREADS), LDS_BYTES, stream, x, M, plan, expert_sel, x2_only,
-                     total, n_ctiles, wv, hact, ldh);
+#define SI_LAUNCH_GU(BMV)                                                                                          \
+  hipLaunchKernelGGL(k_prefill_gateup<BMV>, dim3(total), dim3(THREADS), Shape<BMV>::LDS, stream, x, M, plan,        \
+                     expert_sel, x2_only, total, n_ctiles, wv, hact, ldh)
+  if (bm == 256) SI_LAUNCH_GU(256);
+  else if (bm == 128) SI_LAUNCH_GU(128);
+  else if (bm == 64) SI_LAUNCH_GU(64);
+  else return hipErrorInvalidValue;
+#undef SI_LAUNCH_GU
   return hipGetLastError();
 }
 
-hipError_t launch_prefill_down(const uint16_t* hact, int ldh, int M, const Plan& plan, int expert_sel, int x2_only,
-                               int n_row_tiles, const WeightView& wv, float* yp, size_t slab_stride, int n_split,
-                               int accumulate, hipStream_t stream) {
+hipError_t launch_prefill_down(const uint16_t* hact, int ldh, int M, const Plan& plan, int bm, int expert_sel,
+                               int x2_only, int n_row_tiles, const WeightView& wv, float* yp, size_t slab_stride,
+                               int n_split, int accumulate, hipStream_t stream) {
   if (wv.n_chunks <= 0 || n_row_tiles <= 0) return hipSuccess;
   hipError_t e = ensure_lds_attr();
   if (e != hipSuccess) return e;
   const int n_ntiles = (M + BN - 1) / BN;
   const int total = (n_row_tiles * n_ntiles * n_split + 7) / 8 * 8;
-  hipLaunchKernelGGL(k_prefill_down, dim3(total), dim3(THREADS), LDS_BYTES, stream, hact, ldh, M, plan, expert_sel,
-                     x2_only, total, n_ntiles, n_split, wv, yp, slab_stride, accumulate);
+#define SI_LAUNCH_DN(BMV)                                                                                          \
+  hipLaunchKernelGGL(k_prefill_down<BMV>, dim3(total), dim3(THREADS), Shape<BMV>::LDS, stream, hact, ldh, M, plan,  \
+                     expert_sel, x2_only, total, n_ntiles, n_split, wv, yp, slab_stride, accumulate)
+  if (bm == 256) SI_LAUNCH_DN(256);
+  else if (bm == 128) SI_LAUNCH_DN(128);
+  else if (bm == 64) SI_LAUNCH_DN(64);
+  else return hipErrorInvalidValue;
+#undef SI_LAUNCH_DN
   return hipGetLastError();
 }
 

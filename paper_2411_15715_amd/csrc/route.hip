@@ -48,8 +48,6 @@ __device__ void topk_token(const float* __restrict__ l, int E, int k, int lane, 
     if ((bi & (WAVE - 1)) == lane) taken |= 1u << (bi / WAVE);
     if (lane == 0) { idx_out[s] = bi; sel[s] = bv; }
   }
-  __builtin_amdgcn_wave_barrier();
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
   if (lane == 0) {
     // softmax over the k selected logits; sel[0] is the maximum.  Sequential, slot order.
     float l0 = sel[0];
@@ -74,8 +72,8 @@ __global__ void k_dense_assign(int T, int32_t* __restrict__ idx, float* __restri
 }
 
 // Single block.  Builds count/off/perm/inv and the launch tables from idx.
-__global__ __launch_bounds__(ROUTE_THREADS) void k_assign(int T, int E, int k, int has_shared, int n_x1, int bm,
-                                                          Plan p, RouteOut u) {
+__device__ __forceinline__ void assign_body(int T, int E, int k, int has_shared, int n_x1, int bm, const Plan& p,
+                                            const RouteOut& u) {
   __shared__ int s_count[MAX_EXPERTS + 2];
   __shared__ int s_count1[MAX_EXPERTS + 2];
   __shared__ int s_off[MAX_EXPERTS + 3];
@@ -181,6 +179,32 @@ __global__ __launch_bounds__(ROUTE_THREADS) void k_assign(int T, int E, int k, i
     for (int t = tid; t < T; t += ROUTE_THREADS) p.row_token[n_pairs + t] = t;
 }
 
+__global__ __launch_bounds__(ROUTE_THREADS) void k_assign(int T, int E, int k, int has_shared, int n_x1, int bm,
+                                                          Plan p, RouteOut u) {
+  assign_body(T, E, k, has_shared, n_x1, bm, p, u);
+}
+
+// Few tokens (generation phase): selection and assignment in one launch.  Wave v of the block takes
+// tokens v, v + 16, ...; the assignment then runs on the whole block.
+__global__ __launch_bounds__(ROUTE_THREADS) void k_route_small(const float* __restrict__ logits, int T, int E, int k,
+                                                               int has_shared, int n_x1, int bm, Plan p, RouteOut u) {
+  __shared__ float sel[ROUTE_THREADS / WAVE][MAX_EXPERTS];
+  const int wv = threadIdx.x / WAVE, lane = threadIdx.x % WAVE;
+  if (logits) {
+    for (int t = wv; t < T; t += ROUTE_THREADS / WAVE)
+      topk_token(logits + (size_t)t * E, E, k, lane, p.idx + (size_t)t * k, p.w + (size_t)t * k, sel[wv]);
+  } else {
+    for (int t = threadIdx.x; t < T; t += ROUTE_THREADS) { p.idx[t] = 0; p.w[t] = 1.f; }
+  }
+  __syncthreads();
+  if (u.idx || u.w)
+    for (int i = threadIdx.x; i < T * k; i += ROUTE_THREADS) {
+      if (u.idx) u.idx[i] = p.idx[i];
+      if (u.w) u.w[i] = p.w[i];
+    }
+  assign_body(T, E, k, has_shared, n_x1, bm, p, u);
+}
+
 __global__ void k_copy_user(int n, const int32_t* __restrict__ idx, const float* __restrict__ w, int32_t* uidx,
                             float* uw) {
   int i = blockIdx.x * blockDim.x + threadIdx.x;
@@ -195,6 +219,11 @@ __global__ void k_copy_user(int n, const int32_t* __restrict__ idx, const float*
 hipError_t launch_route(const float* logits, int T, int E, int k, int has_shared, int n_g, int bm,
                         const Plan& plan, const RouteOut& user, hipStream_t stream) {
   if (T <= 0) return hipSuccess;
+  if (T <= 64) {
+    hipLaunchKernelGGL(k_route_small, dim3(1), dim3(ROUTE_THREADS), 0, stream, logits, T, E, k, has_shared, T - n_g, bm,
+                       plan, user);
+    return hipGetLastError();
+  }
   if (logits) {
     hipLaunchKernelGGL(k_topk, dim3((T + 3) / 4), dim3(256), 0, stream, logits, T, E, k, plan.idx, plan.w);
   } else {

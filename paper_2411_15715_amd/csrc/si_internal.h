@@ -23,9 +23,9 @@ inline size_t chunk_bytes(int M) { return chunk_elems(M) * 2; }
 
 constexpr int MAX_EXPERTS = 256;      // routed experts (a shared expert adds one more table entry)
 constexpr int ROUTE_THREADS = 1024;   // block size of the assignment kernel
-constexpr int PREFILL_BM = 256;       // token rows per GEMM tile (row-tile table granularity)
+constexpr int PREFILL_BM_MAX = 256;   // largest row tile of the prefill GEMMs (also 128 and 64)
 constexpr int MAX_KSPLIT = 4;         // k-splits (output slabs) of the prefill down projection
-constexpr int DECODE_TB = 4;          // tokens handled per weight pass in the GEMV kernels
+constexpr int DECODE_TB = 4;          // most tokens handled per weight pass in the GEMV kernels
 constexpr int DOWN_SLOTS = 16;        // j-splits of the decode down projection per part
 
 // Device-side result of the token assignment plus the launch tables derived from it.
@@ -74,10 +74,11 @@ struct WeightView {
 // h[row][j] = SiLU(x_row . Wg[j]) * (x_row . Wu[j]) for the rows of the selected experts.
 //  expert_sel < 0: all touched experts (table lookup);  >= 0: only that expert.
 //  x2_only: restrict to rows of X2 tokens (CG').
-hipError_t launch_decode_gateup(const uint16_t* x, int M, const Plan& plan, int EX, int expert_sel, int x2_only,
+//  tb_hint: upper bound on the rows of one expert (T); picks the tokens-per-pass instantiation (1, 2 or 4).
+hipError_t launch_decode_gateup(const uint16_t* x, int M, const Plan& plan, int tb_hint, int expert_sel, int x2_only,
                                 int max_touched, const WeightView& wv, float* h, int ldh, hipStream_t stream);
 // part[slot][row][m] = sum over the j of the slot of h[row][j] * Wd[j][m]
-hipError_t launch_decode_down(const float* h, int ldh, int M, const Plan& plan, int EX, int expert_sel, int x2_only,
+hipError_t launch_decode_down(const float* h, int ldh, int M, const Plan& plan, int tb_hint, int expert_sel, int x2_only,
                               int max_touched, const WeightView& wv, int slot0, int chunks_per_slot,
                               float* part, size_t slot_stride, hipStream_t stream);
 // y[t][m] = sum_s w[t][s] * sum_slots part[slot][inv[t*k+s]][m] + shared rows + ycc[t][m]
@@ -91,13 +92,14 @@ struct DecodeCombineArgs {
 hipError_t launch_decode_combine(const DecodeCombineArgs& a, const Plan& plan, float* y, hipStream_t stream);
 
 // prefill.hip --------------------------------------------------------------------------------
-// Hact[row][c] (bf16) for c in [0, 64*n_chunks): SwiGLU of the gate/up products (MFMA, fp32 acc)
-hipError_t launch_prefill_gateup(const uint16_t* x, int M, const Plan& plan, int expert_sel, int x2_only,
+// Hact[row][c] (bf16) for c in [0, 64*n_chunks): SwiGLU of the gate/up products (MFMA, fp32 acc).
+// bm: rows per tile (256, 128 or 64); launches over all experts need the row-tile tables built for the same bm.
+hipError_t launch_prefill_gateup(const uint16_t* x, int M, const Plan& plan, int bm, int expert_sel, int x2_only,
                                  int n_row_tiles, const WeightView& wv, uint16_t* hact, int ldh,
                                  hipStream_t stream);
 // Yp[split][row][m] (fp32) (+)= Hact[row][chunks of the split] . Wd[chunks][m]; the chunk range of the launch is
 // cut into n_split equal parts, each with its own output slab (summed by the combine kernel)
-hipError_t launch_prefill_down(const uint16_t* hact, int ldh, int M, const Plan& plan, int expert_sel,
+hipError_t launch_prefill_down(const uint16_t* hact, int ldh, int M, const Plan& plan, int bm, int expert_sel,
                                int x2_only, int n_row_tiles, const WeightView& wv, float* yp, size_t slab_stride,
                                int n_split, int accumulate, hipStream_t stream);
 // y[t][m] = sum_s w[t][s]*Yp[inv[t*k+s]][m] + Yp[T*k+t][m] (shared) + ycc[t][m] (X1 rows)
