@@ -179,9 +179,11 @@ int si_layer_set_profiling(si_layer_t* layer, int32_t on);
  *
  * si_repack_chunks: the storage transform of the Memory Manager for one expert.  Source HOST bf16
  * w_gate/w_up/w_down [d_ff][d_model]; writes chunks [chunk0, chunk0+n_chunks) (64 hidden columns
- * each) to `out` (HOST, n_chunks * 3*64*d_model elements).  One chunk is
- *   [ gate rows j0..j0+63 | up rows j0..j0+63 | down block ],  down block[q][m][i] = Wd[j0+8q+i][m]
- * (q < 8, i < 8), i.e. the contraction index of FC2 made contiguous in groups of 8.
+ * each) to `out` (HOST, n_chunks * 3*64*d_model elements).  One chunk is [ gate | up | down ] with
+ *   gate / up block [M/PW][64 j][PW m]   (PW = largest power of two <= 512 dividing d_model)
+ *   down block      [M/NW][8 q][NW m][8 i] = Wd[j0 + 8q + i][m]   (NW likewise, <= 256)
+ * i.e. FC1 rows cut into panels along the contraction index m, and the contraction index j of FC2
+ * made contiguous in groups of 8 inside tiles of NW output columns.
  *
  * si_cc_compute: what the CC workers do (Stream-A, Section III-C): for tokens t < T1
  *   ycc[t] = sum_s w[t][s] * MLP^CC_{idx[t][s]}(x[t])  (+ the shared expert's CC columns),

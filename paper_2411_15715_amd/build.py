@@ -14,7 +14,7 @@ HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 HIP_SOURCES = ["route.hip", "decode.hip", "prefill.hip", "layer.hip"]
 CPP_SOURCES = ["cc_worker.cpp"]
-HIP_FLAGS = (["-DSI_ROTK=1"] if os.environ.get("SI_ROTK") else []) + ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang",
+HIP_FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang",
              "-packed-fp32-ops", "-Wno-unused-command-line-argument", "-I", os.path.join(ROOT, "include"), "-I", CSRC]
 CPP_FLAGS = ["-O3", "-std=c++17", "-fPIC", "-mavx2", "-mfma", "-pthread", "-I", os.path.join(ROOT, "include"), "-I", CSRC]
 

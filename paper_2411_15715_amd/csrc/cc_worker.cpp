@@ -126,6 +126,7 @@ class CcPool {
   void run_item(const Item& it, std::vector<float>& xf, std::vector<float>& hbuf) {
     const CcJob& j = job_;
     const int M = j.M;
+    const int PW = panel_width(M), NW = ntile_width(M);
     const uint16_t* ebase = it.expert < j.E ? j.routed + (size_t)it.expert * j.expert_stride : j.shared;
     xf.resize((size_t)RB * M);
     for (int r = 0; r < it.nrows; ++r) {
@@ -140,14 +141,15 @@ class CcPool {
     hbuf.resize((size_t)RB * CHUNK_J);
     for (int c = it.c0; c < it.c1; ++c) {
       const uint16_t* cb = ebase + (size_t)c * 3 * CHUNK_J * M;
-      // FC1 + activation
+      // FC1 + activation (gate / up blocks: [M/PW panels][64 j][PW m])
       for (int jj = 0; jj < CHUNK_J; ++jj) {
-        const uint16_t* gr = cb + (size_t)jj * M;
-        const uint16_t* ur = cb + (size_t)(CHUNK_J + jj) * M;
+        const uint16_t* gblk = cb;
+        const uint16_t* ublk = cb + (size_t)CHUNK_J * M;
         v8f ag[RB], au[RB];
         for (int r = 0; r < RB; ++r) { ag[r] = v8f{0, 0, 0, 0, 0, 0, 0, 0}; au[r] = ag[r]; }
         for (int m = 0; m < M; m += 8) {
-          v8f wg = bf16x8_to_f32(gr + m), wu = bf16x8_to_f32(ur + m);
+          const size_t wo = gu_off(jj, m, PW);
+          v8f wg = bf16x8_to_f32(gblk + wo), wu = bf16x8_to_f32(ublk + wo);
           for (int r = 0; r < it.nrows; ++r) {
             v8f xv;
             std::memcpy(&xv, &xf[(size_t)r * M + m], sizeof xv);
@@ -157,11 +159,11 @@ class CcPool {
         }
         for (int r = 0; r < it.nrows; ++r) hbuf[(size_t)r * CHUNK_J + jj] = silu_f(hsum(ag[r])) * hsum(au[r]);
       }
-      // FC2: down block [8 groups][M][8 j]
+      // FC2: down block [M/NW tiles][8 q][NW m][8 i]
       const uint16_t* db = cb + (size_t)2 * CHUNK_J * M;
       for (int m = 0; m < M; ++m) {
         v8f wd[8];
-        for (int q = 0; q < 8; ++q) wd[q] = bf16x8_to_f32(db + ((size_t)q * M + m) * 8);
+        for (int q = 0; q < 8; ++q) wd[q] = bf16x8_to_f32(db + dn_off(q * 8, m, NW));
         for (int r = 0; r < it.nrows; ++r) {
           v8f a = v8f{0, 0, 0, 0, 0, 0, 0, 0};
           for (int q = 0; q < 8; ++q) {

@@ -55,8 +55,10 @@ __global__ __launch_bounds__(GU_THREADS) void k_decode_gateup(const uint16_t* __
   const int chunk = wv.chunk0 + blockIdx.x / blocks_per_chunk;
   const int jj0 = (blockIdx.x % blocks_per_chunk) * GU_JPB + wid * GU_JPW;  // first j of this wave in the chunk
   const uint16_t* cbase = wv.base + (size_t)e * wv.expert_stride + (size_t)chunk * 3 * CHUNK_J * M;
-  const u32x4* grow = reinterpret_cast<const u32x4*>(cbase + (size_t)jj0 * M);
-  const u32x4* urow = reinterpret_cast<const u32x4*>(cbase + (size_t)(CHUNK_J + jj0) * M);
+  // gate / up blocks are [M/PW panels][64 j][PW m]: one wave load = 512 contiguous m of one row
+  const u32x4* gblk = reinterpret_cast<const u32x4*>(cbase);
+  const u32x4* ublk = reinterpret_cast<const u32x4*>(cbase + (size_t)CHUNK_J * M);
+  const int PW = panel_width(M), PW8 = PW / 8;
   const int jcol = wv.col0 + (blockIdx.x / blocks_per_chunk) * CHUNK_J + jj0;
 
   for (int rb = r0; rb < r1; rb += TB) {
@@ -75,10 +77,11 @@ __global__ __launch_bounds__(GU_THREADS) void k_decode_gateup(const uint16_t* __
       for (int tb = 0; tb < TB; ++tb) { ag[j][tb] = 0.f; au[j][tb] = 0.f; }
     for (int c = lane; c < M8; c += WAVE) {
       u32x4 wg[GU_JPW], wu[GU_JPW];
+      const size_t poff = (size_t)(c / PW8) * CHUNK_J * PW8 + (c % PW8);  // panel base + position in the row segment
 #pragma unroll
       for (int j = 0; j < GU_JPW; ++j) {
-        wg[j] = __builtin_nontemporal_load(grow + (size_t)j * M8 + c);
-        wu[j] = __builtin_nontemporal_load(urow + (size_t)j * M8 + c);
+        wg[j] = __builtin_nontemporal_load(gblk + poff + (size_t)(jj0 + j) * PW8);
+        wu[j] = __builtin_nontemporal_load(ublk + poff + (size_t)(jj0 + j) * PW8);
       }
 #pragma unroll
       for (int tb = 0; tb < TB; ++tb) {
@@ -129,6 +132,7 @@ __global__ __launch_bounds__(DN_THREADS) void k_decode_down(const float* __restr
   const int m = blockIdx.x * DN_THREADS + threadIdx.x;
   const bool active = m < M;
   const int mm = active ? m : 0;
+  const int NW = ntile_width(M);
   const uint16_t* ebase = wv.base + (size_t)e * wv.expert_stride;
   float* out = part + (size_t)(slot0 + s) * slot_stride;
 
@@ -150,9 +154,9 @@ __global__ __launch_bounds__(DN_THREADS) void k_decode_down(const float* __restr
     for (int c = c_begin; c < c_end; ++c) {
       const u32x4* dblk = reinterpret_cast<const u32x4*>(ebase + (size_t)(wv.chunk0 + c) * 3 * CHUNK_J * M +
                                                          (size_t)2 * CHUNK_J * M);
-      u32x4 wd[8];
+      u32x4 wd[8];  // down block [M/NW tiles][8 q][NW m][8 i]: 16 bytes per (q, m)
 #pragma unroll
-      for (int q = 0; q < 8; ++q) wd[q] = __builtin_nontemporal_load(dblk + (size_t)q * M + mm);
+      for (int q = 0; q < 8; ++q) wd[q] = __builtin_nontemporal_load(dblk + ((size_t)(mm / NW) * 8 + q) * NW + (mm % NW));
 #pragma unroll
       for (int tb = 0; tb < TB; ++tb) {
         if (tb < nt) {

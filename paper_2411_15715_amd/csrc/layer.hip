@@ -60,20 +60,23 @@ int split_counts(int H, int g, float r_gg, float r_cg, int* n_gg, int* n_cg, int
   return 0;
 }
 
-// one expert [H][M] x3 -> chunk-major chunks [c0, c1) written at dst (see si_internal.h)
+// one expert [H][M] x3 -> chunk-major chunks [c0, c1) written at dst (layout: cc_worker.h)
 void repack_chunks(const uint16_t* wg, const uint16_t* wu, const uint16_t* wd, int M, int c0, int c1, uint16_t* dst) {
+  const int PW = panel_width(M), NW = ntile_width(M);
   for (int c = c0; c < c1; ++c) {
     uint16_t* o = dst + (size_t)(c - c0) * 3 * CHUNK_J * M;
-    std::memcpy(o, wg + (size_t)c * CHUNK_J * M, (size_t)CHUNK_J * M * 2);
-    std::memcpy(o + (size_t)CHUNK_J * M, wu + (size_t)c * CHUNK_J * M, (size_t)CHUNK_J * M * 2);
+    for (int f = 0; f < 2; ++f) {
+      const uint16_t* src = (f ? wu : wg) + (size_t)c * CHUNK_J * M;
+      uint16_t* blk = o + (size_t)f * CHUNK_J * M;
+      for (int j = 0; j < CHUNK_J; ++j)
+        for (int m = 0; m < M; m += PW) std::memcpy(blk + gu_off(j, m, PW), src + (size_t)j * M + m, (size_t)PW * 2);
+    }
     uint16_t* d = o + (size_t)2 * CHUNK_J * M;
     const uint16_t* src = wd + (size_t)c * CHUNK_J * M;
-    for (int q = 0; q < 8; ++q)
-      for (int jj = 0; jj < 8; ++jj) {
-        const uint16_t* row = src + (size_t)(q * 8 + jj) * M;
-        uint16_t* oq = d + (size_t)q * M * 8 + jj;
-        for (int m = 0; m < M; ++m) oq[(size_t)m * 8] = row[m];
-      }
+    for (int j = 0; j < CHUNK_J; ++j) {
+      const uint16_t* row = src + (size_t)j * M;
+      for (int m = 0; m < M; ++m) d[dn_off(j, m, NW)] = row[m];
+    }
   }
 }
 

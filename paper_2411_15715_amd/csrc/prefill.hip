@@ -23,9 +23,6 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 #define SI_GPTR(p) ((const void __attribute__((address_space(1)))*)(p))
 #define SI_LPTR(p) ((void __attribute__((address_space(3)))*)(p))
 
-#ifndef SI_ROTK
-#define SI_ROTK 0
-#endif
 constexpr int WAVE = 64;
 constexpr int THREADS = 512;
 constexpr int BN = 256;  // B rows per tile: 128 hidden columns (gate+up) or 256 output columns
@@ -61,6 +58,8 @@ __device__ inline int swz(int r, int c) { return r * 128 + ((c ^ ((r >> 1) & 7))
 template <int N> __device__ inline void wait_vmcnt() {
   __builtin_amdgcn_s_waitcnt(0x0f70 | (N & 0xf) | (((N >> 4) & 3) << 14));
 }
+
+__device__ inline void wait_lgkmcnt0() { __builtin_amdgcn_s_waitcnt(0xc07f); }  // lgkmcnt(0) only
 
 // Workgroup barrier WITHOUT the memory fence of __syncthreads(): the fence would drain every outstanding
 // global->LDS load (s_waitcnt vmcnt(0)) and so defeat the multi-stage ring.  What has to be visible
@@ -118,9 +117,11 @@ __device__ inline bool decode_tile(const Plan& p, int expert_sel, int x2_only, i
 // ---------------------------------------------------------------------------------------------
 // The two GEMM kernels share their main loop.  8 waves as 2 (rows) x 4 (B-row quarters of 64);
 // wave tile (BM/2) x 64: FA A-fragments x 2 B-fragments of v_mfma_f32_32x32x16_bf16.
-// Ring of NST stages: the loads of k-tile it + NST - 1 are issued right after the barrier of
-// iteration it (the slot was last read in iteration it - 1); the wait at the top leaves the
-// (NST - 2) younger tiles in flight.
+// Ring of NST stages holding k-tiles it .. it+NST-1.  The one barrier of an iteration sits before
+// its last k-step: by then every fragment of stage `st` is in registers, so after the barrier the
+// stage is refilled (tile it+NST) and the first fragments of the next stage are fetched while the
+// last 8 MFMAs of this iteration run; the wait before the barrier leaves the NST-2 youngest tiles in
+// flight.
 // ---------------------------------------------------------------------------------------------
 #define SI_GEMM_MAIN_LOOP(NK, ISSUE, BFRAG_OFF)                                                                  \
   f32x16 acc[S::FA][2];                                                                                          \
@@ -142,20 +143,27 @@ __device__ inline bool decode_tile(const Plan& p, int expert_sel, int x2_only, i
   };                                                                                                             \
   {                                                                                                              \
     const int nk_ = (NK);                                                                                        \
-    _Pragma("unroll") for (int s0 = 0; s0 < S::NST - 1; ++s0) if (s0 < nk_) ISSUE(s0, s0);                       \
-    int st = 0, fill = S::NST - 1;                                                                               \
+    _Pragma("unroll") for (int s0 = 0; s0 < S::NST; ++s0) if (s0 < nk_) ISSUE(s0, s0);                           \
+    if (S::NST - 1 < nk_) wait_vmcnt<(S::NST - 1) * S::LPW>(); else wait_vmcnt<0>();                             \
+    block_barrier();                                                                                             \
+    ldfrag(0, 0, 0);                                                                                             \
+    int st = 0;                                                                                                  \
     for (int it = 0; it < nk_; ++it) {                                                                           \
-      if (it + S::NST - 2 < nk_) wait_vmcnt<(S::NST - 2) * S::LPW>();                                            \
-      else wait_vmcnt<0>();                                                                                      \
-      block_barrier();                                                                                           \
-      if (it + S::NST - 1 < nk_) ISSUE(fill, it + S::NST - 1);                                                   \
-      ldfrag(st, 0, 0);                                                                                          \
+      const int nx = st + 1 == S::NST ? 0 : st + 1;                                                              \
       ldfrag(st, 1, 1); mma(0);                                                                                  \
       ldfrag(st, 2, 0); mma(1);                                                                                  \
       ldfrag(st, 3, 1); mma(0);                                                                                  \
+      /* tile it+1 must have landed for every wave and every read of stage st must be complete before the   */   \
+      /* barrier: after it stage nx is read and stage st is refilled with tile it+NST                       */   \
+      if (it + S::NST - 1 < nk_) wait_vmcnt<(S::NST - 2) * S::LPW>(); else wait_vmcnt<0>();                      \
+      wait_lgkmcnt0();                                                                                           \
+      block_barrier();                                                                                           \
+      if (it + 1 < nk_) ldfrag(nx, 0, 0);                                                                        \
+      if (it + S::NST < nk_) ISSUE(st, it + S::NST);                                                             \
+      __builtin_amdgcn_s_setprio(1);                                                                             \
       mma(1);                                                                                                    \
-      st = st + 1 == S::NST ? 0 : st + 1;                                                                        \
-      fill = fill + 1 == S::NST ? 0 : fill + 1;                                                                  \
+      __builtin_amdgcn_s_setprio(0);                                                                             \
+      st = nx;                                                                                                   \
     }                                                                                                            \
   }
 
@@ -194,26 +202,27 @@ __global__ __launch_bounds__(THREADS, 1) void k_prefill_gateup(const uint16_t* _
     row = row < ti.row_end ? row : ti.row_end - 1;
     a_src[i] = x + (size_t)p.row_token[row] * M + ((lpp ^ ((lr >> 1) & 7)) * 8);
   }
-  // B: LDS row w*32 + i*8 + lrow  ->  chunk 2*tc + w/4, f = w%2, column-in-chunk ((w/2)%2)*32 + i*8 + lrow
+  // B: LDS row w*32 + i*8 + lrow  ->  chunk 2*tc + w/4, f = w%2 (gate / up block), column-in-chunk
+  // jc = ((w/2)%2)*32 + i*8 + lrow.  Blocks are [M/PW panels][64 j][PW m] (cc_worker.h).
   const int chunk_rel = min(2 * tc + (w >> 2), wv.n_chunks - 1);
-  const uint16_t* b_src = ebase + (size_t)(wv.chunk0 + chunk_rel) * 3 * CHUNK_J * M +
-                          (size_t)((w & 1) * CHUNK_J + ((w >> 1) & 1) * 32 + lrow) * M;
+  const uint16_t* b_blk = ebase + (size_t)(wv.chunk0 + chunk_rel) * 3 * CHUNK_J * M + (size_t)(w & 1) * CHUNK_J * M;
+  const int jc0 = ((w >> 1) & 1) * 32 + lrow;
+  const int PW = panel_width(M);
   const int lc0 = lpp ^ (lrow >> 1);  // B piece for even i; odd i uses lc0 ^ 4
-  const int nk_total = M / BK;
-  const int rot = SI_ROTK ? (int)(((unsigned)L * 2654435761u >> 8) % (unsigned)nk_total) : 0;
 
   auto issue = [&](int stage, int kt) {
     unsigned char* sa = lds + stage * S::STAGE + w * (BM / 8) * 128;
     unsigned char* sb = lds + stage * S::STAGE + BM * 128 + w * 4096;
-    int kr = kt + rot; if (kr >= nk_total) kr -= nk_total;
-    const int k0 = kr * BK;
+    const int k0 = kt * BK;
 #pragma unroll
     for (int i = 0; i < S::ALD; ++i)
       __builtin_amdgcn_global_load_lds(SI_GPTR(a_src[i] + k0), SI_LPTR(sa + i * 1024), 16, 0, 0);
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
-      __builtin_amdgcn_global_load_lds(SI_GPTR(b_src + (size_t)i * 8 * M + k0 + (((i & 1) ? (lc0 ^ 4) : lc0) * 8)),
+    for (int i = 0; i < 4; ++i) {
+      const int m0 = k0 + (((i & 1) ? (lc0 ^ 4) : lc0) * 8);
+      __builtin_amdgcn_global_load_lds(SI_GPTR(b_blk + ((size_t)(m0 / PW) * CHUNK_J + jc0 + i * 8) * PW + (m0 % PW)),
                                        SI_LPTR(sb + i * 1024), 16, 0, 0);
+    }
   };
   SI_GEMM_MAIN_LOOP(M / BK, issue, SI_BOFF_SWZ)
   // epilogue: element (row 8*(r/4) + 4*(lane/32) + r%4, column lane%32) of each 32x32 tile;
@@ -268,10 +277,14 @@ __global__ __launch_bounds__(THREADS, 1) void k_prefill_down(const uint16_t* __r
     row = row < ti.row_end ? row : ti.row_end - 1;
     a_src[i] = hact + (size_t)row * ldh + wv.col0 + ((lpp ^ ((lr >> 1) & 7)) * 8);
   }
-  // B: wave w loads group g = w of the chunk's down block, 4 x 64 output columns
+  // B: wave w loads group q = w of the chunk's down block ([M/NW tiles][8 q][NW m][8 i]), 4 x 64 output columns
+  const int NW = ntile_width(M);
   size_t b_off[4];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) b_off[i] = ((size_t)w * M + min(n0 + i * 64 + lane, M - 1)) * 8;
+  for (int i = 0; i < 4; ++i) {
+    const int n = min(n0 + i * 64 + lane, M - 1);
+    b_off[i] = (((size_t)(n / NW) * 8 + w) * NW + (n % NW)) * 8;
+  }
 
   auto issue = [&](int stage, int kt) {
     unsigned char* sa = lds + stage * S::STAGE + w * (BM / 8) * 128;

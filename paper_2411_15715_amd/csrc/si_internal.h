@@ -8,16 +8,10 @@
 
 namespace si {
 
-// ---------------------------------------------------------------------------------------------
-// Weight storage.  One "chunk" holds SI_CHUNK_J = 64 consecutive hidden columns j of one expert:
-//   [ gate rows j0..j0+63 : 64 x M bf16 | up rows : 64 x M bf16 | down block : 8 x M x 8 bf16 ]
-// gate/up rows are contiguous in m (the contraction index of FC1); the down block stores, for each
-// group of 8 consecutive j and each m, the 8 values Wd[j0+8q+0..7][m] contiguously (16 bytes), so
-// that the contraction index of FC2 is contiguous too.  Both the decode GEMV (one 128-bit load per
-// lane) and the MFMA operand fetch (8 consecutive k per lane) read it without a transpose.
-// A part (CC, CG or GG) of an expert is a contiguous range of chunks, so a CG copy is one memcpy
-// and CG' is simply the CC chunk range of the same pinned buffer (Section III-B: same addresses).
-// ---------------------------------------------------------------------------------------------
+// Weight storage: see cc_worker.h (chunk-major; gate/up in 512-wide k panels, down in 256-column
+// tiles with the contraction index grouped by 8).  A part (CC, CG or GG) of an expert is a contiguous
+// range of chunks, so a CG copy is one memcpy and CG' is simply the CC chunk range of the same pinned
+// buffer (Section III-B: same addresses).
 inline size_t chunk_elems(int M) { return (size_t)3 * CHUNK_J * M; }
 inline size_t chunk_bytes(int M) { return chunk_elems(M) * 2; }
 

@@ -84,17 +84,36 @@ def test_create_without_gpu_reports_hip_error():
     assert "device" in si.si_last_error().lower()
 
 
-def test_repack_layout():
+def _panel_width(M):
+    p = 512
+    while M % p:
+        p //= 2
+    return p
+
+
+def _ntile_width(M):
+    p = 256
+    while M % p:
+        p //= 2
+    return p
+
+
+@pytest.mark.parametrize("M", [64, 192, 1024])
+def test_repack_layout(M):
+    """gate / up block: [M/PW panels][64 j][PW m]; down block: [M/NW tiles][8 q][NW m][8 i] = Wd[j0+8q+i][m]."""
     rng = np.random.default_rng(1)
-    H, M = 192, 64
+    H = 192
+    PW, NW = _panel_width(M), _ntile_width(M)
     wg, wu, wd = (rng.integers(0, 65535, (H, M), dtype=np.uint16) for _ in range(3))
     out = si.si_repack_chunks(wg, wu, wd, 1, 2).reshape(2, 3 * 64 * M)
     for ci, c in enumerate((1, 2)):
         blk = out[ci]
-        assert np.array_equal(blk[:64 * M].reshape(64, M), wg[c * 64:(c + 1) * 64])
-        assert np.array_equal(blk[64 * M:128 * M].reshape(64, M), wu[c * 64:(c + 1) * 64])
-        down = blk[128 * M:].reshape(8, M, 8)  # [q][m][i] = Wd[j0 + 8q + i][m]
-        ref = wd[c * 64:(c + 1) * 64].reshape(8, 8, M).transpose(0, 2, 1)
+        for f, src in enumerate((wg, wu)):
+            panels = blk[f * 64 * M:(f + 1) * 64 * M].reshape(M // PW, 64, PW)
+            ref = src[c * 64:(c + 1) * 64].reshape(64, M // PW, PW).transpose(1, 0, 2)
+            assert np.array_equal(panels, ref)
+        down = blk[128 * M:].reshape(M // NW, 8, NW, 8)  # [tile][q][m][i]
+        ref = wd[c * 64:(c + 1) * 64].reshape(8, 8, M // NW, NW).transpose(2, 0, 3, 1)
         assert np.array_equal(down, ref)
     with pytest.raises(si.ScheInferError):
         si.si_repack_chunks(wg, wu, wd, 2, 2)
