@@ -73,8 +73,13 @@ __device__ inline void block_barrier() {
 }
 
 // XCD-aware remap: consecutive hardware block ids go round-robin over the 8 XCDs; give each XCD a
-// contiguous range of logical ids so that blocks sharing weights share an L2.
-__device__ inline int xcd_remap(int b, int total) {
+// contiguous range of logical ids so that the row tiles that read the same weights share an L2.
+// In the first GEMM only for the 256-row tiles (several row tiles per expert, MFMA bound).  With the small tiles an
+// expert has one or two row tiles, nothing is shared, and the remap would make the 8 XCDs stream 8
+// regions of memory a whole expert apart (same low address bits): measured 453 -> 394 us on the
+// weight stream of the Mixtral-shaped gate/up GEMM without it.
+template <bool ON> __device__ inline int xcd_remap(int b, int total) {
+  if (!ON) return b;
   const int per = (total + 7) / 8;
   return (b % 8) * per + b / 8;
 }
@@ -183,7 +188,7 @@ __global__ __launch_bounds__(THREADS, 1) void k_prefill_gateup(const uint16_t* _
                                                                uint16_t* __restrict__ hact, int ldh) {
   using S = Shape<BM>;
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
-  const int L = xcd_remap(blockIdx.x, total_blocks);
+  const int L = xcd_remap<BM == 256>(blockIdx.x, total_blocks);
   int tc;
   TileInfo ti;
   if (!decode_tile<BM>(p, expert_sel, x2_only, L, n_ctiles, tc, ti)) return;
@@ -255,7 +260,7 @@ __global__ __launch_bounds__(THREADS, 1) void k_prefill_down(const uint16_t* __r
                                                              int accumulate) {
   using S = Shape<BM>;
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
-  const int L = xcd_remap(blockIdx.x, total_blocks);
+  const int L = xcd_remap<true>(blockIdx.x, total_blocks);  // one expert's Hact rows (A operand) stay in one L2
   int inner;
   TileInfo ti;
   if (!decode_tile<BM>(p, expert_sel, x2_only, L, n_ntiles * n_split, inner, ti)) return;
