@@ -182,16 +182,10 @@ __device__ inline bool decode_tile(const Plan& p, int expert_sel, int x2_only, i
 // registers from the two accumulator tiles of a wave.
 // ---------------------------------------------------------------------------------------------
 template <int BM>
-__global__ __launch_bounds__(THREADS, 1) void k_prefill_gateup(const uint16_t* __restrict__ x, int M, Plan p,
-                                                               int expert_sel, int x2_only, int total_blocks,
-                                                               int n_ctiles, WeightView wv,
-                                                               uint16_t* __restrict__ hact, int ldh) {
+__device__ __forceinline__ void gateup_body(const uint16_t* __restrict__ x, int M, const Plan& p, int tc, const TileInfo& ti,
+                                            const WeightView& wv, uint16_t* __restrict__ hact, int ldh,
+                                            unsigned char* lds) {
   using S = Shape<BM>;
-  extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
-  const int L = xcd_remap<BM == 256>(blockIdx.x, total_blocks);
-  int tc;
-  TileInfo ti;
-  if (!decode_tile<BM>(p, expert_sel, x2_only, L, n_ctiles, tc, ti)) return;
   const int tid = threadIdx.x, lane = tid % WAVE, w = tid / WAVE;
   const int wr = w >> 2, wc = w & 3;
   const uint16_t* ebase = wv.base + (size_t)ti.e * wv.expert_stride;
@@ -245,6 +239,29 @@ __global__ __launch_bounds__(THREADS, 1) void k_prefill_gateup(const uint16_t* _
   }
 }
 
+// Row tiles are laid out with 256 rows when experts have many rows; the last tile of an expert then
+// usually holds fewer: a block picks the body for the rows it really has (whole-block branch), so a
+// 40-row tail costs a 64-row tile, not a 256-row one.
+template <int BM>
+__global__ __launch_bounds__(THREADS, 1) void k_prefill_gateup(const uint16_t* __restrict__ x, int M, Plan p,
+                                                               int expert_sel, int x2_only, int total_blocks,
+                                                               int n_ctiles, WeightView wv,
+                                                               uint16_t* __restrict__ hact, int ldh) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+  const int L = xcd_remap<BM == 256>(blockIdx.x, total_blocks);
+  int tc;
+  TileInfo ti;
+  if (!decode_tile<BM>(p, expert_sel, x2_only, L, n_ctiles, tc, ti)) return;
+  if (BM == 256) {
+    const int rows = ti.row_end - ti.row0;
+    if (rows <= 64) gateup_body<64>(x, M, p, tc, ti, wv, hact, ldh, lds);
+    else if (rows <= 128) gateup_body<128>(x, M, p, tc, ti, wv, hact, ldh, lds);
+    else gateup_body<256>(x, M, p, tc, ti, wv, hact, ldh, lds);
+  } else {
+    gateup_body<BM>(x, M, p, tc, ti, wv, hact, ldh, lds);
+  }
+}
+
 // ---------------------------------------------------------------------------------------------
 // FC2.  Tile: BM rows x 256 output columns m; contraction over the hidden columns of this
 // k-split's chunk range (one chunk = 64 per step).  B operand: the down block of a chunk is
@@ -253,17 +270,10 @@ __global__ __launch_bounds__(THREADS, 1) void k_prefill_gateup(const uint16_t* _
 // Output slab `split` of yp: rows x M fp32; overwritten or accumulated.
 // ---------------------------------------------------------------------------------------------
 template <int BM>
-__global__ __launch_bounds__(THREADS, 1) void k_prefill_down(const uint16_t* __restrict__ hact, int ldh, int M, Plan p,
-                                                             int expert_sel, int x2_only, int total_blocks,
-                                                             int n_ntiles, int n_split, WeightView wv,
-                                                             float* __restrict__ yp, size_t slab_stride,
-                                                             int accumulate) {
+__device__ __forceinline__ void down_body(const uint16_t* __restrict__ hact, int ldh, int M, int inner, const TileInfo& ti,
+                                          int n_ntiles, int n_split, const WeightView& wv, float* __restrict__ yp,
+                                          size_t slab_stride, int accumulate, unsigned char* lds) {
   using S = Shape<BM>;
-  extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
-  const int L = xcd_remap<true>(blockIdx.x, total_blocks);  // one expert's Hact rows (A operand) stay in one L2
-  int inner;
-  TileInfo ti;
-  if (!decode_tile<BM>(p, expert_sel, x2_only, L, n_ntiles * n_split, inner, ti)) return;
   const int nt = inner % n_ntiles, split = inner / n_ntiles;
   const int c_begin = (int)((long)wv.n_chunks * split / n_split), c_end = (int)((long)wv.n_chunks * (split + 1) / n_split);
   if (c_begin >= c_end && accumulate) return;  // nothing to add
@@ -328,6 +338,27 @@ __global__ __launch_bounds__(THREADS, 1) void k_prefill_down(const uint16_t* __r
   }
 }
 
+template <int BM>
+__global__ __launch_bounds__(THREADS, 1) void k_prefill_down(const uint16_t* __restrict__ hact, int ldh, int M, Plan p,
+                                                             int expert_sel, int x2_only, int total_blocks,
+                                                             int n_ntiles, int n_split, WeightView wv,
+                                                             float* __restrict__ yp, size_t slab_stride,
+                                                             int accumulate) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+  const int L = xcd_remap<true>(blockIdx.x, total_blocks);  // one expert's Hact rows (A operand) stay in one L2
+  int inner;
+  TileInfo ti;
+  if (!decode_tile<BM>(p, expert_sel, x2_only, L, n_ntiles * n_split, inner, ti)) return;
+  if (BM == 256) {
+    const int rows = ti.row_end - ti.row0;
+    if (rows <= 64) down_body<64>(hact, ldh, M, inner, ti, n_ntiles, n_split, wv, yp, slab_stride, accumulate, lds);
+    else if (rows <= 128) down_body<128>(hact, ldh, M, inner, ti, n_ntiles, n_split, wv, yp, slab_stride, accumulate, lds);
+    else down_body<256>(hact, ldh, M, inner, ti, n_ntiles, n_split, wv, yp, slab_stride, accumulate, lds);
+  } else {
+    down_body<BM>(hact, ldh, M, inner, ti, n_ntiles, n_split, wv, yp, slab_stride, accumulate, lds);
+  }
+}
+
 __global__ __launch_bounds__(256) void k_prefill_combine(const float* __restrict__ yp, size_t slab_stride, int n_split,
                                                          const float* __restrict__ ycc, int T, int k, int M, int n_x1,
                                                          int has_shared, Plan p, float* __restrict__ y) {
@@ -368,10 +399,15 @@ __global__ void k_fill_zero(float* __restrict__ p, size_t n) {
 
 }  // namespace
 
+// dynamic LDS of a launch: the 256-row kernels may run the smaller bodies on tail tiles
+template <int BM> constexpr int kernel_lds() {
+  return BM == 256 ? (Shape<128>::LDS > Shape<256>::LDS ? Shape<128>::LDS : Shape<256>::LDS) : Shape<BM>::LDS;
+}
+
 template <int BM> static hipError_t set_lds_attr() {
-  hipError_t e = hipFuncSetAttribute((const void*)k_prefill_gateup<BM>, hipFuncAttributeMaxDynamicSharedMemorySize, Shape<BM>::LDS);
+  hipError_t e = hipFuncSetAttribute((const void*)k_prefill_gateup<BM>, hipFuncAttributeMaxDynamicSharedMemorySize, kernel_lds<BM>());
   if (e != hipSuccess) return e;
-  return hipFuncSetAttribute((const void*)k_prefill_down<BM>, hipFuncAttributeMaxDynamicSharedMemorySize, Shape<BM>::LDS);
+  return hipFuncSetAttribute((const void*)k_prefill_down<BM>, hipFuncAttributeMaxDynamicSharedMemorySize, kernel_lds<BM>());
 }
 
 static hipError_t ensure_lds_attr() {
@@ -393,7 +429,7 @@ hipError_t launch_prefill_gateup(const uint16_t* x, int M, const Plan& plan, int
   const int n_ctiles = (wv.n_chunks + 1) / 2;
   const int total = (n_row_tiles * n_ctiles + 7) / 8 * 8;
 #define SI_LAUNCH_GU(BMV)                                                                                          \
-  hipLaunchKernelGGL(k_prefill_gateup<BMV>, dim3(total), dim3(THREADS), Shape<BMV>::LDS, stream, x, M, plan,        \
+  hipLaunchKernelGGL(k_prefill_gateup<BMV>, dim3(total), dim3(THREADS), kernel_lds<BMV>(), stream, x, M, plan,        \
                      expert_sel, x2_only, total, n_ctiles, wv, hact, ldh)
   if (bm == 256) SI_LAUNCH_GU(256);
   else if (bm == 128) SI_LAUNCH_GU(128);
@@ -412,7 +448,7 @@ hipError_t launch_prefill_down(const uint16_t* hact, int ldh, int M, const Plan&
   const int n_ntiles = (M + BN - 1) / BN;
   const int total = (n_row_tiles * n_ntiles * n_split + 7) / 8 * 8;
 #define SI_LAUNCH_DN(BMV)                                                                                          \
-  hipLaunchKernelGGL(k_prefill_down<BMV>, dim3(total), dim3(THREADS), Shape<BMV>::LDS, stream, hact, ldh, M, plan,  \
+  hipLaunchKernelGGL(k_prefill_down<BMV>, dim3(total), dim3(THREADS), kernel_lds<BMV>(), stream, hact, ldh, M, plan,  \
                      expert_sel, x2_only, total, n_ntiles, n_split, wv, yp, slab_stride, accumulate)
   if (bm == 256) SI_LAUNCH_DN(256);
   else if (bm == 128) SI_LAUNCH_DN(128);
