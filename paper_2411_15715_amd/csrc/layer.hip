@@ -353,7 +353,7 @@ int si_layer_create(const si_layer_desc_t* desc, const uint16_t* w_gate, const u
     size_t stage_bytes = (size_t)(desc->stage_mib == 0 ? 256 : desc->stage_mib) << 20;
     int sc = (int)std::max<size_t>(1, stage_bytes / (ce * 2));
     // a decode piece must hold whole down-projection slots
-    int cps_max = std::max({ceil_div(L->ch_cg, DOWN_SLOTS), ceil_div(L->ch_cc, DOWN_SLOTS), ceil_div(L->sch_cg, DOWN_SLOTS), ceil_div(L->sch_cc, DOWN_SLOTS), 1});
+    int cps_max = std::max({ceil_div(L->ch_cg, DOWN_SLOTS), ceil_div(L->ch_cc, DOWN_SLOTS), ceil_div(L->sch_cg, DOWN_SLOTS), ceil_div(L->sch_cc, DOWN_SLOTS), 8});
     L->stage_chunks = std::max(sc, cps_max);
     L->d_stage.assign(L->n_stage, nullptr);
     L->ev_ready.assign(L->n_stage, nullptr);
@@ -538,10 +538,11 @@ int si_layer_forward(si_layer_t* L, const void* x_dev, const float* logits_dev, 
   auto rows_x2 = [&](int e) { return need_sync ? L->hcount[e] - L->hcount[EX + e] : n_g; };
   const int max_touched = std::min(EX, T * k + L->has_shared);
   const int tiles_upper = (T * k) / bm_call + E;  // bound on the routed row tiles
-  const int cps_gg = std::max(1, ceil_div(L->ch_gg, DOWN_SLOTS)), cps_cg = std::max(1, ceil_div(L->ch_cg, DOWN_SLOTS)),
-            cps_cc = std::max(1, ceil_div(L->ch_cc, DOWN_SLOTS));
-  const int scps_gg = std::max(1, ceil_div(L->sch_gg, DOWN_SLOTS)), scps_cg = std::max(1, ceil_div(L->sch_cg, DOWN_SLOTS)),
-            scps_cc = std::max(1, ceil_div(L->sch_cc, DOWN_SLOTS));
+  // chunks per j-slot of the decode down projection: at most DOWN_SLOTS slots per part, and at least 8 chunks
+  // (256 KB of weights per block) so that small experts do not shatter into tiny blocks
+  auto cps_of = [](int ch) { return std::max(1, std::max(ceil_div(ch, DOWN_SLOTS), std::min(8, ch))); };
+  const int cps_gg = cps_of(L->ch_gg), cps_cg = cps_of(L->ch_cg), cps_cc = cps_of(L->ch_cc);
+  const int scps_gg = cps_of(L->sch_gg), scps_cg = cps_of(L->sch_cg), scps_cc = cps_of(L->sch_cc);
   const size_t slot_stride = (size_t)L->rows_dec * M;
   // k-splits of the prefill down projection: enough blocks to fill 256 CUs when there are few row tiles
   const int n_ntiles = ceil_div(M, 256);
