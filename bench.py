@@ -28,6 +28,17 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0      # MI355X HBM3E
 MFMA_BF16_PEAK_TF = 2500.0  # dense bf16
 
+# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE (x2.000, the factor a plain 1 GiB copy gives) plus
+# WRITE_SIZE (x1.000), averaged over the launches of the kernel class in one bench step; the runs and the raw
+# counters are in profiles/mixtral_8x7b_gg_only_hbm_traffic.md.  Keyed by (config, split, kernel class).
+PMC_TRAFFIC = {
+    ("mixtral_8x7b", (0.5, 0.5, 0.0), "decode_gateup"): 153040.2 * 1024 + 56.3 * 1024,
+    ("mixtral_8x7b", (1.0, 0.0, 0.0), "decode_gateup"): 458877.0 * 1024 + 112.5 * 1024,
+    ("mixtral_8x7b", (1.0, 0.0, 0.0), "decode_down"): 230330.2 * 1024 + 512.0 * 1024,
+    ("mixtral_8x7b", (1.0, 0.0, 0.0), "prefill_gateup"): 2608378.0 * 1024 + 28672.0 * 1024,
+    ("mixtral_8x7b", (1.0, 0.0, 0.0), "prefill_down"): 954442.4 * 1024 + 32768.0 * 1024,
+}
+
 
 def parse_args():
     ap = argparse.ArgumentParser()
@@ -188,7 +199,8 @@ def kernel_table(si, cfg, info, wl, stats, steps, n_g):
     return out
 
 
-def roofline_of(name, ent, traffic=None):
+def roofline_of(name, ent, cfg_name=None, split=None):
+    traffic = PMC_TRAFFIC.get((cfg_name, tuple(split) if split is not None else None, name))
     if ent["bound"] == "hbm":
         a, p, unit = ent["GBps"], HBM_PEAK_GBS, "GB/s"
     else:
@@ -278,7 +290,7 @@ def main():
                                                          (" + shared H=%d" % cfg.d_ff_shared) if cfg.d_ff_shared else "",
                                                          cfg.t_prefill, args.decode_calls, cfg.t_decode),
                    "split_gg_cg_cc": list(split), "columns": info, "n_g": n_g, "tokens_per_step": tokens_per_step},
-        "roofline": roofline_of(dominant, ktab[dominant]),
+        "roofline": roofline_of(dominant, ktab[dominant], cfg.name, split),
         "phases": {k: round(v, 4) for k, v in phase.items()},
         "kernels": {k: {kk: (round(vv, 4) if isinstance(vv, float) else vv) for kk, vv in v.items()} for k, v in ktab.items()},
         "host_link": link,
@@ -295,7 +307,7 @@ def main():
             "decode_call_us": round(calls2["decode_call_us"], 2), "prefill_call_us": round(calls2["prefill_call_us"], 2),
             "prefill_ms": round(float(np.mean([s["total_ms"] for s in pre2])), 4),
             "decode_ms": round(float(np.mean([s["total_ms"] for s in dec2])), 4),
-            "rooflines": [roofline_of(k, k2[k]) for k in k2 if "bound" in k2[k]],
+            "rooflines": [roofline_of(k, k2[k], cfg.name, (1.0, 0.0, 0.0)) for k in k2 if "bound" in k2[k]],
         }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, w, wl, args.cpu_seconds)
