@@ -201,3 +201,37 @@ def test_edge_cases(oracle):
         assert np.array_equal(d1, d2)
     finally:
         L.close()
+
+
+def test_unusual_shapes_and_knobs(oracle):
+    """Granule 128, three staging buffers, top_k == n_experts, d_model not a multiple of 256 or 512,
+    a hidden size with an odd number of chunks, several forward calls in a row on one layer."""
+    cfg = synth.scaled(synth.CONFIGS["phimoe"], d_model=192, d_ff=640, n_experts=4, top_k=4)
+    w = synth.make_weights(cfg)
+    L = GpuLayer(cfg, w, (0.4, 0.4, 0.2), max_tokens=300, granule=128, stage_mib=1, n_stage=3, cc_threads=3)
+    try:
+        assert (L.info["n_gg"], L.info["n_cg"], L.info["n_cc"]) == (256, 256, 128)
+        for T, n_g, mode in ((2, 0, si.SI_AUTO), (9, 4, si.SI_DECODE), (9, 4, si.SI_PREFILL), (300, 77, si.SI_AUTO),
+                             (130, 130, si.SI_AUTO), (1, 1, si.SI_AUTO)):
+            xb = synth.make_tokens(cfg, T, stream=T)
+            lg = synth.make_router_logits(cfg, xb)
+            y, r = L.forward(xb, lg, n_g=n_g, mode=mode, routing=True)
+            assert_routing_equal(r, oracle.route(lg, cfg.top_k), T, cfg.top_k)
+            assert np.array_equal(r["count"], np.full(4, T))  # top_k == E: every expert gets every token
+            assert_parity(y, oracle_y(oracle, cfg, w, xb, lg))
+    finally:
+        L.close()
+    # many experts, few tokens: most experts receive nothing
+    cfg = synth.scaled(synth.CONFIGS["qwen_moe"], d_model=128, d_ff=128, d_ff_shared=0, n_experts=256, top_k=6)
+    w = synth.make_weights(cfg)
+    L = GpuLayer(cfg, w, (0.5, 0.5, 0.0), max_tokens=40, stage_mib=1)
+    try:
+        for T in (3, 40):
+            xb = synth.make_tokens(cfg, T, stream=T)
+            lg = synth.make_router_logits(cfg, xb)
+            y, r = L.forward(xb, lg, routing=True)
+            assert_routing_equal(r, oracle.route(lg, cfg.top_k), T, cfg.top_k)
+            assert (r["count"] == 0).sum() > 100
+            assert_parity(y, oracle_y(oracle, cfg, w, xb, lg))
+    finally:
+        L.close()
