@@ -199,6 +199,32 @@ def kernel_table(si, cfg, info, wl, stats, steps, n_g):
     return out
 
 
+def eq6_prediction(st):
+    """Layer time predicted by the timestamp recurrence of Section IV-A.2 (Eq. 6) from the separately measured
+    per-resource times of one call: for the n staged pieces
+        tau_L^i   = tau_L^(i-1) + t_L
+        tau_C2G^i = max(tau_L^i, tau_C2G^(i-1)) + t_C2G
+        tau_G^i   = max(tau_C2G^i, tau_G^(i-1)) + t_G
+    with tau^0 = the hand-off wait, tau_G^0 additionally the assignment kernels and the resident (GG) part, which
+    are enqueued before the first copy is waited for; t_fin = max(tau_G^n + merge, tau_C)."""
+    n = st["n_copies"]
+    t0 = st["handoff_ms"]
+    merge = st["kernel_ms"][3] + st["kernel_ms"][6]
+    gg = st["gpu_ms"] - st["staged_ms"] - merge
+    tau_c = t0 + st["cc_ms"]
+    if n == 0:
+        return max(t0 + gg + merge, tau_c)
+    t_c2g, t_g = st["copy_ms"] / n, st["staged_ms"] / n
+    t_l = max(0.0, st["enqueue_ms"] - st["handoff_ms"] - st["cc_ms"]) / (n + 1)
+    tau_l = tau_c2g = t0
+    tau_g = t0 + gg
+    for _ in range(n):
+        tau_l += t_l
+        tau_c2g = max(tau_l, tau_c2g) + t_c2g
+        tau_g = max(tau_c2g, tau_g) + t_g
+    return max(tau_g + merge, tau_c)
+
+
 def roofline_of(name, ent, cfg_name=None, split=None):
     traffic = PMC_TRAFFIC.get((cfg_name, tuple(split) if split is not None else None, name))
     if ent["bound"] == "hbm":
@@ -279,7 +305,11 @@ def main():
                 "copy_ms_per_step": copy_ms / args.steps,
                 "overlap_prefill": float(np.mean([s["overlap"] for s in pre])),
                 "overlap_decode": float(np.mean([s["overlap"] for s in dec])),
-                "cc_ms_per_step": sum(s["cc_ms"] for _, s in stats) / args.steps}
+                "cc_ms_per_step": sum(s["cc_ms"] for _, s in stats) / args.steps,
+                "eq6_predicted_prefill_ms": float(np.mean([eq6_prediction(s) for s in pre])),
+                "eq6_predicted_decode_ms": float(np.mean([eq6_prediction(s) for s in dec])),
+                "measured_prefill_ms": float(np.mean([s["total_ms"] for s in pre])),
+                "measured_decode_ms": float(np.mean([s["total_ms"] for s in dec]))}
 
     out = {
         "metric": "FFN/MoE layer tokens/s (decode+prefill)", "value": round(tokens_per_step / (ms_per_step / 1e3), 2),

@@ -112,6 +112,9 @@ typedef struct {
   int32_t path;       /* SI_DECODE or SI_PREFILL actually taken */
   float kernel_ms[SI_K_COUNT];         /* summed HIP-event time of each kernel class (SI_K_*) */
   int32_t kernel_launches[SI_K_COUNT]; /* launches of each class */
+  float staged_ms;    /* part of gpu_ms spent in kernels that read a staged (CG / CG') piece */
+  float handoff_ms;   /* host wait for the token assignment to reach the host (0 if not needed) */
+  float enqueue_ms;   /* host wall time spent inside the forward call (Stream-B) */
 } si_stats_t;
 
 /*

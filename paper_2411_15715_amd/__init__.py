@@ -39,7 +39,8 @@ class si_stats_t(ctypes.Structure):
                 ("cc_ms", ctypes.c_float), ("route_ms", ctypes.c_float), ("bytes_streamed", ctypes.c_double),
                 ("bytes_gg", ctypes.c_double), ("bytes_cc", ctypes.c_double), ("overlap", ctypes.c_float),
                 ("n_copies", ctypes.c_int32), ("n_touched", ctypes.c_int32), ("path", ctypes.c_int32),
-                ("kernel_ms", ctypes.c_float * 8), ("kernel_launches", ctypes.c_int32 * 8)]
+                ("kernel_ms", ctypes.c_float * 8), ("kernel_launches", ctypes.c_int32 * 8),
+                ("staged_ms", ctypes.c_float), ("handoff_ms", ctypes.c_float), ("enqueue_ms", ctypes.c_float)]
 
 
 SI_K_NAMES = ["route", "decode_gateup", "decode_down", "decode_combine", "prefill_gateup", "prefill_down",

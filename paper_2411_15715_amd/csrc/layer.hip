@@ -43,7 +43,7 @@ int fail(int code, const char* fmt, ...) {
     if (_e != hipSuccess) return fail(SI_EHIP, "%s failed: %s", #expr, hipGetErrorString(_e));  \
   } while (0)
 
-struct Seg { hipEvent_t a, b; int kind; };  // kind: SI_K_* kernel class, or SEG_COPY
+struct Seg { hipEvent_t a, b; int kind; int staged; };  // kind: SI_K_* kernel class, or SEG_COPY
 constexpr int SEG_COPY = SI_K_COUNT;
 
 int split_counts(int H, int g, float r_gg, float r_cg, int* n_gg, int* n_cg, int* n_cc) {
@@ -136,6 +136,7 @@ struct si_layer {
   CcPool* pool = nullptr;
   // stats
   int profiling = 0;
+  int in_staged = 0;  // the launches being enqueued read a staged piece
   std::vector<hipEvent_t> ev_pool;
   size_t ev_used = 0;
   std::vector<Seg> segs;
@@ -178,7 +179,7 @@ struct SegScope {
     if (L->profiling) { a = next_event(L); if (a) (void)hipEventRecord(a, s); }
   }
   ~SegScope() {
-    if (L->profiling && a) { hipEvent_t b = next_event(L); if (b) { (void)hipEventRecord(b, s); L->segs.push_back({a, b, kind}); } }
+    if (L->profiling && a) { hipEvent_t b = next_event(L); if (b) { (void)hipEventRecord(b, s); L->segs.push_back({a, b, kind, L->in_staged}); } }
   }
 };
 
@@ -486,6 +487,7 @@ int si_layer_forward(si_layer_t* L, const void* x_dev, const float* logits_dev, 
   auto pick_bm = [](int rows) { return rows >= 192 ? 256 : (rows >= 96 ? 128 : 64); };
   const int bm_call = pick_bm(ceil_div(T * k, E));
   L->ev_used = 0;
+  L->in_staged = 0;
   L->segs.clear();
   si_stats_t st{};
   st.path = path;
@@ -511,7 +513,9 @@ int si_layer_forward(si_layer_t* L, const void* x_dev, const float* logits_dev, 
     HIP_TRY(hipMemcpyAsync(L->hcount, L->plan.count, (size_t)EX * 4, hipMemcpyDeviceToHost, stream));
     HIP_TRY(hipMemcpyAsync(L->hcount + EX, L->plan.count1, (size_t)EX * 4, hipMemcpyDeviceToHost, stream));
     HIP_TRY(hipEventRecord(L->ev_host, stream));
+    const auto h0 = std::chrono::steady_clock::now();
     HIP_TRY(hipEventSynchronize(L->ev_host));
+    st.handoff_ms = std::chrono::duration<float, std::milli>(std::chrono::steady_clock::now() - h0).count();
     int nt = 0;
     for (int e = 0; e < EX; ++e) nt += L->hcount[e] > 0;
     st.n_touched = nt;
@@ -642,7 +646,9 @@ int si_layer_forward(si_layer_t* L, const void* x_dev, const float* logits_dev, 
           HIP_TRY(hipEventRecord(L->ev_ready[slot], L->copy_stream));
           HIP_TRY(hipStreamWaitEvent(stream, L->ev_ready[slot], 0));
           {
+            L->in_staged = 1;
             int rc = run_part(L->d_stage[slot], 0, sh ? 0 : e, sh, 0, n, (pc0 + c) * CHUNK_J, part, c, x2_only, false);
+            L->in_staged = 0;
             if (rc) return rc;
           }
           HIP_TRY(hipEventRecord(L->ev_free[slot], stream));
@@ -683,7 +689,8 @@ int si_layer_forward(si_layer_t* L, const void* x_dev, const float* logits_dev, 
     }
   }
   if (L->profiling) HIP_TRY(hipEventRecord(L->ev_t1, stream));
-  st.total_ms = std::chrono::duration<float, std::milli>(std::chrono::steady_clock::now() - wall0).count();  // replaced by event time in si_layer_stats
+  st.enqueue_ms = std::chrono::duration<float, std::milli>(std::chrono::steady_clock::now() - wall0).count();
+  st.total_ms = st.enqueue_ms;  // replaced by event time in si_layer_stats when profiling is on
   L->last = st;
   return SI_OK;
 }
@@ -698,7 +705,7 @@ int si_layer_stats(si_layer_t* L, si_stats_t* out) {
     float ms = 0.f;
     HIP_TRY(hipEventElapsedTime(&ms, L->ev_t0, L->ev_t1));
     st.total_ms = ms;
-    st.copy_ms = st.gpu_ms = st.route_ms = 0.f;
+    st.copy_ms = st.gpu_ms = st.route_ms = st.staged_ms = 0.f;
     for (int i = 0; i < SI_K_COUNT; ++i) { st.kernel_ms[i] = 0.f; st.kernel_launches[i] = 0; }
     for (const Seg& s : L->segs) {
       float d = 0.f;
@@ -707,6 +714,7 @@ int si_layer_stats(si_layer_t* L, si_stats_t* out) {
       st.gpu_ms += d;
       st.kernel_ms[s.kind] += d;
       st.kernel_launches[s.kind] += 1;
+      if (s.staged) st.staged_ms += d;
       if (s.kind == SI_K_ROUTE) st.route_ms += d;
     }
     float mx = std::max(st.copy_ms, std::max(st.gpu_ms, st.cc_ms));
