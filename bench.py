@@ -52,6 +52,10 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-gg-only", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
+    ap.add_argument("--solve", action="store_true",
+                    help="instead of the throughput line: profile this machine (Eq. 3), solve r_CG* for the config's "
+                         "r_GG and n_g* for its prompt length (Section IV), and measure the layer over a sweep of "
+                         "r_CG and of n_g next to the solved values")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="first run a plain elementwise copy of 1 GiB (reads 1 GiB, writes 1 GiB) three times: "
                          "the reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE counters")
@@ -257,6 +261,107 @@ def cpu_baseline(cfg, w, wl, seconds):
                       "the sampled ones), %.1f s" % (n, cfg.t_prefill, t)}
 
 
+def solver_study(args, si, torch, cfg, w, r_gg):
+    """Profiler & Solver end to end on this machine: fit Eq. 3 from measurements of the library's own kernels,
+    workers and copies; solve the generation-phase r_CG* for the given r_GG (Section IV-A.3) and, with the rates
+    fixed there, the prompt-phase n_g* (Section IV-B); then measure the real layer at the solved values and on a
+    sweep around them (the shape of the paper's slicing-rate ablation, Section V-E.2)."""
+    M, H, E, k = cfg.d_model, cfg.d_ff, cfg.n_experts, cfg.top_k
+    shared = tuple(w[kk] for kk in ("s_gate", "s_up", "s_down")) if cfg.d_ff_shared else None
+    stream = torch.cuda.current_stream().cuda_stream
+    wl = Workload(cfg, args.decode_calls)
+    R = 1.0 - r_gg
+
+    def touched_mean(calls):
+        return float(np.mean([Workload.touched(cfg, lg) for _, _, lg in calls]))
+
+    def layer_times(split, n_g, reps):
+        layer = si.si_layer_create(M, H, E, k, w["w_gate"], w["w_up"], w["w_down"], split[0], split[1], split[2],
+                                   max(cfg.t_prefill, cfg.t_decode), d_ff_shared=cfg.d_ff_shared, shared=shared)
+        try:
+            info = si.si_layer_split_info(layer)
+            dec, pre = [], []
+            for r in range(reps + 1):
+                for xd, ld, _ in wl.dec:
+                    torch.cuda.synchronize()
+                    t0 = time.perf_counter()
+                    si.si_layer_forward(layer, xd.data_ptr(), ld.data_ptr() if ld is not None else None, cfg.t_decode, 0,
+                                        si.SI_DECODE, wl.yd.data_ptr(), stream=stream)
+                    torch.cuda.synchronize()
+                    if r:
+                        dec.append(time.perf_counter() - t0)
+            for r in range(reps + 1):
+                for ng in n_g:
+                    torch.cuda.synchronize()
+                    t0 = time.perf_counter()
+                    si.si_layer_forward(layer, wl.xp.data_ptr(), wl.lp_dev.data_ptr() if wl.lp_dev is not None else None,
+                                        cfg.t_prefill, ng, si.SI_PREFILL, wl.yp.data_ptr(), stream=stream)
+                    torch.cuda.synchronize()
+                    if r:
+                        pre.append((ng, time.perf_counter() - t0))
+        finally:
+            si.si_layer_destroy(layer)
+        return info, float(np.median(dec)), {ng: float(np.median([t for g, t in pre if g == ng])) for ng in n_g}
+
+    # --- Profiler: one model per phase (rows of one expert's GEMM in that phase)
+    rows_dec = max(1, -(-cfg.t_decode * k // E)) if E > 1 else cfg.t_decode
+    e_dec = touched_mean(wl.dec) if E > 1 else 1.0
+    if E > 1:
+        rows_dec = max(1, int(round(cfg.t_decode * k / e_dec)))
+    rows_pre = max(1, cfg.t_prefill * k // E)
+    t0 = time.perf_counter()
+    prof_dec = si.si_profile(M, H, rows_dec, mode=si.SI_DECODE, n_sizes=6, reps=5)
+    prof_pre = si.si_profile(M, H, rows_pre, mode=si.SI_PREFILL, n_sizes=5, reps=3)
+    t_prof = time.perf_counter() - t0
+
+    # --- Solver, generation phase: n_l = 3 GEMMs (gate, up, down) per expert that received tokens
+    n_w = 2.0 * M * H
+    n_l_dec = int(round(3 * e_dec))
+    sol = si.si_solve_split(prof_dec["model"], float(rows_dec) * M * H, n_w, n_l_dec, r_gg, r_step=64.0 / H)
+    sweep = sorted({round(f * R, 6) for f in (0.0, 0.25, 0.5, 0.75, 1.0)} | {round(sol["r_cg"], 6)})
+    e_pre = float(Workload.touched(cfg, wl.lp)) if E > 1 else 1.0
+    n_l_pre = int(round(3 * e_pre))
+    T = cfg.t_prefill
+    rows = []
+    best_split = None
+    for r_cg in sweep:
+        split = (r_gg, r_cg, max(0.0, 1.0 - r_gg - r_cg))
+        is_star = abs(r_cg - sol["r_cg"]) < 1e-6
+        ngs = [0]
+        sol_ng = None
+        if is_star:
+            # --- Solver, prompt phase, rates fixed at the generation-phase optimum
+            sol_ng = si.si_solve_ng(prof_pre["model"], rows_pre, M, H, n_w, n_l_pre, split[0], split[1])
+            # the model counts rows of one expert's GEMM; the layer takes n_g in tokens
+            ng_tokens = int(round(sol_ng["n_g"] * T / rows_pre))
+            ngs = sorted({0, T // 4, T // 2, 3 * T // 4, T, min(T, ng_tokens)})
+        info, t_dec, t_pre = layer_times(split, ngs, 3)
+        pred = si.si_simulate(si.si_model_times(prof_dec["model"], float(rows_dec) * M * H, n_w, n_l_dec, split[0], split[1]),
+                              n_l_dec)["t_fin"]
+        row = {"r_cg": r_cg, "r_cc": round(split[2], 6), "columns": info, "solved": is_star,
+               "decode_ms_measured": round(1e3 * t_dec, 4), "decode_ms_model": round(1e3 * pred, 4)}
+        if is_star:
+            row["prefill"] = {"n_g_solved_tokens": min(T, ng_tokens), "n_g_solved_rows": sol_ng["n_g"],
+                              "model_ms_at_solved": round(1e3 * sol_ng["t_fin"], 4),
+                              "measured_ms_by_n_g": {str(g): round(1e3 * t, 4) for g, t in t_pre.items()}}
+        rows.append(row)
+    best = min(rows, key=lambda r: r["decode_ms_measured"])
+    star = [r for r in rows if r["solved"]][0]
+    fixed = [r for r in rows if not r["solved"]]
+    out = {
+        "solver_study": cfg.name, "r_gg": r_gg, "profile_seconds": round(t_prof, 1),
+        "model_decode": prof_dec["model"], "r2_decode": [prof_dec["r2_g"], prof_dec["r2_c"], prof_dec["r2_c2g"]],
+        "model_prefill": prof_pre["model"], "r2_prefill": [prof_pre["r2_g"], prof_pre["r2_c"], prof_pre["r2_c2g"]],
+        "sigma_launch": prof_dec["sigma_launch"], "rows_decode": rows_dec, "rows_prefill": rows_pre,
+        "n_l_decode": n_l_dec, "n_l_prefill": n_l_pre,
+        "r_cg_solved": sol["r_cg"], "case": sol["case"], "t_fin_model_ms": round(1e3 * sol["t_fin"], 4),
+        "sweep": rows,
+        "solved_vs_best_measured": round(star["decode_ms_measured"] / best["decode_ms_measured"], 4),
+        "speedup_over_fixed": {str(r["r_cg"]): round(r["decode_ms_measured"] / star["decode_ms_measured"], 3) for r in fixed},
+    }
+    print(json.dumps(out))
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -280,6 +385,9 @@ def main():
     n_g = args.n_g if args.n_g >= 0 else (cfg.t_prefill if split[2] > 0 else 0)
     t0 = time.perf_counter()
     w = synth.make_weights(cfg, threads=min(16, os.cpu_count() or 8))
+    if args.solve:
+        solver_study(args, si, torch, cfg, w, split[0])
+        return
     wl = Workload(cfg, args.decode_calls)
     t_gen = time.perf_counter() - t0
     tokens_per_step = cfg.t_prefill + args.decode_calls * cfg.t_decode

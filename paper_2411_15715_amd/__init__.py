@@ -18,7 +18,11 @@ SI_AUTO, SI_DECODE, SI_PREFILL = 0, 1, 2
 SI_DECODE_AUTO_T, SI_DECODE_MAX_T = 8, 16
 
 EXPORTS = ["si_layer_create", "si_layer_split_info", "si_split_counts", "si_layer_forward", "si_route",
-           "si_layer_stats", "si_layer_set_profiling", "si_repack_chunks", "si_cc_compute", "si_layer_destroy", "si_last_error", "si_version"]
+           "si_layer_stats", "si_layer_set_profiling", "si_repack_chunks", "si_cc_compute", "si_layer_destroy", "si_last_error", "si_version",
+           # scheinfer_solver.h
+           "si_fit_linear", "si_model_times", "si_simulate", "si_solve_split", "si_model_times_ng", "si_solve_ng",
+           "si_assign_gpu_memory", "si_profile"]
+SI_MAX_EDGE_POINTS, SI_PROFILE_MAX_SIZES = 24, 12
 
 
 class si_layer_desc_t(ctypes.Structure):
@@ -41,6 +45,43 @@ class si_stats_t(ctypes.Structure):
                 ("n_copies", ctypes.c_int32), ("n_touched", ctypes.c_int32), ("path", ctypes.c_int32),
                 ("kernel_ms", ctypes.c_float * 8), ("kernel_launches", ctypes.c_int32 * 8),
                 ("staged_ms", ctypes.c_float), ("handoff_ms", ctypes.c_float), ("enqueue_ms", ctypes.c_float)]
+
+
+class si_perf_model_t(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_double) for n in ("alpha_g", "beta_g", "alpha_c", "beta_c", "alpha_c2g", "beta_c2g", "t_launch")]
+
+
+class si_problem_t(ctypes.Structure):
+    _fields_ = [("n_gemm", ctypes.c_double), ("n_w", ctypes.c_double), ("n_l", ctypes.c_int32)]
+
+
+class si_task_times_t(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_double) for n in ("t_g", "t_c", "t_c2g", "t_l")]
+
+
+class si_split_solution_t(ctypes.Structure):
+    _fields_ = [("r_cg", ctypes.c_double), ("r_cc", ctypes.c_double), ("t_fin", ctypes.c_double),
+                ("which_case", ctypes.c_int32), ("n_points", ctypes.c_int32),
+                ("x", ctypes.c_double * SI_MAX_EDGE_POINTS), ("y", ctypes.c_double * SI_MAX_EDGE_POINTS)]
+
+
+class si_ng_solution_t(ctypes.Structure):
+    _fields_ = [("n_g", ctypes.c_int32), ("t_fin", ctypes.c_double), ("which_case", ctypes.c_int32),
+                ("n_points", ctypes.c_int32), ("x", ctypes.c_double * SI_MAX_EDGE_POINTS),
+                ("y", ctypes.c_double * SI_MAX_EDGE_POINTS)]
+
+
+class si_profile_desc_t(ctypes.Structure):
+    _fields_ = [("d_model", ctypes.c_int32), ("d_ff", ctypes.c_int32), ("tokens", ctypes.c_int32),
+                ("mode", ctypes.c_int32), ("n_sizes", ctypes.c_int32), ("reps", ctypes.c_int32),
+                ("cc_threads", ctypes.c_int32), ("device", ctypes.c_int32), ("copy_max_mib", ctypes.c_int32),
+                ("seed", ctypes.c_uint32)]
+
+
+class si_profile_result_t(ctypes.Structure):
+    _fields_ = [("model", si_perf_model_t), ("r2_g", ctypes.c_double), ("r2_c", ctypes.c_double),
+                ("r2_c2g", ctypes.c_double), ("sigma_launch", ctypes.c_double), ("n_points", ctypes.c_int32)] + \
+               [(n, ctypes.c_double * SI_PROFILE_MAX_SIZES) for n in ("n_gemm", "t_g", "t_c", "bytes", "t_c2g")]
 
 
 SI_K_NAMES = ["route", "decode_gateup", "decode_down", "decode_combine", "prefill_gateup", "prefill_down",
@@ -86,6 +127,24 @@ def lib():
         L.si_layer_destroy.argtypes = [vp]
         L.si_last_error.restype = ctypes.c_char_p
         L.si_version.restype = ctypes.c_char_p
+        f64, pd = ctypes.c_double, ctypes.POINTER(ctypes.c_double)
+        pm, pp, pt = ctypes.POINTER(si_perf_model_t), ctypes.POINTER(si_problem_t), ctypes.POINTER(si_task_times_t)
+        L.si_fit_linear.restype = ctypes.c_int
+        L.si_fit_linear.argtypes = [vp, vp, i32, i32, pd, pd, pd]
+        L.si_model_times.restype = ctypes.c_int
+        L.si_model_times.argtypes = [pm, pp, f64, f64, pt]
+        L.si_simulate.restype = ctypes.c_int
+        L.si_simulate.argtypes = [pt, i32, pd, pd, pd]
+        L.si_solve_split.restype = ctypes.c_int
+        L.si_solve_split.argtypes = [pm, pp, f64, f64, ctypes.POINTER(si_split_solution_t)]
+        L.si_model_times_ng.restype = ctypes.c_int
+        L.si_model_times_ng.argtypes = [pm, i32, i32, i32, f64, f64, f64, i32, pt]
+        L.si_solve_ng.restype = ctypes.c_int
+        L.si_solve_ng.argtypes = [pm, i32, i32, i32, f64, i32, f64, f64, ctypes.POINTER(si_ng_solution_t)]
+        L.si_assign_gpu_memory.restype = ctypes.c_int
+        L.si_assign_gpu_memory.argtypes = [vp, vp, i32, i32, f64, vp]
+        L.si_profile.restype = ctypes.c_int
+        L.si_profile.argtypes = [ctypes.POINTER(si_profile_desc_t), ctypes.POINTER(si_profile_result_t)]
         _lib = L
     return _lib
 
@@ -193,3 +252,87 @@ def si_cc_compute(x, idx, w, n_experts, routed, expert_stride, n_cc_chunks, shar
 
 def si_layer_destroy(layer):
     lib().si_layer_destroy(layer)
+
+
+# ---------------------------------------------------------------- scheinfer_solver.h
+_MODEL_KEYS = ("alpha_g", "beta_g", "alpha_c", "beta_c", "alpha_c2g", "beta_c2g", "t_launch")
+
+
+def _model(m):
+    return m if isinstance(m, si_perf_model_t) else si_perf_model_t(*[float(m[k]) for k in _MODEL_KEYS])
+
+
+def _times(t):
+    return {k: getattr(t, k) for k in ("t_g", "t_c", "t_c2g", "t_l")}
+
+
+def si_fit_linear(n, t, nonneg=False):
+    """(alpha, beta, r2) of t = alpha + n*beta."""
+    import numpy as np
+    n = np.ascontiguousarray(n, np.float64)
+    t = np.ascontiguousarray(t, np.float64)
+    if n.shape != t.shape or n.ndim != 1:
+        raise ValueError("n and t must be 1-d arrays of equal length")
+    a, b, r2 = ctypes.c_double(), ctypes.c_double(), ctypes.c_double()
+    _check(lib().si_fit_linear(ctypes.c_void_p(n.ctypes.data), ctypes.c_void_p(t.ctypes.data), n.size, int(nonneg),
+                               ctypes.byref(a), ctypes.byref(b), ctypes.byref(r2)))
+    return a.value, b.value, r2.value
+
+
+def si_model_times(model, n_gemm, n_w, n_l, r_gg, r_cg) -> dict:
+    out = si_task_times_t()
+    _check(lib().si_model_times(ctypes.byref(_model(model)), ctypes.byref(si_problem_t(n_gemm, n_w, n_l)), r_gg, r_cg,
+                                ctypes.byref(out)))
+    return _times(out)
+
+
+def si_simulate(times: dict, n_l) -> dict:
+    t = si_task_times_t(times["t_g"], times["t_c"], times["t_c2g"], times["t_l"])
+    f, g, c = ctypes.c_double(), ctypes.c_double(), ctypes.c_double()
+    _check(lib().si_simulate(ctypes.byref(t), n_l, ctypes.byref(f), ctypes.byref(g), ctypes.byref(c)))
+    return {"t_fin": f.value, "tau_g": g.value, "tau_c": c.value}
+
+
+def si_solve_split(model, n_gemm, n_w, n_l, r_gg, r_step=0.0) -> dict:
+    out = si_split_solution_t()
+    _check(lib().si_solve_split(ctypes.byref(_model(model)), ctypes.byref(si_problem_t(n_gemm, n_w, n_l)), r_gg, r_step,
+                                ctypes.byref(out)))
+    return {"r_cg": out.r_cg, "r_cc": out.r_cc, "t_fin": out.t_fin, "case": out.which_case,
+            "X": list(out.x[:out.n_points]), "Y": list(out.y[:out.n_points])}
+
+
+def si_model_times_ng(model, T, d_model, d_ff, n_w, r_gg, r_cg, n_g) -> dict:
+    out = si_task_times_t()
+    _check(lib().si_model_times_ng(ctypes.byref(_model(model)), T, d_model, d_ff, n_w, r_gg, r_cg, n_g, ctypes.byref(out)))
+    return _times(out)
+
+
+def si_solve_ng(model, T, d_model, d_ff, n_w, n_l, r_gg, r_cg) -> dict:
+    out = si_ng_solution_t()
+    _check(lib().si_solve_ng(ctypes.byref(_model(model)), T, d_model, d_ff, n_w, n_l, r_gg, r_cg, ctypes.byref(out)))
+    return {"n_g": out.n_g, "t_fin": out.t_fin, "case": out.which_case,
+            "X": [int(v) for v in out.x[:out.n_points]], "Y": list(out.y[:out.n_points])}
+
+
+def si_assign_gpu_memory(t_star, n_m, budget):
+    """t_star: [n_layers][n_grid+1]; returns the chosen grid index per layer."""
+    import numpy as np
+    t = np.ascontiguousarray(t_star, np.float64)
+    w = np.ascontiguousarray(n_m, np.float64)
+    if t.ndim != 2 or w.shape != (t.shape[0],):
+        raise ValueError("t_star must be [n_layers][n_grid+1] and n_m [n_layers]")
+    pick = np.zeros(t.shape[0], np.int32)
+    _check(lib().si_assign_gpu_memory(ctypes.c_void_p(t.ctypes.data), ctypes.c_void_p(w.ctypes.data), t.shape[0],
+                                      t.shape[1] - 1, float(budget), ctypes.c_void_p(pick.ctypes.data)))
+    return pick.tolist()
+
+
+def si_profile(d_model, d_ff, tokens, mode=SI_AUTO, n_sizes=0, reps=0, cc_threads=0, device=0, copy_max_mib=0, seed=1) -> dict:
+    """Measure this machine and fit Eq. 3; returns the model, the r^2 values and the raw points."""
+    desc = si_profile_desc_t(d_model, d_ff, tokens, mode, n_sizes, reps, cc_threads, device, copy_max_mib, seed)
+    out = si_profile_result_t()
+    _check(lib().si_profile(ctypes.byref(desc), ctypes.byref(out)))
+    k = out.n_points
+    return {"model": {n: getattr(out.model, n) for n in _MODEL_KEYS}, "r2_g": out.r2_g, "r2_c": out.r2_c,
+            "r2_c2g": out.r2_c2g, "sigma_launch": out.sigma_launch, "n_gemm": list(out.n_gemm[:k]),
+            "t_g": list(out.t_g[:k]), "t_c": list(out.t_c[:k]), "bytes": list(out.bytes[:k]), "t_c2g": list(out.t_c2g[:k])}

@@ -12,8 +12,8 @@ OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libscheinfer.so")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
-HIP_SOURCES = ["route.hip", "decode.hip", "prefill.hip", "layer.hip"]
-CPP_SOURCES = ["cc_worker.cpp"]
+HIP_SOURCES = ["route.hip", "decode.hip", "prefill.hip", "layer.hip", "profiler.hip"]
+CPP_SOURCES = ["cc_worker.cpp", "solver.cpp"]
 HIP_FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang",
              "-packed-fp32-ops", "-Wno-unused-command-line-argument", "-I", os.path.join(ROOT, "include"), "-I", CSRC]
 CPP_FLAGS = ["-O3", "-std=c++17", "-fPIC", "-mavx2", "-mfma", "-pthread", "-I", os.path.join(ROOT, "include"), "-I", CSRC]
@@ -35,7 +35,7 @@ def build(force: bool = True, jobs: int = 4) -> str:
     """Compile every source and link the shared library.  ``force=False`` skips up-to-date objects."""
     from concurrent.futures import ThreadPoolExecutor
     os.makedirs(OBJ, exist_ok=True)
-    headers = [os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".h")] + [os.path.join(ROOT, "include", "scheinfer.h")]
+    headers = [os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".h")] + [os.path.join(ROOT, "include", f) for f in os.listdir(os.path.join(ROOT, "include")) if f.endswith(".h")]
     newest_h = max(os.path.getmtime(h) for h in headers)
     tasks = []
     objs = []

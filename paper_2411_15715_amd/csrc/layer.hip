@@ -20,6 +20,7 @@
 #include <vector>
 
 #include "si_internal.h"
+#include "si_error.h"
 
 using namespace si;
 
@@ -36,6 +37,20 @@ int fail(int code, const char* fmt, ...) {
   g_err = buf;
   return code;
 }
+
+}  // namespace
+
+int si::set_error(int code, const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  g_err = buf;
+  return code;
+}
+
+namespace {
 
 #define HIP_TRY(expr)                                                                           \
   do {                                                                                          \

@@ -1,0 +1,70 @@
+"""Profiler on the GPU machine: the measurements behind Eq. 3 are sane, the fits describe them, and the
+solved slicing rate is competitive with a sweep of fixed rates on the real layer."""
+import time
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2411_15715_amd as si
+import synth
+from gpu_helpers import GpuLayer
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def profile():
+    return si.si_profile(2048, 8192, 4, mode=si.SI_DECODE, n_sizes=5, reps=5, copy_max_mib=128)
+
+
+def test_profile_points_and_fits(profile):
+    p = profile
+    assert len(p["n_gemm"]) == 5 and p["n_gemm"] == sorted(p["n_gemm"])
+    assert p["n_gemm"][-1] == 4.0 * 2048 * 8192
+    for key in ("t_g", "t_c", "t_c2g"):
+        assert all(1e-7 < v < 1.0 for v in p[key]), (key, p[key])
+    m = p["model"]
+    assert all(v >= 0.0 for v in m.values())
+    assert m["beta_g"] > 0 and m["beta_c"] > 0 and m["beta_c2g"] > 0
+    # this machine: copies run at 10..70 GB/s, a launch costs 1..200 us, the GPU beats the host per unit of work
+    assert 1.0 / 70e9 < m["beta_c2g"] < 1.0 / 10e9
+    assert 1e-6 < m["t_launch"] < 2e-4 and p["sigma_launch"] < m["t_launch"]
+    assert m["beta_g"] < m["beta_c"]
+    assert p["r2_c2g"] > 0.98 and p["r2_g"] > 0.8
+    # the library's fit of its own points is the least-squares one
+    a, b, r2 = si.si_fit_linear(p["bytes"], p["t_c2g"], nonneg=True)
+    assert (a, b) == (m["alpha_c2g"], m["beta_c2g"]) and r2 == p["r2_c2g"]
+    # larger copies take longer, and so do larger GEMMs on both sides
+    assert p["t_c2g"][-1] > p["t_c2g"][0] and p["t_g"][-1] > p["t_g"][0] and p["t_c"][-1] > p["t_c"][0]
+
+
+def test_solved_rate_is_competitive(profile):
+    """r_GG = 0 as in the paper's slicing-rate ablation: the layer at the solved r_CG is not slower than the
+    best of the fixed rates 0 / 0.5 / 1 by more than measurement noise allows (factor 1.5)."""
+    cfg = synth.scaled(synth.CONFIGS["llama2_70b"], d_model=2048, d_ff=8192)
+    w = synth.make_weights(cfg)
+    M, H = cfg.d_model, cfg.d_ff
+    sol = si.si_solve_split(profile["model"], 4.0 * M * H, 2.0 * M * H, 3, 0.0, r_step=64.0 / H)
+    assert 0.0 <= sol["r_cg"] <= 1.0 and sol["case"] in (1, 2, 3)
+    xb = synth.make_tokens(cfg, 4, stream=9)
+
+    def measure(r_cg):
+        L = GpuLayer(cfg, w, (0.0, r_cg, 1.0 - r_cg), max_tokens=4)
+        try:
+            ts = []
+            for i in range(8):
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                L.forward(xb, None, mode=si.SI_DECODE)
+                torch.cuda.synchronize()
+                if i >= 2:
+                    ts.append(time.perf_counter() - t0)
+            return float(np.median(ts))
+        finally:
+            L.close()
+
+    t_star = measure(sol["r_cg"])
+    fixed = {r: measure(r) for r in (0.0, 0.5, 1.0)}
+    print("solved r_cg %.4f: %.3f ms; fixed: %s; model %.3f ms" % (sol["r_cg"], 1e3 * t_star, {r: round(1e3 * t, 3) for r, t in fixed.items()}, 1e3 * sol["t_fin"]))
+    assert t_star <= 1.5 * min(fixed.values())
