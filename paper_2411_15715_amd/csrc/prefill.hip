@@ -72,19 +72,48 @@ __device__ inline void block_barrier() {
   asm volatile("" ::: "memory");
 }
 
-// XCD-aware remap: consecutive hardware block ids go round-robin over the 8 XCDs; give each XCD a
-// contiguous range of logical ids so that the row tiles that read the same weights share an L2.
-// In the first GEMM only for the 256-row tiles (several row tiles per expert, MFMA bound).  With the small tiles an
-// expert has one or two row tiles, nothing is shared, and the remap would make the 8 XCDs stream 8
-// regions of memory a whole expert apart (same low address bits): measured 453 -> 394 us on the
-// weight stream of the Mixtral-shaped gate/up GEMM without it.
-template <bool ON> __device__ inline int xcd_remap(int b, int total) {
-  if (!ON) return b;
-  const int per = (total + 7) / 8;
-  return (b % 8) * per + b / 8;
+// Hardware block id -> logical tile id.
+//  * XCD-aware remap: consecutive hardware block ids go round-robin over the 8 XCDs; give each XCD a
+//    contiguous range of logical ids so that the row tiles that read the same weights share an L2.  The
+//    ranges are cut from the number of ids that really have work (known on the device only), so that no
+//    XCD is handed a range of empty ids.  In the first GEMM only for the 256-row tiles (several row tiles
+//    per expert, MFMA bound).  With the small tiles an expert has one or two row tiles, nothing is shared,
+//    and the remap would make the 8 XCDs stream 8 regions of memory a whole expert apart (same low address
+//    bits): measured 453 -> 394 us on the weight stream of the Mixtral-shaped gate/up GEMM without it.
+//  * Tail split (256-row launches): N tiles on n_cu compute units run in ceil(N / n_cu) rounds; when the
+//    last round is at most half full its tiles are cut into two 128-row halves, each a block of its own,
+//    so that the round costs about half a round (LLaMA-shaped gate/up GEMM: 896 tiles = 3.5 rounds).
+template <int BM, bool REMAP>
+__device__ inline bool map_block(int b, int N, int n_cu, int& L, int& half, int& halves) {
+  int r = BM == 256 ? N % n_cu : 0;
+  if (2 * r > n_cu) r = 0;
+  const int main_n = N - r;
+  const int per = (main_n + 7) / 8;
+  if (b < 8 * per) {
+    L = REMAP ? (b % 8) * per + b / 8 : b;
+    half = 0;
+    halves = 1;
+    return L < main_n;
+  }
+  const int bt = b - 8 * per;
+  if (bt >= 2 * r) return false;
+  L = main_n + (bt >> 1);
+  half = bt & 1;
+  halves = 2;
+  return true;
 }
 
 struct TileInfo { int e, row0, row_end; };
+
+// Number of logical tile ids with work in this launch (row tiles of BM rows x inner tiles).
+template <int BM>
+__device__ inline int launch_extent(const Plan& p, int expert_sel, int x2_only, int n_inner) {
+  if (expert_sel >= 0) {
+    const int start = p.off[expert_sel] + (x2_only ? p.count1[expert_sel] : 0);
+    return (p.off[expert_sel + 1] - start + BM - 1) / BM * n_inner;
+  }
+  return (x2_only ? *p.n_tiles_x2 : *p.n_tiles) * n_inner;  // row tiles of the routed experts
+}
 
 // logical id L -> (expert, inner index, row tile) with the row tile varying fastest inside an
 // expert: L / n_inner indexes the row-tile table (built for the same BM), which yields the expert.
@@ -116,6 +145,22 @@ __device__ inline bool decode_tile(const Plan& p, int expert_sel, int x2_only, i
   ti.e = e;
   ti.row0 = start + r * BM;
   ti.row_end = end;
+  return true;
+}
+
+// block id -> tile of this block (false: nothing to do)
+template <int BM, bool REMAP>
+__device__ inline bool block_tile(const Plan& p, int expert_sel, int x2_only, int n_inner, int n_cu, int& inner,
+                                  TileInfo& ti) {
+  int L, half, halves;
+  if (!map_block<BM, REMAP>(blockIdx.x, launch_extent<BM>(p, expert_sel, x2_only, n_inner), n_cu, L, half, halves))
+    return false;
+  if (!decode_tile<BM>(p, expert_sel, x2_only, L, n_inner, inner, ti)) return false;
+  if (halves == 2) {
+    ti.row0 += half * (BM / 2);
+    ti.row_end = min(ti.row_end, ti.row0 + BM / 2);
+    if (ti.row0 >= ti.row_end) return false;
+  }
   return true;
 }
 
@@ -244,14 +289,13 @@ __device__ __forceinline__ void gateup_body(const uint16_t* __restrict__ x, int 
 // 40-row tail costs a 64-row tile, not a 256-row one.
 template <int BM>
 __global__ __launch_bounds__(THREADS, 1) void k_prefill_gateup(const uint16_t* __restrict__ x, int M, Plan p,
-                                                               int expert_sel, int x2_only, int total_blocks,
+                                                               int expert_sel, int x2_only, int n_cu,
                                                                int n_ctiles, WeightView wv,
                                                                uint16_t* __restrict__ hact, int ldh) {
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
-  const int L = xcd_remap<BM == 256>(blockIdx.x, total_blocks);
   int tc;
   TileInfo ti;
-  if (!decode_tile<BM>(p, expert_sel, x2_only, L, n_ctiles, tc, ti)) return;
+  if (!block_tile<BM, BM == 256>(p, expert_sel, x2_only, n_ctiles, n_cu, tc, ti)) return;
   if (BM == 256) {
     const int rows = ti.row_end - ti.row0;
     if (rows <= 64) gateup_body<64>(x, M, p, tc, ti, wv, hact, ldh, lds);
@@ -340,15 +384,15 @@ __device__ __forceinline__ void down_body(const uint16_t* __restrict__ hact, int
 
 template <int BM>
 __global__ __launch_bounds__(THREADS, 1) void k_prefill_down(const uint16_t* __restrict__ hact, int ldh, int M, Plan p,
-                                                             int expert_sel, int x2_only, int total_blocks,
+                                                             int expert_sel, int x2_only, int n_cu,
                                                              int n_ntiles, int n_split, WeightView wv,
                                                              float* __restrict__ yp, size_t slab_stride,
                                                              int accumulate) {
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
-  const int L = xcd_remap<true>(blockIdx.x, total_blocks);  // one expert's Hact rows (A operand) stay in one L2
   int inner;
   TileInfo ti;
-  if (!decode_tile<BM>(p, expert_sel, x2_only, L, n_ntiles * n_split, inner, ti)) return;
+  // remap always: one expert's Hact rows (A operand) stay in one L2
+  if (!block_tile<BM, true>(p, expert_sel, x2_only, n_ntiles * n_split, n_cu, inner, ti)) return;
   if (BM == 256) {
     const int rows = ti.row_end - ti.row0;
     if (rows <= 64) down_body<64>(hact, ldh, M, inner, ti, n_ntiles, n_split, wv, yp, slab_stride, accumulate, lds);
@@ -410,6 +454,21 @@ template <int BM> static hipError_t set_lds_attr() {
   return hipFuncSetAttribute((const void*)k_prefill_down<BM>, hipFuncAttributeMaxDynamicSharedMemorySize, kernel_lds<BM>());
 }
 
+// compute units of the current device (a round of the tail split)
+static int cu_count() {
+  static int n = [] {
+    int dev = 0, v = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0)
+      v = 256;
+    return v;
+  }();
+  return n;
+}
+
+// grid of a launch over at most n_tiles logical ids: room for the XCD ranges (rounded up to 8) and for the
+// second halves of a split tail (at most half a round)
+static int grid_blocks(int n_tiles, int bm) { return (n_tiles + 7) / 8 * 8 + 8 + (bm == 256 ? cu_count() / 2 + 8 : 0); }
+
 static hipError_t ensure_lds_attr() {
   static hipError_t st = [] {
     hipError_t e = set_lds_attr<256>();
@@ -427,10 +486,10 @@ hipError_t launch_prefill_gateup(const uint16_t* x, int M, const Plan& plan, int
   hipError_t e = ensure_lds_attr();
   if (e != hipSuccess) return e;
   const int n_ctiles = (wv.n_chunks + 1) / 2;
-  const int total = (n_row_tiles * n_ctiles + 7) / 8 * 8;
+  const int total = grid_blocks(n_row_tiles * n_ctiles, bm);
 #define SI_LAUNCH_GU(BMV)                                                                                          \
   hipLaunchKernelGGL(k_prefill_gateup<BMV>, dim3(total), dim3(THREADS), kernel_lds<BMV>(), stream, x, M, plan,        \
-                     expert_sel, x2_only, total, n_ctiles, wv, hact, ldh)
+                     expert_sel, x2_only, cu_count(), n_ctiles, wv, hact, ldh)
   if (bm == 256) SI_LAUNCH_GU(256);
   else if (bm == 128) SI_LAUNCH_GU(128);
   else if (bm == 64) SI_LAUNCH_GU(64);
@@ -446,10 +505,10 @@ hipError_t launch_prefill_down(const uint16_t* hact, int ldh, int M, const Plan&
   hipError_t e = ensure_lds_attr();
   if (e != hipSuccess) return e;
   const int n_ntiles = (M + BN - 1) / BN;
-  const int total = (n_row_tiles * n_ntiles * n_split + 7) / 8 * 8;
+  const int total = grid_blocks(n_row_tiles * n_ntiles * n_split, bm);
 #define SI_LAUNCH_DN(BMV)                                                                                          \
   hipLaunchKernelGGL(k_prefill_down<BMV>, dim3(total), dim3(THREADS), kernel_lds<BMV>(), stream, hact, ldh, M, plan,  \
-                     expert_sel, x2_only, total, n_ntiles, n_split, wv, yp, slab_stride, accumulate)
+                     expert_sel, x2_only, cu_count(), n_ntiles, n_split, wv, yp, slab_stride, accumulate)
   if (bm == 256) SI_LAUNCH_DN(256);
   else if (bm == 128) SI_LAUNCH_DN(128);
   else if (bm == 64) SI_LAUNCH_DN(64);

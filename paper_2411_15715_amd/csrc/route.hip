@@ -111,8 +111,9 @@ __device__ __forceinline__ void assign_body(int T, int E, int k, int has_shared,
     s_tiles[0][EX] = a;
     s_tiles[1][EX] = b;
     if (p.n_touched) *p.n_touched = nt;
-    if (p.n_tiles) *p.n_tiles = a;
-    if (p.n_tiles_x2) *p.n_tiles_x2 = b;
+    // launches over "all experts" cover the routed experts only (the shared expert, entry E, gets its own)
+    if (p.n_tiles) *p.n_tiles = s_tiles[0][E];
+    if (p.n_tiles_x2) *p.n_tiles_x2 = s_tiles[1][E];
   }
   __syncthreads();
   for (int e = tid; e < EX; e += ROUTE_THREADS) {

@@ -38,7 +38,7 @@ struct Plan {
   int32_t* n_touched;  // [1]
   int32_t* tile_e;     // [max_tiles] expert of each row tile (all rows)
   int32_t* tile_r;     // [max_tiles] index of the tile inside its expert
-  int32_t* n_tiles;    // [1]
+  int32_t* n_tiles;    // [1] row tiles of the routed experts (the shared expert's follow in the table)
   int32_t* tile_e_x2;  // the same for the X2 rows only (CG')
   int32_t* tile_r_x2;
   int32_t* n_tiles_x2;  // [1]
