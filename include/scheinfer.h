@@ -203,6 +203,31 @@ int si_cc_compute(const uint16_t* x, const int32_t* idx, const float* w, int32_t
 /* Free everything the layer owns.  NULL is allowed. */
 void si_layer_destroy(si_layer_t* layer);
 
+/*
+ * A stack of layers run back to back: the MLP / MoE blocks of consecutive Transformer layers with the
+ * residual connection around each (attention lies outside this library),
+ *   x_0 = x,   x_{l+1} = bf16(x_l + Layer_l(x_l)),   h_out = x_{n-1} + Layer_{n-1}(x_{n-1})   (fp32, not rounded).
+ * Each layer keeps its own slicing rates, e.g. the r_GG that si_assign_gpu_memory gave it (Section IV-A.4).
+ * prefetch bit 0: the first CG pieces of layer l+1 are put on the host link as soon as the copies of layer l are
+ * enqueued, before the host waits for layer l's CC workers, so that the link does not idle between layers
+ * (dense layers only: which experts of an MoE layer are streamed depends on its own token assignment).
+ * prefetch bit 1: likewise layer 0's pieces after the last layer, for the next call on this stack (token by
+ * token generation); they are used if that call takes the same path (decode / prefill) and copied again if not.
+ *
+ * si_stack_create: `layers` HOST array of n_layers >= 1 distinct layer handles with equal d_model on one
+ *   device.  The stack borrows the layers (the caller destroys them after the stack) and owns two bf16
+ *   hidden-state buffers and one fp32 output buffer of max_tokens x d_model (the smallest max_tokens).
+ * si_stack_forward: x_dev DEVICE bf16 [T][d_model]; logits_dev HOST array of n_layers DEVICE pointers
+ *   (f32 [T][n_experts] of each layer; entries of dense layers and the array itself may be NULL when every
+ *   layer is dense); n_g, mode, stream as in si_layer_forward, applied to every layer; h_out_dev DEVICE
+ *   f32 [T][d_model].  Errors as si_layer_forward.
+ */
+typedef struct si_stack si_stack_t;
+int si_stack_create(si_layer_t* const* layers, int32_t n_layers, si_stack_t** out);
+int si_stack_forward(si_stack_t* stack, const void* x_dev, const float* const* logits_dev, int32_t T, int32_t n_g,
+                     int32_t mode, float* h_out_dev, int32_t prefetch, void* stream);
+void si_stack_destroy(si_stack_t* stack);
+
 /* Text of the last error raised on the calling thread ("" if none). */
 const char* si_last_error(void);
 

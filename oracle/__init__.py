@@ -125,3 +125,32 @@ def layer_forward(x, w_gate, w_up, w_down, logits=None, top_k=1, shared=None, co
     if rc:
         raise ValueError("so_layer_forward failed with code %d" % rc)
     return y
+
+
+def round_to_bf16(v: np.ndarray) -> np.ndarray:
+    """Round float64 values to the nearest bfloat16 (8 significant bits, ties to even) and return the uint16
+    bit patterns.  Normal range only (no subnormals, no overflow): the hidden states of a layer stack."""
+    v = np.asarray(v, np.float64)
+    m, e = np.frexp(v)                    # v = m * 2^e, 0.5 <= |m| < 1
+    q = np.rint(m * 256.0)                # 8 significant bits; rint rounds halves to even
+    r = np.ldexp(q / 256.0, e).astype(np.float32)   # exact: 8 bits fit float32
+    return (r.view(np.uint32) >> np.uint32(16)).astype(np.uint16)
+
+
+def bf16_to_f64(b: np.ndarray) -> np.ndarray:
+    return (np.asarray(b, np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+
+
+def stack_forward(x, layers) -> np.ndarray:
+    """Layers run back to back with the residual connection around each:
+    x_{l+1} = bf16(x_l + Layer_l(x_l)); returns h = x_{n-1} + Layer_{n-1}(x_{n-1}) in float64, not rounded.
+    layers: list of dicts with the keyword arguments of layer_forward (w_gate, w_up, w_down, logits, top_k,
+    shared)."""
+    x = np.ascontiguousarray(x, dtype=np.uint16)
+    h = None
+    for i, kw in enumerate(layers):
+        y = layer_forward(x, **kw)
+        h = bf16_to_f64(x) + y
+        if i + 1 < len(layers):
+            x = round_to_bf16(h)
+    return h

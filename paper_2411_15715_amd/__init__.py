@@ -19,6 +19,7 @@ SI_DECODE_AUTO_T, SI_DECODE_MAX_T = 8, 16
 
 EXPORTS = ["si_layer_create", "si_layer_split_info", "si_split_counts", "si_layer_forward", "si_route",
            "si_layer_stats", "si_layer_set_profiling", "si_repack_chunks", "si_cc_compute", "si_layer_destroy", "si_last_error", "si_version",
+           "si_stack_create", "si_stack_forward", "si_stack_destroy",
            # scheinfer_solver.h
            "si_fit_linear", "si_model_times", "si_simulate", "si_solve_split", "si_model_times_ng", "si_solve_ng",
            "si_assign_gpu_memory", "si_profile"]
@@ -126,6 +127,12 @@ def lib():
         L.si_layer_destroy.restype = None
         L.si_layer_destroy.argtypes = [vp]
         L.si_last_error.restype = ctypes.c_char_p
+        L.si_stack_create.restype = ctypes.c_int
+        L.si_stack_create.argtypes = [ctypes.POINTER(vp), i32, ctypes.POINTER(vp)]
+        L.si_stack_forward.restype = ctypes.c_int
+        L.si_stack_forward.argtypes = [vp, vp, ctypes.POINTER(vp), i32, i32, i32, vp, i32, vp]
+        L.si_stack_destroy.restype = None
+        L.si_stack_destroy.argtypes = [vp]
         L.si_version.restype = ctypes.c_char_p
         f64, pd = ctypes.c_double, ctypes.POINTER(ctypes.c_double)
         pm, pp, pt = ctypes.POINTER(si_perf_model_t), ctypes.POINTER(si_problem_t), ctypes.POINTER(si_task_times_t)
@@ -252,6 +259,26 @@ def si_cc_compute(x, idx, w, n_experts, routed, expert_stride, n_cc_chunks, shar
 
 def si_layer_destroy(layer):
     lib().si_layer_destroy(layer)
+
+
+def si_stack_create(layers):
+    """layers: list of layer handles; returns the opaque stack handle."""
+    arr = (ctypes.c_void_p * len(layers))(*layers)
+    out = ctypes.c_void_p(None)
+    _check(lib().si_stack_create(arr, len(layers), ctypes.byref(out)))
+    return out.value
+
+
+def si_stack_forward(stack, x_ptr, logits_ptrs, T, n_g, mode, h_out_ptr, prefetch=1, stream=0):
+    """logits_ptrs: None, or one device address (or None) per layer.  prefetch: bit 0 next layer, bit 1 wrap-around."""
+    arr = None
+    if logits_ptrs is not None:
+        arr = (ctypes.c_void_p * len(logits_ptrs))(*logits_ptrs)
+    _check(lib().si_stack_forward(stack, x_ptr, arr, T, n_g, mode, h_out_ptr, int(prefetch), stream))
+
+
+def si_stack_destroy(stack):
+    lib().si_stack_destroy(stack)
 
 
 # ---------------------------------------------------------------- scheinfer_solver.h

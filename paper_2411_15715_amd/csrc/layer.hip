@@ -128,6 +128,12 @@ struct si_layer {
   std::vector<hipEvent_t> ev_ready, ev_free;
   std::vector<char> slot_used;
   long piece_counter = 0;
+  // CG pieces copied ahead of the forward call that will use them (cross-layer prefetch in a stack):
+  // the first pre_n pieces of the CG part, cut for path pre_path, sit in slots pre_slot[0..pre_n)
+  int pre_n = 0, pre_path = 0;
+  std::vector<int> pre_slot;
+  bool segs_preloaded = false;   // this call's event list already holds the prefetch copies
+  si_layer* chain_next = nullptr;  // layer whose CG copies are issued once this call's own are (set by the stack)
   hipStream_t copy_stream = nullptr;
   hipEvent_t ev_host = nullptr;
   // device workspaces
@@ -470,8 +476,49 @@ int si_route(const float* logits_dev, int32_t T, int32_t E, int32_t k, const si_
   return SI_OK;
 }
 
-// One staged piece: chunks [c0, c0+n) of one expert's host range.
-struct Piece { int expert; int c0, n; int part; /* 1 = CG, 2 = CC (CG') */ };
+}  // extern "C"
+
+namespace {
+
+// chunks per j-slot of the decode down projection: at most DOWN_SLOTS slots per part, and at least 8 chunks
+// (256 KB of weights per block) so that small experts do not shatter into tiny blocks
+int cps_of(int ch) { return std::max(1, std::max(ceil_div(ch, DOWN_SLOTS), std::min(8, ch))); }
+
+// chunks per staged piece of a part with `cps` chunks per j-slot
+int piece_chunks(const si_layer* L, int path, int cps) {
+  return path == SI_DECODE ? std::max(cps, L->stage_chunks / cps * cps) : L->stage_chunks;
+}
+
+// Copy the first CG pieces of a dense layer into its staging ring ahead of its forward call (as many as the
+// ring has slots).  Only dense layers without a shared expert: which experts of an MoE layer are streamed is
+// known only after its own token assignment.
+int prefetch_cg(si_layer* N, int path) {
+  if (N->E != 1 || N->has_shared || N->ch_cg <= 0 || N->pre_n > 0) return SI_OK;
+  HIP_TRY(hipSetDevice(N->device));
+  const int piece_max = piece_chunks(N, path, cps_of(N->ch_cg));
+  const uint16_t* hbase = N->h_routed;
+  if (N->profiling) { N->ev_used = 0; N->segs.clear(); N->segs_preloaded = true; }
+  N->pre_slot.clear();
+  for (int c = 0; c < N->ch_cg && (int)N->pre_slot.size() < N->n_stage; c += piece_max) {
+    const int n = std::min(piece_max, N->ch_cg - c);
+    const int slot = (int)(N->piece_counter++ % N->n_stage);
+    if (N->slot_used[slot]) HIP_TRY(hipStreamWaitEvent(N->copy_stream, N->ev_free[slot], 0));
+    {
+      SegScope sc(N, N->copy_stream, SEG_COPY);
+      HIP_TRY(hipMemcpyAsync(N->d_stage[slot], hbase + (size_t)(N->ch_cc + c) * N->ce, (size_t)n * N->ce * 2, hipMemcpyHostToDevice, N->copy_stream));
+    }
+    HIP_TRY(hipEventRecord(N->ev_ready[slot], N->copy_stream));
+    N->pre_slot.push_back(slot);
+  }
+  N->pre_n = (int)N->pre_slot.size();
+  N->pre_path = path;
+  return SI_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
 
 int si_layer_forward(si_layer_t* L, const void* x_dev, const float* logits_dev, int32_t T, int32_t n_g, int32_t mode,
                      float* y_dev, const si_routing_out_t* rout, void* stream_v) {
@@ -501,9 +548,10 @@ int si_layer_forward(si_layer_t* L, const void* x_dev, const float* logits_dev, 
   // rows per GEMM tile: 256 when experts have many rows (MFMA bound), smaller when the GEMM only streams weights
   auto pick_bm = [](int rows) { return rows >= 192 ? 256 : (rows >= 96 ? 128 : 64); };
   const int bm_call = pick_bm(ceil_div(T * k, E));
-  L->ev_used = 0;
+  if (!L->segs_preloaded) { L->ev_used = 0; L->segs.clear(); }
+  L->segs_preloaded = false;
   L->in_staged = 0;
-  L->segs.clear();
+  if (L->pre_n > 0 && L->pre_path != path) L->pre_n = 0;  // cut for the other path: copy again
   si_stats_t st{};
   st.path = path;
   st.n_touched = -1;
@@ -557,9 +605,6 @@ int si_layer_forward(si_layer_t* L, const void* x_dev, const float* logits_dev, 
   auto rows_x2 = [&](int e) { return need_sync ? L->hcount[e] - L->hcount[EX + e] : n_g; };
   const int max_touched = std::min(EX, T * k + L->has_shared);
   const int tiles_upper = (T * k) / bm_call + E;  // bound on the routed row tiles
-  // chunks per j-slot of the decode down projection: at most DOWN_SLOTS slots per part, and at least 8 chunks
-  // (256 KB of weights per block) so that small experts do not shatter into tiny blocks
-  auto cps_of = [](int ch) { return std::max(1, std::max(ceil_div(ch, DOWN_SLOTS), std::min(8, ch))); };
   const int cps_gg = cps_of(L->ch_gg), cps_cg = cps_of(L->ch_cg), cps_cc = cps_of(L->ch_cc);
   const int scps_gg = cps_of(L->sch_gg), scps_cg = cps_of(L->sch_cg), scps_cc = cps_of(L->sch_cc);
   const size_t slot_stride = (size_t)L->rows_dec * M;
@@ -649,16 +694,21 @@ int si_layer_forward(si_layer_t* L, const void* x_dev, const float* logits_dev, 
         if (part == 2 && (!need_cgp || rows_x2(e) <= 0)) continue;
         const int pc0 = part == 2 ? 0 : n_cc_e, pn = part == 2 ? n_cc_e : n_cg_e;
         const int cps = sh ? (part == 2 ? scps_cc : scps_cg) : (part == 2 ? cps_cc : cps_cg);
-        const int piece_max = path == SI_DECODE ? std::max(cps, L->stage_chunks / cps * cps) : L->stage_chunks;
+        const int piece_max = piece_chunks(L, path, cps);
         for (int c = 0; c < pn; c += piece_max) {
           const int n = std::min(piece_max, pn - c);
-          const int slot = (int)(L->piece_counter++ % L->n_stage);
-          if (L->slot_used[slot]) HIP_TRY(hipStreamWaitEvent(L->copy_stream, L->ev_free[slot], 0));
-          {
-            SegScope sc(L, L->copy_stream, SEG_COPY);
-            HIP_TRY(hipMemcpyAsync(L->d_stage[slot], hbase + (size_t)(pc0 + c) * ce, (size_t)n * ce * 2, hipMemcpyHostToDevice, L->copy_stream));
+          int slot;
+          if (part == 1 && !sh && c / piece_max < L->pre_n) {
+            slot = L->pre_slot[c / piece_max];  // already on its way (prefetched after the previous layer's copies)
+          } else {
+            slot = (int)(L->piece_counter++ % L->n_stage);
+            if (L->slot_used[slot]) HIP_TRY(hipStreamWaitEvent(L->copy_stream, L->ev_free[slot], 0));
+            {
+              SegScope sc(L, L->copy_stream, SEG_COPY);
+              HIP_TRY(hipMemcpyAsync(L->d_stage[slot], hbase + (size_t)(pc0 + c) * ce, (size_t)n * ce * 2, hipMemcpyHostToDevice, L->copy_stream));
+            }
+            HIP_TRY(hipEventRecord(L->ev_ready[slot], L->copy_stream));
           }
-          HIP_TRY(hipEventRecord(L->ev_ready[slot], L->copy_stream));
           HIP_TRY(hipStreamWaitEvent(stream, L->ev_ready[slot], 0));
           {
             L->in_staged = 1;
@@ -673,6 +723,14 @@ int si_layer_forward(si_layer_t* L, const void* x_dev, const float* logits_dev, 
         }
       }
     }
+  }
+
+  L->pre_n = 0;
+  // ---- cross-layer prefetch: this call's copies are all enqueued; before blocking on the CC workers put the
+  //      next layer's first CG pieces on the link so that it never idles between layers
+  if (L->chain_next) {
+    int rc = prefetch_cg(L->chain_next, path);
+    if (rc) return rc;
   }
 
   // ---- CC result: wait for Stream-A, send Y^CC to the GPU
@@ -736,6 +794,121 @@ int si_layer_stats(si_layer_t* L, si_stats_t* out) {
     st.overlap = st.total_ms > 0.f ? mx / st.total_ms : 0.f;
   }
   *out = st;
+  return SI_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
+// A stack of layers run back to back (the MLP / MoE blocks of consecutive Transformer layers with the
+// residual connection around each; attention is outside this library): x_{l+1} = bf16(x_l + y_l).
+// ------------------------------------------------------------------------------------------------
+}  // extern "C"
+
+struct si_stack {
+  std::vector<si_layer*> layers;
+  int M = 0, max_T = 0, device = 0;
+  uint16_t* d_x[2] = {nullptr, nullptr};  // hidden state between layers, bf16 [max_T][M]
+  float* d_y = nullptr;                   // layer output, f32 [max_T][M]
+};
+
+namespace {
+
+// out_bf16 (if not null) = bf16(x + y), out_f32 (if not null) = x + y; 8 elements per thread
+__global__ __launch_bounds__(256) void k_residual(const uint16_t* __restrict__ x, const float* __restrict__ y, size_t n8,
+                                                   uint16_t* __restrict__ out_bf16, float* __restrict__ out_f32) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= n8) return;
+  const uint4 xv = reinterpret_cast<const uint4*>(x)[i];
+  const float4 y0 = reinterpret_cast<const float4*>(y)[2 * i], y1 = reinterpret_cast<const float4*>(y)[2 * i + 1];
+  const uint32_t xw[4] = {xv.x, xv.y, xv.z, xv.w};
+  const float yv[8] = {y0.x, y0.y, y0.z, y0.w, y1.x, y1.y, y1.z, y1.w};
+  float r[8];
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    r[2 * q] = __uint_as_float(xw[q] << 16) + yv[2 * q];
+    r[2 * q + 1] = __uint_as_float(xw[q] & 0xffff0000u) + yv[2 * q + 1];
+  }
+  if (out_f32) {
+    reinterpret_cast<float4*>(out_f32)[2 * i] = make_float4(r[0], r[1], r[2], r[3]);
+    reinterpret_cast<float4*>(out_f32)[2 * i + 1] = make_float4(r[4], r[5], r[6], r[7]);
+  }
+  if (out_bf16) {
+    uint32_t o[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      uint32_t a = __float_as_uint(r[2 * q]), b = __float_as_uint(r[2 * q + 1]);
+      a += 0x7fffu + ((a >> 16) & 1u);  // round to nearest even
+      b += 0x7fffu + ((b >> 16) & 1u);
+      o[q] = (a >> 16) | (b & 0xffff0000u);
+    }
+    reinterpret_cast<uint4*>(out_bf16)[i] = make_uint4(o[0], o[1], o[2], o[3]);
+  }
+}
+
+}  // namespace
+
+extern "C" {
+
+int si_stack_create(si_layer_t* const* layers, int32_t n_layers, si_stack_t** out) {
+  if (!layers || !out || n_layers < 1) return fail(SI_EINVAL, "si_stack_create: need layers, out and n_layers >= 1");
+  for (int i = 0; i < n_layers; ++i) {
+    if (!layers[i]) return fail(SI_EINVAL, "si_stack_create: layer %d is NULL", i);
+    if (layers[i]->M != layers[0]->M || layers[i]->device != layers[0]->device)
+      return fail(SI_EINVAL, "si_stack_create: layer %d differs from layer 0 in d_model or device", i);
+    for (int j = 0; j < i; ++j)
+      if (layers[j] == layers[i]) return fail(SI_EINVAL, "si_stack_create: layer %d appears twice", i);
+  }
+  si_stack* S = new (std::nothrow) si_stack();
+  if (!S) return fail(SI_ENOMEM, "si_stack_create: out of host memory");
+  S->layers.assign(layers, layers + n_layers);
+  S->M = layers[0]->M;
+  S->device = layers[0]->device;
+  S->max_T = layers[0]->max_T;
+  for (int i = 1; i < n_layers; ++i) S->max_T = std::min(S->max_T, layers[i]->max_T);
+  hipError_t e = hipSetDevice(S->device);
+  int rc = e == hipSuccess ? SI_OK : fail(SI_EHIP, "hipSetDevice failed: %s", hipGetErrorString(e));
+  const size_t n = (size_t)S->max_T * S->M;
+  if (rc == SI_OK) rc = dev_alloc(&S->d_x[0], n);
+  if (rc == SI_OK) rc = dev_alloc(&S->d_x[1], n);
+  if (rc == SI_OK) rc = dev_alloc(&S->d_y, n);
+  if (rc != SI_OK) { si_stack_destroy(S); return rc; }
+  *out = S;
+  return SI_OK;
+}
+
+void si_stack_destroy(si_stack_t* S) {
+  if (!S) return;
+  (void)hipSetDevice(S->device);
+  for (auto* p : S->d_x) if (p) (void)hipFree(p);
+  if (S->d_y) (void)hipFree(S->d_y);
+  delete S;
+}
+
+int si_stack_forward(si_stack_t* S, const void* x_dev, const float* const* logits_dev, int32_t T, int32_t n_g, int32_t mode,
+                     float* h_out_dev, int32_t prefetch, void* stream_v) {
+  if (!S) return fail(SI_EINVAL, "stack is NULL");
+  if (T < 0 || T > S->max_T) return fail(SI_ESTATE, "T=%d outside [0, %d]", T, S->max_T);
+  if (T == 0) return SI_OK;
+  if (!x_dev || !h_out_dev) return fail(SI_EINVAL, "x_dev or h_out_dev is NULL");
+  HIP_TRY(hipSetDevice(S->device));
+  hipStream_t stream = (hipStream_t)stream_v;
+  const int nl = (int)S->layers.size();
+  const size_t n8 = (size_t)T * S->M / 8;
+  const uint16_t* x = static_cast<const uint16_t*>(x_dev);
+  for (int l = 0; l < nl; ++l) {
+    si_layer* L = S->layers[l];
+    const float* lg = logits_dev ? logits_dev[l] : nullptr;
+    // bit 0: layer l+1 after layer l; bit 1: layer 0 (for the next call) after the last layer
+    L->chain_next = ((prefetch & 1) && l + 1 < nl) ? S->layers[l + 1] : ((prefetch & 2) && l + 1 == nl) ? S->layers[0] : nullptr;
+    const int rc = si_layer_forward(L, x, lg, T, n_g, mode, S->d_y, nullptr, stream_v);
+    L->chain_next = nullptr;
+    if (rc != SI_OK) return rc;
+    const bool last = l + 1 == nl;
+    uint16_t* xn = last ? nullptr : S->d_x[l & 1];
+    hipLaunchKernelGGL(k_residual, dim3((unsigned)((n8 + 255) / 256)), dim3(256), 0, stream, x, S->d_y, n8, xn,
+                       last ? h_out_dev : nullptr);
+    HIP_TRY(hipGetLastError());
+    x = xn;
+  }
   return SI_OK;
 }
 

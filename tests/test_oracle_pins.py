@@ -392,3 +392,40 @@ def test_threads_do_not_change_result(oracle):
     y4 = oracle.layer_forward(xb, w["w_gate"], w["w_up"], w["w_down"])
     oracle.set_threads(n0)
     assert np.array_equal(y1, y4)  # each j and each m-block is summed by one thread in the same order
+
+
+# ------------------------------------------------------------------ layer stack (residual chain)
+def test_round_to_bf16_against_bit_arithmetic_and_ties(oracle):
+    rng = np.random.default_rng(17)
+    v32 = (rng.standard_normal(20000) * np.exp(rng.uniform(-8, 8, 20000))).astype(np.float32)
+    # float32 inputs: the integer rounding trick on the bit pattern is an independent implementation
+    assert np.array_equal(oracle.round_to_bf16(v32.astype(np.float64)), synth.f32_to_bf16_bits(v32))
+    # exact ties go to the even mantissa: 1 + 2^-8 -> 1.0, 1 + 3*2^-8 -> 1 + 2^-6
+    assert oracle.round_to_bf16(np.array([1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8, -(1.0 + 2.0 ** -8)])).tolist() == \
+        [0x3F80, 0x3F82, 0xBF80]
+    # a float64 just above a tie rounds up although its float32 rounding would sit on the tie
+    assert oracle.round_to_bf16(np.array([1.0 + 2.0 ** -8 + 2.0 ** -40])).tolist() == [0x3F81]
+    # representable values are fixed points
+    b = np.arange(0x3F00, 0x4100, dtype=np.uint16)
+    assert np.array_equal(oracle.round_to_bf16(oracle.bf16_to_f64(b)), b)
+
+
+def test_stack_reduces_to_layers(oracle):
+    cfg = synth.scaled(synth.CONFIGS["mixtral_8x7b"], d_model=64, d_ff=128, n_experts=4)
+    w = synth.make_weights(cfg)
+    xb = synth.make_tokens(cfg, 5)
+    lg = synth.make_router_logits(cfg, xb)
+    kw = dict(w_gate=w["w_gate"], w_up=w["w_up"], w_down=w["w_down"], logits=lg, top_k=cfg.top_k)
+    x64 = synth.bf16_bits_to_f64(xb)
+    y0 = oracle.layer_forward(xb, **kw)
+    # one layer: the residual sum, nothing rounded
+    assert np.array_equal(oracle.stack_forward(xb, [kw]), x64 + y0)
+    # two layers written out by hand
+    x1 = synth.f32_to_bf16_bits((x64 + y0).astype(np.float32))   # float32 first: differs from direct rounding only on double-rounding ties
+    x1d = oracle.round_to_bf16(x64 + y0)
+    assert np.mean(x1 != x1d) < 1e-3
+    h2 = synth.bf16_bits_to_f64(x1d) + oracle.layer_forward(x1d, **kw)
+    assert np.array_equal(oracle.stack_forward(xb, [kw, kw]), h2)
+    # a layer with zero down projection passes the hidden state through unchanged
+    kz = dict(kw, w_down=np.zeros_like(w["w_down"]))
+    assert np.array_equal(oracle.stack_forward(xb, [kz, kz, kz]), x64)
