@@ -56,6 +56,10 @@ def parse_args():
                     help="instead of the throughput line: profile this machine (Eq. 3), solve r_CG* for the config's "
                          "r_GG and n_g* for its prompt length (Section IV), and measure the layer over a sweep of "
                          "r_CG and of n_g next to the solved values")
+    ap.add_argument("--stack", type=int, default=0,
+                    help="instead of the throughput line: a stack of this many layers of the config's shape under GPU-memory "
+                         "budgets of 25/50/75 %% of its weights; greedy per-layer r_GG (Section IV-A.4) against the same "
+                         "r_GG for every layer, decode step measured with and without cross-layer prefetch")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="first run a plain elementwise copy of 1 GiB (reads 1 GiB, writes 1 GiB) three times: "
                          "the reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE counters")
@@ -362,6 +366,75 @@ def solver_study(args, si, torch, cfg, w, r_gg):
     print(json.dumps(out))
 
 
+def stack_study(args, si, torch, cfg, w):
+    """Section IV-A.4 end to end: profile, t_fin*(r_GG = i/n_G) from the slicing-rate solve, greedy assignment of
+    a GPU-memory budget over the layers of a stack, and the measured generation step of the stack against the
+    uniform assignment of the same budget (the paper's memory-assignment ablation, Section V-E.3)."""
+    M, H, E, k = cfg.d_model, cfg.d_ff, cfg.n_experts, cfg.top_k
+    assert E == 1 and not cfg.d_ff_shared, "--stack is set up for dense layers"
+    n_layers, n_G = args.stack, 8
+    T = cfg.t_decode
+    dev = torch.device("cuda:0")
+    stream = torch.cuda.current_stream().cuda_stream
+    prof = si.si_profile(M, H, T, mode=si.SI_DECODE, n_sizes=6, reps=5)
+    n_gemm, n_w, n_l, step = float(T) * M * H, 2.0 * M * H, 3, 64.0 / H
+    sols = [si.si_solve_split(prof["model"], n_gemm, n_w, n_l, i / n_G, r_step=step) for i in range(n_G + 1)]
+    t_star = [s["t_fin"] for s in sols]
+    n_m = 3.0 * n_w
+    x = torch.from_numpy(synth_tokens(cfg, T).view(np.int16)).to(dev)
+    out = torch.empty((T, M), dtype=torch.float32, device=dev)
+
+    def run(r_ggs):
+        layers = []
+        try:
+            for r_gg in r_ggs:
+                sol = si.si_solve_split(prof["model"], n_gemm, n_w, n_l, r_gg, r_step=step)
+                r_cg = sol["r_cg"]
+                layers.append(si.si_layer_create(M, H, 1, 1, w["w_gate"], w["w_up"], w["w_down"], r_gg, r_cg,
+                                                 max(0.0, 1.0 - r_gg - r_cg), T))
+            st = si.si_stack_create(layers)
+            res = {}
+            for name, pf in (("prefetch", 3), ("no_prefetch", 0)):
+                ts = []
+                for i in range(8):
+                    torch.cuda.synchronize()
+                    t0 = time.perf_counter()
+                    si.si_stack_forward(st, x.data_ptr(), None, T, 0, si.SI_DECODE, out.data_ptr(), prefetch=pf, stream=stream)
+                    torch.cuda.synchronize()
+                    if i >= 2:
+                        ts.append(time.perf_counter() - t0)
+                res[name] = float(np.median(ts))
+            si.si_stack_destroy(st)
+            return res
+        finally:
+            for l in layers:
+                si.si_layer_destroy(l)
+
+    rows = []
+    for frac in (0.25, 0.5, 0.75):
+        budget = frac * n_layers * n_m
+        pick = si.si_assign_gpu_memory([t_star] * n_layers, [n_m] * n_layers, budget)
+        greedy = [p / n_G for p in pick]
+        uniform = [frac] * n_layers
+        model_greedy = sum(t_star[p] for p in pick)
+        model_uniform = n_layers * si.si_solve_split(prof["model"], n_gemm, n_w, n_l, frac, r_step=step)["t_fin"]
+        mg, mu = run(greedy), run(uniform)
+        rows.append({"budget_fraction": frac, "greedy_r_gg": greedy,
+                     "greedy_ms": round(1e3 * mg["prefetch"], 3), "greedy_no_prefetch_ms": round(1e3 * mg["no_prefetch"], 3),
+                     "uniform_ms": round(1e3 * mu["prefetch"], 3), "uniform_no_prefetch_ms": round(1e3 * mu["no_prefetch"], 3),
+                     "model_greedy_ms": round(1e3 * model_greedy, 3), "model_uniform_ms": round(1e3 * model_uniform, 3),
+                     "speedup_greedy_over_uniform": round(mu["prefetch"] / mg["prefetch"], 3),
+                     "speedup_prefetch": round(mg["no_prefetch"] / mg["prefetch"], 3)})
+    print(json.dumps({"stack_study": cfg.name, "layers": n_layers, "n_G": n_G, "tokens": T, "model": prof["model"],
+                      "t_star_ms_by_r_gg": [round(1e3 * t, 4) for t in t_star],
+                      "r_cg_star_by_r_gg": [round(s["r_cg"], 4) for s in sols], "budgets": rows}))
+
+
+def synth_tokens(cfg, T):
+    import synth
+    return synth.make_tokens(cfg, T, stream=7)
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -387,6 +460,9 @@ def main():
     w = synth.make_weights(cfg, threads=min(16, os.cpu_count() or 8))
     if args.solve:
         solver_study(args, si, torch, cfg, w, split[0])
+        return
+    if args.stack:
+        stack_study(args, si, torch, cfg, w)
         return
     wl = Workload(cfg, args.decode_calls)
     t_gen = time.perf_counter() - t0

@@ -215,8 +215,10 @@ void si_layer_destroy(si_layer_t* layer);
  * token generation); they are used if that call takes the same path (decode / prefill) and copied again if not.
  *
  * si_stack_create: `layers` HOST array of n_layers >= 1 distinct layer handles with equal d_model on one
- *   device.  The stack borrows the layers (the caller destroys them after the stack) and owns two bf16
- *   hidden-state buffers and one fp32 output buffer of max_tokens x d_model (the smallest max_tokens).
+ *   device.  The stack borrows the layers (the caller destroys them after the stack; a layer belongs to at
+ *   most one stack at a time) and owns two bf16 hidden-state buffers, one fp32 output buffer of max_tokens x
+ *   d_model (the smallest max_tokens) and one copy stream that all its layers use while the stack exists, so
+ *   that weight copies cross the host link in the order they were enqueued.
  * si_stack_forward: x_dev DEVICE bf16 [T][d_model]; logits_dev HOST array of n_layers DEVICE pointers
  *   (f32 [T][n_experts] of each layer; entries of dense layers and the array itself may be NULL when every
  *   layer is dense); n_g, mode, stream as in si_layer_forward, applied to every layer; h_out_dev DEVICE

@@ -134,7 +134,8 @@ struct si_layer {
   std::vector<int> pre_slot;
   bool segs_preloaded = false;   // this call's event list already holds the prefetch copies
   si_layer* chain_next = nullptr;  // layer whose CG copies are issued once this call's own are (set by the stack)
-  hipStream_t copy_stream = nullptr;
+  hipStream_t copy_stream = nullptr;      // Stream-C in use: the layer's own, or its stack's
+  hipStream_t own_copy_stream = nullptr;  // the one this layer created and destroys
   hipEvent_t ev_host = nullptr;
   // device workspaces
   char* d_plan = nullptr;
@@ -281,6 +282,7 @@ void si_layer_destroy(si_layer_t* L) {
   if (L->pool) cc_pool_destroy(L->pool);
   if (L->copy_stream) { (void)hipStreamSynchronize(L->copy_stream); }
   (void)hipDeviceSynchronize();
+  L->copy_stream = L->own_copy_stream;
   for (auto p : L->d_stage) if (p) (void)hipFree(p);
   for (auto e : L->ev_ready) if (e) (void)hipEventDestroy(e);
   for (auto e : L->ev_free) if (e) (void)hipEventDestroy(e);
@@ -388,6 +390,7 @@ int si_layer_create(const si_layer_desc_t* desc, const uint16_t* w_gate, const u
     }
   }
   HIP_OR_DESTROY(hipStreamCreateWithFlags(&L->copy_stream, hipStreamNonBlocking));
+  L->own_copy_stream = L->copy_stream;
   HIP_OR_DESTROY(hipEventCreateWithFlags(&L->ev_host, hipEventDisableTiming));
   HIP_OR_DESTROY(hipEventCreate(&L->ev_t0));
   HIP_OR_DESTROY(hipEventCreate(&L->ev_t1));
@@ -808,6 +811,10 @@ struct si_stack {
   int M = 0, max_T = 0, device = 0;
   uint16_t* d_x[2] = {nullptr, nullptr};  // hidden state between layers, bf16 [max_T][M]
   float* d_y = nullptr;                   // layer output, f32 [max_T][M]
+  // One Stream-C for the whole stack: copies run in the order they are enqueued, so the pieces prefetched for
+  // layer l+1 queue up behind layer l's own instead of sharing the link with them (which would hold back
+  // layer l, and with it the start of layer l+1's CPU part).
+  hipStream_t copy_stream = nullptr;
 };
 
 namespace {
@@ -870,7 +877,13 @@ int si_stack_create(si_layer_t* const* layers, int32_t n_layers, si_stack_t** ou
   if (rc == SI_OK) rc = dev_alloc(&S->d_x[0], n);
   if (rc == SI_OK) rc = dev_alloc(&S->d_x[1], n);
   if (rc == SI_OK) rc = dev_alloc(&S->d_y, n);
-  if (rc != SI_OK) { si_stack_destroy(S); return rc; }
+  if (rc == SI_OK && (e = hipStreamCreateWithFlags(&S->copy_stream, hipStreamNonBlocking)) != hipSuccess)
+    rc = fail(SI_EHIP, "hipStreamCreateWithFlags failed: %s", hipGetErrorString(e));
+  if (rc != SI_OK) { S->layers.clear(); si_stack_destroy(S); return rc; }
+  for (si_layer* L : S->layers) {
+    (void)hipStreamSynchronize(L->copy_stream);
+    L->copy_stream = S->copy_stream;
+  }
   *out = S;
   return SI_OK;
 }
@@ -878,6 +891,9 @@ int si_stack_create(si_layer_t* const* layers, int32_t n_layers, si_stack_t** ou
 void si_stack_destroy(si_stack_t* S) {
   if (!S) return;
   (void)hipSetDevice(S->device);
+  if (S->copy_stream) (void)hipStreamSynchronize(S->copy_stream);
+  for (si_layer* L : S->layers) { L->copy_stream = L->own_copy_stream; L->pre_n = 0; }
+  if (S->copy_stream) (void)hipStreamDestroy(S->copy_stream);
   for (auto* p : S->d_x) if (p) (void)hipFree(p);
   if (S->d_y) (void)hipFree(S->d_y);
   delete S;
