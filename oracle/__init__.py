@@ -44,6 +44,11 @@ def _load():
         L.so_layer_forward.restype = c_i
         L.so_layer_forward.argtypes = [c_p, c_i, c_i, c_i, c_i, c_i, c_p, c_p, c_p, c_p, c_i, c_p, c_p, c_p,
                                        c_i, c_i, c_i, c_i, c_i, c_p, c_i, c_p]
+        L.so_layer_forward_q4.restype = c_i
+        L.so_layer_forward_q4.argtypes = [c_p, c_i, c_i, c_i, c_i, c_i, c_p] + [c_p] * 6 + [c_i] + [c_p] * 6 + \
+                                         [c_i, c_i, c_i, c_i, c_i, c_p, c_i, c_p]
+        L.so_q4_value.restype = c_d
+        L.so_q4_value.argtypes = [c_p, c_p, c_i, c_i, c_i, c_i]
         _lib = L
     return _lib
 
@@ -125,6 +130,43 @@ def layer_forward(x, w_gate, w_up, w_down, logits=None, top_k=1, shared=None, co
     if rc:
         raise ValueError("so_layer_forward failed with code %d" % rc)
     return y
+
+
+def layer_forward_q4(x, wq: dict, logits=None, top_k=1, counts=(0, 0), shared_counts=(0, 0), n_g=0, sel=None) -> np.ndarray:
+    """As layer_forward, for 4-bit weights: wq holds q_gate, q_up, q_down (uint8 [E][H][M/2]), z_gate, z_up
+    (uint16 [E][H][M/64]), z_down (uint16 [E][H/64][M]) and optionally the shared expert's sq_* / sz_*."""
+    x = np.ascontiguousarray(x, dtype=np.uint16)
+    T, M = x.shape
+    q = [np.ascontiguousarray(wq[k], dtype=np.uint8) for k in ("q_gate", "q_up", "q_down")]
+    z = [np.ascontiguousarray(wq[k], dtype=np.uint16) for k in ("z_gate", "z_up", "z_down")]
+    E, H, M2 = q[0].shape
+    assert M2 * 2 == M and z[0].shape == (E, H, M // 64) and z[2].shape == (E, H // 64, M)
+    lg = None
+    if logits is not None:
+        lg = np.ascontiguousarray(logits, dtype=np.float32)
+        assert lg.shape == (T, E)
+    Hs, sq, sz = 0, [None] * 3, [None] * 3
+    if "sq_gate" in wq:
+        sq = [np.ascontiguousarray(wq[k], dtype=np.uint8) for k in ("sq_gate", "sq_up", "sq_down")]
+        sz = [np.ascontiguousarray(wq[k], dtype=np.uint16) for k in ("sz_gate", "sz_up", "sz_down")]
+        Hs = sq[0].shape[0]
+    sel_a = None if sel is None else np.ascontiguousarray(sel, dtype=np.int32)
+    n_out = T if sel_a is None else len(sel_a)
+    y = np.zeros((n_out, M), np.float64)
+    rc = _load().so_layer_forward_q4(_ptr(x), T, M, H, E, int(top_k), _ptr(lg), *[_ptr(a) for a in q + z], Hs,
+                                     *[_ptr(a) for a in sq + sz], int(counts[0]), int(counts[1]),
+                                     int(shared_counts[0]), int(shared_counts[1]), int(n_g), _ptr(sel_a),
+                                     0 if sel_a is None else len(sel_a), _ptr(y))
+    if rc:
+        raise ValueError("so_layer_forward_q4 failed with code %d" % rc)
+    return y
+
+
+def q4_value(q, z, M, which, j, m) -> float:
+    """Dequantised element (which: 0 gate, 1 up, 2 down) of one expert's code / scale arrays."""
+    q = np.ascontiguousarray(q, np.uint8)
+    z = np.ascontiguousarray(z, np.uint16)
+    return float(_load().so_q4_value(_ptr(q), _ptr(z), int(M), int(which), int(j), int(m)))
 
 
 def round_to_bf16(v: np.ndarray) -> np.ndarray:

@@ -128,22 +128,52 @@ int so_route(const float* logits, int T, int E, int k, int32_t* idx, double* w, 
 }
 
 /*
+ * Weights of one SwiGLU MLP, [hidden index j][model index m], in one of two storage forms:
+ *  kind 0: bfloat16 bit patterns g, u, d.
+ *  kind 1: 4-bit codes with group scales (the paper evaluates INT4 models, Section V-A, without naming a
+ *          format; this one is the build's own): code c in 0..15 stands for (c - 8) * scale.
+ *          qg, qu, qd [H][M/2] bytes: element m of row j is the low nibble of byte m/2 for even m, the high
+ *          nibble for odd m.  Scales are bfloat16: sg, su [H][M/64] (one per 64 consecutive m of a row, the
+ *          contraction index of FC1), sd [H/64][M] (one per 64 consecutive j of a column, the contraction
+ *          index of FC2).  The dequantised value is exact in double and is never rounded.
+ */
+typedef struct {
+  int kind;
+  const uint16_t *g, *u, *d;
+  const uint8_t *qg, *qu, *qd;
+  const uint16_t *sg, *su, *sd;
+} mlp_w;
+
+static inline int q4_code(const uint8_t* q, int M, int j, int m) {
+  int b = q[(size_t)j * (M / 2) + m / 2];
+  return (m & 1) ? (b >> 4) : (b & 15);
+}
+
+static inline double w_fc1(const mlp_w* w, int which /* 0 gate, 1 up */, int M, int j, int m) {
+  if (w->kind == 0) return bf16_to_double((which ? w->u : w->g)[(size_t)j * M + m]);
+  return (double)(q4_code(which ? w->qu : w->qg, M, j, m) - 8) *
+         bf16_to_double((which ? w->su : w->sg)[(size_t)j * (M / 64) + m / 64]);
+}
+
+static inline double w_fc2(const mlp_w* w, int M, int j, int m) {
+  if (w->kind == 0) return bf16_to_double(w->d[(size_t)j * M + m]);
+  return (double)(q4_code(w->qd, M, j, m) - 8) * bf16_to_double(w->sd[(size_t)(j / 64) * M + m]);
+}
+
+/*
  * One token through the hidden columns j in [j0, j1) of one SwiGLU MLP:
  *   h_j = SiLU(sum_m x_m Wg[j][m]) * (sum_m x_m Wu[j][m]),   y_m += coef * sum_j h_j Wd[j][m].
  * With [j0,j1) = [0,H) this is the unsliced layer; with a sub-range it is one term of Eq. 2.
  */
-static void mlp_token_range(int M, const uint16_t* wg, const uint16_t* wu,
-                            const uint16_t* wd, int j0, int j1, double coef, double* y, double* h,
+static void mlp_token_range(int M, const mlp_w* w, int j0, int j1, double coef, double* y, double* h,
                             const double* xd /* the token, widened: xd[m] */) {
   if (j1 <= j0) return;
 #pragma omp parallel for schedule(static)
   for (int j = j0; j < j1; ++j) {
-    const uint16_t* gr = wg + (size_t)j * M;
-    const uint16_t* ur = wu + (size_t)j * M;
     double g = 0.0, u = 0.0;
     for (int m = 0; m < M; ++m) {
-      g += xd[m] * bf16_to_double(gr[m]);
-      u += xd[m] * bf16_to_double(ur[m]);
+      g += xd[m] * w_fc1(w, 0, M, j, m);
+      u += xd[m] * w_fc1(w, 1, M, j, m);
     }
     h[j] = so_silu(g) * u;
   }
@@ -154,12 +184,23 @@ static void mlp_token_range(int M, const uint16_t* wg, const uint16_t* wu,
     double acc[256];
     for (int m = m0; m < m1; ++m) acc[m - m0] = 0.0;
     for (int j = j0; j < j1; ++j) {
-      const uint16_t* dr = wd + (size_t)j * M;
       double hj = h[j];
-      for (int m = m0; m < m1; ++m) acc[m - m0] += hj * bf16_to_double(dr[m]);
+      for (int m = m0; m < m1; ++m) acc[m - m0] += hj * w_fc2(w, M, j, m);
     }
     for (int m = m0; m < m1; ++m) y[m] += coef * acc[m - m0];
   }
+}
+
+/* the MLP of expert e inside [E][H][...] arrays of either storage form */
+static mlp_w expert_view(const mlp_w* all, int e, int H, int M) {
+  mlp_w v = *all;
+  if (all->kind == 0) {
+    v.g = all->g + (size_t)e * H * M; v.u = all->u + (size_t)e * H * M; v.d = all->d + (size_t)e * H * M;
+  } else {
+    v.qg = all->qg + (size_t)e * H * (M / 2); v.qu = all->qu + (size_t)e * H * (M / 2); v.qd = all->qd + (size_t)e * H * (M / 2);
+    v.sg = all->sg + (size_t)e * H * (M / 64); v.su = all->su + (size_t)e * H * (M / 64); v.sd = all->sd + (size_t)e * (H / 64) * M;
+  }
+  return v;
 }
 
 /*
@@ -176,10 +217,9 @@ static void mlp_token_range(int M, const uint16_t* wg, const uint16_t* wu,
  *  y        [n_sel or T][M] double, overwritten.
  * Returns 0 or a negative error code (so_route's, or -1).
  */
-int so_layer_forward(const uint16_t* x, int T, int M, int H, int E, int k, const float* logits,
-                     const uint16_t* wg, const uint16_t* wu, const uint16_t* wd, int Hs,
-                     const uint16_t* sg, const uint16_t* su, const uint16_t* sd, int n_cc, int n_cg,
-                     int s_cc, int s_cg, int n_g, const int32_t* sel, int n_sel, double* y) {
+static int layer_forward_core(const uint16_t* x, int T, int M, int H, int E, int k, const float* logits,
+                              const mlp_w* routed, int Hs, const mlp_w* shared, int n_cc, int n_cg,
+                              int s_cc, int s_cg, int n_g, const int32_t* sel, int n_sel, double* y) {
   if (T < 0 || M <= 0 || H <= 0 || E <= 0 || k <= 0 || k > E) return -1;
   if (n_cc < 0 || n_cg < 0 || n_cc + n_cg > H || n_g < 0 || n_g > T) return -1;
   if (Hs > 0 && (s_cc < 0 || s_cg < 0 || s_cc + s_cg > Hs)) return -1;
@@ -217,17 +257,15 @@ int so_layer_forward(const uint16_t* x, int T, int M, int H, int E, int k, const
     for (int s = 0; s < k; ++s) {
       int e = idx[(size_t)t * k + s];
       double c = w[(size_t)t * k + s];
-      const uint16_t* g = wg + (size_t)e * H * M;
-      const uint16_t* u = wu + (size_t)e * H * M;
-      const uint16_t* d = wd + (size_t)e * H * M;
-      mlp_token_range(M, g, u, d, 0, n_cc, c, part[0], h, xd);
-      mlp_token_range(M, g, u, d, n_cc, n_cc + n_cg, c, part[1], h, xd);
-      mlp_token_range(M, g, u, d, n_cc + n_cg, H, c, part[2], h, xd);
+      const mlp_w we = expert_view(routed, e, H, M);
+      mlp_token_range(M, &we, 0, n_cc, c, part[0], h, xd);
+      mlp_token_range(M, &we, n_cc, n_cc + n_cg, c, part[1], h, xd);
+      mlp_token_range(M, &we, n_cc + n_cg, H, c, part[2], h, xd);
     }
     if (Hs > 0) {
-      mlp_token_range(M, sg, su, sd, 0, s_cc, 1.0, part[0], h, xd);
-      mlp_token_range(M, sg, su, sd, s_cc, s_cc + s_cg, 1.0, part[1], h, xd);
-      mlp_token_range(M, sg, su, sd, s_cc + s_cg, Hs, 1.0, part[2], h, xd);
+      mlp_token_range(M, shared, 0, s_cc, 1.0, part[0], h, xd);
+      mlp_token_range(M, shared, s_cc, s_cc + s_cg, 1.0, part[1], h, xd);
+      mlp_token_range(M, shared, s_cc + s_cg, Hs, 1.0, part[2], h, xd);
     }
     double* yo = y + (size_t)i * M;
     for (int m = 0; m < M; ++m) yo[m] = part[0][m] + part[1][m] + part[2][m];
@@ -235,4 +273,34 @@ int so_layer_forward(const uint16_t* x, int T, int M, int H, int E, int k, const
   for (int p = 0; p < 3; ++p) free(part[p]);
   free(xd); free(h); free(idx); free(w);
   return 0;
+}
+
+int so_layer_forward(const uint16_t* x, int T, int M, int H, int E, int k, const float* logits,
+                     const uint16_t* wg, const uint16_t* wu, const uint16_t* wd, int Hs,
+                     const uint16_t* sg, const uint16_t* su, const uint16_t* sd, int n_cc, int n_cg,
+                     int s_cc, int s_cg, int n_g, const int32_t* sel, int n_sel, double* y) {
+  mlp_w routed = {0, wg, wu, wd, NULL, NULL, NULL, NULL, NULL, NULL};
+  mlp_w shared = {0, sg, su, sd, NULL, NULL, NULL, NULL, NULL, NULL};
+  return layer_forward_core(x, T, M, H, E, k, logits, &routed, Hs, &shared, n_cc, n_cg, s_cc, s_cg, n_g, sel, n_sel, y);
+}
+
+/*
+ * The same layer with 4-bit weights (storage form 1 above): q* are the code arrays, z* the scale arrays of
+ * the routed experts ([E] leading) and of the shared expert.  M and H (and Hs) must be multiples of 64.
+ */
+int so_layer_forward_q4(const uint16_t* x, int T, int M, int H, int E, int k, const float* logits,
+                        const uint8_t* qg, const uint8_t* qu, const uint8_t* qd, const uint16_t* zg,
+                        const uint16_t* zu, const uint16_t* zd, int Hs, const uint8_t* sqg, const uint8_t* squ,
+                        const uint8_t* sqd, const uint16_t* szg, const uint16_t* szu, const uint16_t* szd,
+                        int n_cc, int n_cg, int s_cc, int s_cg, int n_g, const int32_t* sel, int n_sel, double* y) {
+  if (M % 64 != 0 || H % 64 != 0 || Hs % 64 != 0) return -1;
+  mlp_w routed = {1, NULL, NULL, NULL, qg, qu, qd, zg, zu, zd};
+  mlp_w shared = {1, NULL, NULL, NULL, sqg, squ, sqd, szg, szu, szd};
+  return layer_forward_core(x, T, M, H, E, k, logits, &routed, Hs, &shared, n_cc, n_cg, s_cc, s_cg, n_g, sel, n_sel, y);
+}
+
+/* Dequantised value of one element (test hook for the pins): which = 0 gate, 1 up, 2 down. */
+double so_q4_value(const uint8_t* q, const uint16_t* z, int M, int which, int j, int m) {
+  mlp_w w = {1, NULL, NULL, NULL, q, q, q, z, z, z};
+  return which == 2 ? w_fc2(&w, M, j, m) : w_fc1(&w, which, M, j, m);
 }

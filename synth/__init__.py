@@ -122,6 +122,55 @@ def make_weights(cfg: LayerConfig, threads: int = 8) -> dict:
     return w
 
 
+def _codes_chunk(seed: int, tid: int, chunk: int, n_bytes: int, out: np.ndarray) -> None:
+    g = np.random.Generator(np.random.PCG64(np.random.SeedSequence([seed, tid, chunk, 4])))
+    # codes of a bell-shaped weight distribution: round(2.4 z) + 8 clipped to 0..15, two per byte
+    z = g.standard_normal(2 * n_bytes, dtype=np.float32)
+    c = np.clip(np.rint(z * np.float32(2.4)) + 8, 0, 15).astype(np.uint8)
+    out[:] = c[0::2] | (c[1::2] << np.uint8(4))
+
+
+def codes_u4(seed: int, tid: int, shape, threads: int = 8) -> np.ndarray:
+    """Packed 4-bit codes (uint8, two per byte, low nibble first) of the given shape (last dim = bytes)."""
+    n = int(np.prod(shape))
+    out = np.empty(n, dtype=np.uint8)
+    jobs = [(c, min(_CHUNK, n - c * _CHUNK)) for c in range((n + _CHUNK - 1) // _CHUNK)]
+    with ThreadPoolExecutor(max_workers=max(1, threads)) as ex:
+        list(ex.map(lambda cm: _codes_chunk(seed, tid, cm[0], cm[1], out[cm[0] * _CHUNK:cm[0] * _CHUNK + cm[1]]), jobs))
+    return out.reshape(shape)
+
+
+def scales_bf16(seed: int, tid: int, shape, mean: float) -> np.ndarray:
+    """Positive group scales around ``mean`` (uniform in [0.7, 1.3] x mean) as bf16 bit patterns."""
+    g = np.random.Generator(np.random.PCG64(np.random.SeedSequence([seed, tid, 0, 16])))
+    return f32_to_bf16_bits((g.uniform(0.7, 1.3, size=shape) * mean).astype(np.float32))
+
+
+def make_weights_q4(cfg: LayerConfig, threads: int = 8) -> dict:
+    """Expert weights in 4-bit storage: codes q_* [E][H][M/2] (uint8, element m in byte m/2, low nibble for even
+    m), scales z_gate / z_up [E][H][M/64] and z_down [E][H/64][M] (bf16 bit patterns).  The standard deviation
+    of the weights the codes stand for is about cfg.w_std (scale mean = w_std / 2.4)."""
+    E, H, M = cfg.n_experts, cfg.d_ff, cfg.d_model
+    zm = cfg.w_std / 2.4
+    w = {
+        "q_gate": codes_u4(cfg.seed, TID_WG, (E, H, M // 2), threads),
+        "q_up": codes_u4(cfg.seed, TID_WU, (E, H, M // 2), threads),
+        "q_down": codes_u4(cfg.seed, TID_WD, (E, H, M // 2), threads),
+        "z_gate": scales_bf16(cfg.seed, TID_WG, (E, H, M // 64), zm),
+        "z_up": scales_bf16(cfg.seed, TID_WU, (E, H, M // 64), zm),
+        "z_down": scales_bf16(cfg.seed, TID_WD, (E, H // 64, M), zm),
+    }
+    if cfg.d_ff_shared:
+        Hs = cfg.d_ff_shared
+        w["sq_gate"] = codes_u4(cfg.seed, TID_SG, (Hs, M // 2), threads)
+        w["sq_up"] = codes_u4(cfg.seed, TID_SU, (Hs, M // 2), threads)
+        w["sq_down"] = codes_u4(cfg.seed, TID_SD, (Hs, M // 2), threads)
+        w["sz_gate"] = scales_bf16(cfg.seed, TID_SG, (Hs, M // 64), zm)
+        w["sz_up"] = scales_bf16(cfg.seed, TID_SU, (Hs, M // 64), zm)
+        w["sz_down"] = scales_bf16(cfg.seed, TID_SD, (Hs // 64, M), zm)
+    return w
+
+
 def make_tokens(cfg: LayerConfig, T: int, stream: int = 0) -> np.ndarray:
     """Hidden states x[T, M] ~ N(0,1) as bf16 bit patterns.  ``stream`` selects an independent batch."""
     return normal_bf16(cfg.seed + 1000 * stream, TID_X, (T, cfg.d_model), 1.0, threads=1)

@@ -429,3 +429,83 @@ def test_stack_reduces_to_layers(oracle):
     # a layer with zero down projection passes the hidden state through unchanged
     kz = dict(kw, w_down=np.zeros_like(w["w_down"]))
     assert np.array_equal(oracle.stack_forward(xb, [kz, kz, kz]), x64)
+
+
+# ------------------------------------------------------------------ 4-bit weight storage
+def _dequant_numpy(q, z, kind):
+    """Independent vectorised reading of the storage form: q [.., H, M/2] -> values [.., H, M] in float64."""
+    lo = (q & 0x0F).astype(np.float64) - 8.0
+    hi = (q >> 4).astype(np.float64) - 8.0
+    v = np.stack([lo, hi], axis=-1).reshape(q.shape[:-1] + (q.shape[-1] * 2,))
+    zf = synth.bf16_bits_to_f64(z)
+    if kind == "fc1":
+        return v * np.repeat(zf, 64, axis=-1)
+    return v * np.repeat(zf, 64, axis=-2)
+
+
+def test_q4_values_against_numpy_reading(oracle):
+    cfg = synth.scaled(synth.CONFIGS["mixtral_8x7b"], d_model=128, d_ff=192, n_experts=2)
+    wq = synth.make_weights_q4(cfg)
+    assert wq["q_gate"].shape == (2, 192, 64) and wq["z_gate"].shape == (2, 192, 2) and wq["z_down"].shape == (2, 3, 128)
+    codes = np.concatenate([wq["q_gate"] & 15, wq["q_gate"] >> 4]).ravel()
+    assert codes.min() == 0 and codes.max() == 15 and abs(codes.mean() - 8.0) < 0.1     # bell shape around 8
+    rng = np.random.default_rng(2)
+    for which, (qk, zk, kind) in enumerate((("q_gate", "z_gate", "fc1"), ("q_up", "z_up", "fc1"), ("q_down", "z_down", "fc2"))):
+        full = _dequant_numpy(wq[qk][1], wq[zk][1], kind)
+        for _ in range(300):
+            j, m = int(rng.integers(192)), int(rng.integers(128))
+            assert oracle.q4_value(wq[qk][1], wq[zk][1], 128, which, j, m) == full[j, m]
+    # hand-made bytes: 0x3A holds code 10 (even m) and code 3 (odd m); scale 0.5 -> +1.0 and -2.5
+    q = np.zeros((64, 32), np.uint8)
+    q[5, 7] = 0x3A
+    z = synth.f32_to_bf16_bits(np.full((64, 1), 0.5, np.float32))
+    assert oracle.q4_value(q, z, 64, 0, 5, 14) == 1.0 and oracle.q4_value(q, z, 64, 0, 5, 15) == -2.5
+    assert oracle.q4_value(q, z, 64, 0, 5, 13) == -4.0                                     # code 0 -> -8 * 0.5
+    zd = synth.f32_to_bf16_bits(np.full((1, 64), 0.25, np.float32))
+    assert oracle.q4_value(q, zd, 64, 2, 5, 14) == 0.5
+
+
+def test_q4_layer_equals_bf16_layer_when_values_are_representable(oracle):
+    """Power-of-two scales make every (code - 8) * scale exactly a bfloat16: the 4-bit layer must then give the
+    bit-identical result of the bf16 layer on those values (pins nibble order, both scale groupings, the offset
+    8, expert and shared-expert addressing, slicing and token split)."""
+    cfg = synth.scaled(synth.CONFIGS["qwen_moe"], d_model=128, d_ff=192, d_ff_shared=128, n_experts=6, top_k=3)
+    wq = synth.make_weights_q4(cfg)
+    rng = np.random.default_rng(3)
+    for k in list(wq):
+        if k.startswith(("z_", "sz_")):
+            wq[k] = synth.f32_to_bf16_bits((2.0 ** rng.integers(-9, -4, size=wq[k].shape)).astype(np.float32))
+    deq = {}
+    for name, qk, zk, kind in (("w_gate", "q_gate", "z_gate", "fc1"), ("w_up", "q_up", "z_up", "fc1"), ("w_down", "q_down", "z_down", "fc2"),
+                               ("s_gate", "sq_gate", "sz_gate", "fc1"), ("s_up", "sq_up", "sz_up", "fc1"), ("s_down", "sq_down", "sz_down", "fc2")):
+        v = _dequant_numpy(wq[qk], wq[zk], kind)
+        bits = synth.f32_to_bf16_bits(v.astype(np.float32))
+        assert np.array_equal(synth.bf16_bits_to_f64(bits), v)     # representable, as constructed
+        deq[name] = bits
+    xb = synth.make_tokens(cfg, 9)
+    lg = synth.make_router_logits(cfg, xb)
+    shared = (deq["s_gate"], deq["s_up"], deq["s_down"])
+    for counts, sc, n_g in (((0, 0), (0, 0), 0), ((64, 64), (64, 0), 4), ((128, 0), (0, 64), 9)):
+        a = oracle.layer_forward_q4(xb, wq, logits=lg, top_k=3, counts=counts, shared_counts=sc, n_g=n_g)
+        b = oracle.layer_forward(xb, deq["w_gate"], deq["w_up"], deq["w_down"], logits=lg, top_k=3, shared=shared,
+                                 counts=counts, shared_counts=sc, n_g=n_g)
+        assert np.array_equal(a, b)
+    sel = np.array([8, 0, 3], np.int32)
+    assert np.array_equal(oracle.layer_forward_q4(xb, wq, logits=lg, top_k=3, sel=sel),
+                          oracle.layer_forward_q4(xb, wq, logits=lg, top_k=3)[sel])
+
+
+def test_q4_layer_against_numpy_matmul(oracle):
+    """General scales (not representable in bf16 after multiplication): float64 matmul on the numpy reading."""
+    cfg = synth.scaled(synth.CONFIGS["llama2_70b"], d_model=64, d_ff=128)
+    wq = synth.make_weights_q4(cfg)
+    xb = synth.make_tokens(cfg, 4)
+    x = synth.bf16_bits_to_f64(xb)
+    Wg = _dequant_numpy(wq["q_gate"][0], wq["z_gate"][0], "fc1")
+    Wu = _dequant_numpy(wq["q_up"][0], wq["z_up"][0], "fc1")
+    Wd = _dequant_numpy(wq["q_down"][0], wq["z_down"][0], "fc2")
+    g = x @ Wg.T
+    ref = ((g / (1.0 + np.exp(-g))) * (x @ Wu.T)) @ Wd
+    got = oracle.layer_forward_q4(xb, wq)
+    assert np.allclose(got, ref, rtol=1e-11, atol=1e-13)
+    assert np.std(Wg) == pytest.approx(cfg.w_std, rel=0.15)
