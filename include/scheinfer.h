@@ -129,6 +129,33 @@ int si_layer_create(const si_layer_desc_t* desc, const uint16_t* w_gate, const u
                     const uint16_t* w_down, const uint16_t* shared_gate, const uint16_t* shared_up,
                     const uint16_t* shared_down, si_layer_t** out);
 
+/*
+ * The same layer from 4-bit weights (the paper evaluates INT4 models, Section V-A, without naming a format;
+ * this one is the library's own): a weight is a code c in 0..15 standing for (c - 8) * scale.
+ *   q_gate, q_up, q_down  HOST uint8 [n_experts][d_ff][d_model/2]: element m of row j is the low nibble of byte
+ *                         m/2 for even m, the high nibble for odd m
+ *   z_gate, z_up          HOST bf16 [n_experts][d_ff][d_model/64]: one scale per 64 consecutive m of a row (the
+ *                         contraction index of FC1)
+ *   z_down                HOST bf16 [n_experts][d_ff/64][d_model]: one scale per 64 consecutive j of a column (the
+ *                         contraction index of FC2)
+ * `shared`: the shared expert's arrays without the leading [n_experts], or NULL when d_ff_shared == 0.
+ * Everything else (slicing, placement, forward, stats) is as for si_layer_create; the parts keep the 4-bit
+ * form in HBM, in pinned memory and on the host link (102*d_model bytes per 64 hidden columns instead of
+ * 384*d_model).  Generation-phase kernels and the host workers multiply codes and scales in fp32 (exact); the
+ * prompt-phase GEMMs run on bf16 copies of the weights made piece by piece on the GPU, (c - 8) * scale
+ * rounded to bf16.
+ */
+typedef struct {
+  const uint8_t* q_gate;
+  const uint8_t* q_up;
+  const uint8_t* q_down;
+  const uint16_t* z_gate;
+  const uint16_t* z_up;
+  const uint16_t* z_down;
+} si_q4_weights_t;
+int si_layer_create_q4(const si_layer_desc_t* desc, const si_q4_weights_t* routed, const si_q4_weights_t* shared,
+                       si_layer_t** out);
+
 /* Hidden-column counts actually used (routed expert n_*, shared expert s_*; any pointer may be
  * NULL).  Tests read the counts from here instead of re-deriving the rounding. */
 int si_layer_split_info(const si_layer_t* layer, int32_t* n_gg, int32_t* n_cg, int32_t* n_cc,
@@ -199,6 +226,16 @@ int si_repack_chunks(const uint16_t* w_gate, const uint16_t* w_up, const uint16_
 int si_cc_compute(const uint16_t* x, const int32_t* idx, const float* w, int32_t T1, int32_t k, int32_t d_model,
                   int32_t n_experts, const uint16_t* routed, uint64_t expert_stride, int32_t n_cc_chunks,
                   const uint16_t* shared, int32_t s_cc_chunks, int32_t threads, float* ycc);
+
+/* The host-only pieces for the 4-bit storage form: one expert's arrays (w: [d_ff][d_model/2] codes,
+ * [d_ff][d_model/64] and [d_ff/64][d_model] scales) -> n_chunks * 51*d_model uint16 units of library storage
+ * (per chunk: gate, up, down codes, then gate, up, down scales), and the CC workers on such storage
+ * (expert_stride in uint16 units).  d_model must be a multiple of 64. */
+int si_repack_chunks_q4(const si_q4_weights_t* w, int32_t d_ff, int32_t d_model, int32_t chunk0, int32_t n_chunks,
+                        uint16_t* out);
+int si_cc_compute_q4(const uint16_t* x, const int32_t* idx, const float* w, int32_t T1, int32_t k, int32_t d_model,
+                     int32_t n_experts, const uint16_t* routed, uint64_t expert_stride, int32_t n_cc_chunks,
+                     const uint16_t* shared, int32_t s_cc_chunks, int32_t threads, float* ycc);
 
 /* Free everything the layer owns.  NULL is allowed. */
 void si_layer_destroy(si_layer_t* layer);

@@ -20,6 +20,7 @@ SI_DECODE_AUTO_T, SI_DECODE_MAX_T = 8, 16
 EXPORTS = ["si_layer_create", "si_layer_split_info", "si_split_counts", "si_layer_forward", "si_route",
            "si_layer_stats", "si_layer_set_profiling", "si_repack_chunks", "si_cc_compute", "si_layer_destroy", "si_last_error", "si_version",
            "si_stack_create", "si_stack_forward", "si_stack_destroy",
+           "si_layer_create_q4", "si_repack_chunks_q4", "si_cc_compute_q4",
            # scheinfer_solver.h
            "si_fit_linear", "si_model_times", "si_simulate", "si_solve_split", "si_model_times_ng", "si_solve_ng",
            "si_assign_gpu_memory", "si_profile"]
@@ -32,6 +33,10 @@ class si_layer_desc_t(ctypes.Structure):
                 ("r_cg", ctypes.c_float), ("r_cc", ctypes.c_float), ("granule", ctypes.c_int32),
                 ("max_tokens", ctypes.c_int32), ("cc_threads", ctypes.c_int32), ("device", ctypes.c_int32),
                 ("stage_mib", ctypes.c_int32), ("n_stage", ctypes.c_int32)]
+
+
+class si_q4_weights_t(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_void_p) for n in ("q_gate", "q_up", "q_down", "z_gate", "z_up", "z_down")]
 
 
 class si_routing_out_t(ctypes.Structure):
@@ -127,6 +132,13 @@ def lib():
         L.si_layer_destroy.restype = None
         L.si_layer_destroy.argtypes = [vp]
         L.si_last_error.restype = ctypes.c_char_p
+        pq = ctypes.POINTER(si_q4_weights_t)
+        L.si_layer_create_q4.restype = ctypes.c_int
+        L.si_layer_create_q4.argtypes = [ctypes.POINTER(si_layer_desc_t), pq, pq, ctypes.POINTER(vp)]
+        L.si_repack_chunks_q4.restype = ctypes.c_int
+        L.si_repack_chunks_q4.argtypes = [pq, i32, i32, i32, i32, vp]
+        L.si_cc_compute_q4.restype = ctypes.c_int
+        L.si_cc_compute_q4.argtypes = [vp, vp, vp, i32, i32, i32, i32, vp, ctypes.c_uint64, i32, vp, i32, i32, vp]
         L.si_stack_create.restype = ctypes.c_int
         L.si_stack_create.argtypes = [ctypes.POINTER(vp), i32, ctypes.POINTER(vp)]
         L.si_stack_forward.restype = ctypes.c_int
@@ -197,6 +209,36 @@ def si_layer_create(d_model, d_ff, n_experts, top_k, w_gate, w_up, w_down, r_gg,
     return out.value
 
 
+def _q4_struct(w, prefix=""):
+    """si_q4_weights_t over the NumPy arrays w[prefix + 'q_gate'] ...; returns (struct, keep-alive list)."""
+    import numpy as np
+    keep = []
+    vals = []
+    for name, dt in (("q_gate", np.uint8), ("q_up", np.uint8), ("q_down", np.uint8), ("z_gate", np.uint16), ("z_up", np.uint16), ("z_down", np.uint16)):
+        a = w[prefix + name]
+        if a.dtype != dt or not a.flags["C_CONTIGUOUS"]:
+            raise ValueError(prefix + name + " must be a C-contiguous %s array" % dt.__name__)
+        keep.append(a)
+        vals.append(a.ctypes.data)
+    return si_q4_weights_t(*vals), keep
+
+
+def si_layer_create_q4(d_model, d_ff, n_experts, top_k, wq, r_gg, r_cg, r_cc, max_tokens, d_ff_shared=0, granule=0,
+                       cc_threads=0, device=0, stage_mib=0, n_stage=0):
+    """Layer from 4-bit weights: wq holds q_gate, q_up, q_down, z_gate, z_up, z_down (and sq_* / sz_* of the shared
+    expert when d_ff_shared > 0) as NumPy arrays.  Returns the opaque layer handle."""
+    desc = si_layer_desc_t(d_model, d_ff, n_experts, top_k, d_ff_shared, r_gg, r_cg, r_cc, granule, max_tokens,
+                           cc_threads, device, stage_mib, n_stage)
+    routed, keep = _q4_struct(wq)
+    shared = None
+    if d_ff_shared:
+        sh, keep2 = _q4_struct(wq, "s")
+        shared = ctypes.byref(sh)
+    out = ctypes.c_void_p(None)
+    _check(lib().si_layer_create_q4(ctypes.byref(desc), ctypes.byref(routed), shared, ctypes.byref(out)))
+    return out.value
+
+
 def si_layer_split_info(layer):
     """dict of hidden-column counts n_gg, n_cg, n_cc (routed) and s_gg, s_cg, s_cc (shared)."""
     n = [ctypes.c_int32(0) for _ in range(6)]
@@ -243,7 +285,17 @@ def si_repack_chunks(w_gate, w_up, w_down, chunk0, n_chunks):
     return out
 
 
-def si_cc_compute(x, idx, w, n_experts, routed, expert_stride, n_cc_chunks, shared=None, s_cc_chunks=0, threads=4):
+def si_repack_chunks_q4(wq, chunk0, n_chunks, prefix=""):
+    """Host: library storage (NumPy uint16, n_chunks*51*M units) of one expert's 4-bit arrays wq[prefix + 'q_gate'] ..."""
+    import numpy as np
+    H, M2 = wq[prefix + "q_gate"].shape
+    st, keep = _q4_struct(wq, prefix)
+    out = np.empty(n_chunks * 51 * M2 * 2, np.uint16)
+    _check(lib().si_repack_chunks_q4(ctypes.byref(st), H, M2 * 2, chunk0, n_chunks, _host_ptr(out)))
+    return out
+
+
+def si_cc_compute(x, idx, w, n_experts, routed, expert_stride, n_cc_chunks, shared=None, s_cc_chunks=0, threads=4, q4=False):
     """Host: the CC workers' result ycc[T1, M] (float32) for NumPy inputs."""
     import numpy as np
     T1, M = x.shape
@@ -251,9 +303,10 @@ def si_cc_compute(x, idx, w, n_experts, routed, expert_stride, n_cc_chunks, shar
     idx = np.ascontiguousarray(idx, np.int32)
     w = np.ascontiguousarray(w, np.float32)
     ycc = np.empty((T1, M), np.float32)
-    _check(lib().si_cc_compute(_host_ptr(x), ctypes.c_void_p(idx.ctypes.data), ctypes.c_void_p(w.ctypes.data), T1, k, M,
-                               n_experts, _host_ptr(routed), expert_stride, n_cc_chunks, _host_ptr(shared),
-                               s_cc_chunks, threads, ctypes.c_void_p(ycc.ctypes.data)))
+    fn = lib().si_cc_compute_q4 if q4 else lib().si_cc_compute
+    _check(fn(_host_ptr(x), ctypes.c_void_p(idx.ctypes.data), ctypes.c_void_p(w.ctypes.data), T1, k, M,
+              n_experts, _host_ptr(routed), expert_stride, n_cc_chunks, _host_ptr(shared),
+              s_cc_chunks, threads, ctypes.c_void_p(ycc.ctypes.data)))
     return ycc
 
 

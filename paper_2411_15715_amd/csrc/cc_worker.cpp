@@ -37,6 +37,24 @@ inline v8f bf16x8_to_f32(const uint16_t* p) {
   return out;
 }
 
+// the 8 codes of a 32-bit word as floats (code - 8), element order 0..7, for the two nibble orders of the
+// 4-bit storage (cc_worker.h)
+inline v8f q4_word(uint32_t w, const v8u32& shifts) {
+  v8u32 v = {w, w, w, w, w, w, w, w};
+  v = (v >> shifts) & 15u;
+  typedef int32_t v8i32 __attribute__((vector_size(32)));
+  return __builtin_convertvector((v8i32)v, v8f) - 8.f;
+}
+const v8u32 Q4_FC1_SHIFTS = {0, 16, 4, 20, 8, 24, 12, 28};
+const v8u32 Q4_FC2_SHIFTS = {0, 8, 16, 24, 4, 12, 20, 28};
+
+inline float bf16_to_f32(uint16_t b) {
+  uint32_t u = (uint32_t)b << 16;
+  float f;
+  std::memcpy(&f, &u, sizeof f);
+  return f;
+}
+
 inline float hsum(v8f v) { return ((v[0] + v[4]) + (v[2] + v[6])) + ((v[1] + v[5]) + (v[3] + v[7])); }
 
 inline float silu_f(float z) { return z / (1.f + std::exp(-z)); }
@@ -139,6 +157,10 @@ class CcPool {
       }
     }
     hbuf.resize((size_t)RB * CHUNK_J);
+    if (j.q4) {
+      run_chunks_q4(it, ebase, xf, hbuf);
+      return;
+    }
     for (int c = it.c0; c < it.c1; ++c) {
       const uint16_t* cb = ebase + (size_t)c * 3 * CHUNK_J * M;
       // FC1 + activation (gate / up blocks: [M/PW panels][64 j][PW m])
@@ -172,6 +194,52 @@ class CcPool {
             a += hv * wd[q];
           }
           scratch_[((size_t)it.slice * n_rows_ + it.row0 + r) * M + m] += hsum(a);
+        }
+      }
+    }
+  }
+
+  // the same two steps on the 4-bit storage form: codes are widened to (code - 8) and multiplied by their group
+  // scale in fp32 (exact: at most 12 significant bits)
+  void run_chunks_q4(const Item& it, const uint16_t* ebase, const std::vector<float>& xf, std::vector<float>& hbuf) {
+    const CcJob& j = job_;
+    const int M = j.M, NW = ntile_width(M);
+    for (int c = it.c0; c < it.c1; ++c) {
+      const unsigned char* cb = reinterpret_cast<const unsigned char*>(ebase + (size_t)c * q4_chunk_u16(M));
+      const uint32_t* gq = reinterpret_cast<const uint32_t*>(cb + q4_off_codes(0, M));
+      const uint32_t* uq = reinterpret_cast<const uint32_t*>(cb + q4_off_codes(1, M));
+      const uint32_t* dq = reinterpret_cast<const uint32_t*>(cb + q4_off_codes(2, M));
+      const uint16_t* gs = reinterpret_cast<const uint16_t*>(cb + q4_off_scales(0, M));
+      const uint16_t* us = reinterpret_cast<const uint16_t*>(cb + q4_off_scales(1, M));
+      const uint16_t* ds = reinterpret_cast<const uint16_t*>(cb + q4_off_scales(2, M));
+      for (int jj = 0; jj < CHUNK_J; ++jj) {
+        v8f ag[RB], au[RB];
+        for (int r = 0; r < RB; ++r) { ag[r] = v8f{0, 0, 0, 0, 0, 0, 0, 0}; au[r] = ag[r]; }
+        for (int m = 0; m < M; m += 8) {
+          const float sg = bf16_to_f32(gs[(size_t)jj * (M / 64) + m / 64]), su = bf16_to_f32(us[(size_t)jj * (M / 64) + m / 64]);
+          const v8f wg = q4_word(gq[q4_fc1_word(jj, m, M)], Q4_FC1_SHIFTS) * sg;
+          const v8f wu = q4_word(uq[q4_fc1_word(jj, m, M)], Q4_FC1_SHIFTS) * su;
+          for (int r = 0; r < it.nrows; ++r) {
+            v8f xv;
+            std::memcpy(&xv, &xf[(size_t)r * M + m], sizeof xv);
+            ag[r] += xv * wg;
+            au[r] += xv * wu;
+          }
+        }
+        for (int r = 0; r < it.nrows; ++r) hbuf[(size_t)r * CHUNK_J + jj] = silu_f(hsum(ag[r])) * hsum(au[r]);
+      }
+      for (int m = 0; m < M; ++m) {
+        v8f wd[8];
+        for (int q = 0; q < 8; ++q) wd[q] = q4_word(dq[q4_fc2_word(q * 8, m, NW)], Q4_FC2_SHIFTS);
+        const float sd = bf16_to_f32(ds[m]);
+        for (int r = 0; r < it.nrows; ++r) {
+          v8f a = v8f{0, 0, 0, 0, 0, 0, 0, 0};
+          for (int q = 0; q < 8; ++q) {
+            v8f hv;
+            std::memcpy(&hv, &hbuf[(size_t)r * CHUNK_J + q * 8], sizeof hv);
+            a += hv * wd[q];
+          }
+          scratch_[((size_t)it.slice * n_rows_ + it.row0 + r) * M + m] += sd * hsum(a);
         }
       }
     }

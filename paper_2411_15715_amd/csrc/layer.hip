@@ -95,6 +95,57 @@ void repack_chunks(const uint16_t* wg, const uint16_t* wu, const uint16_t* wd, i
   }
 }
 
+// 4-bit storage form of chunks [c0, c1) of one expert (layout: cc_worker.h).  Sources are the caller's plain
+// arrays: codes [H][M/2] (element m in byte m/2, low nibble for even m), scales zg / zu [H][M/64], zd [H/64][M].
+void repack_chunks_q4(const uint8_t* qg, const uint8_t* qu, const uint8_t* qd, const uint16_t* zg, const uint16_t* zu,
+                      const uint16_t* zd, int M, int c0, int c1, uint16_t* dst16) {
+  const int NW = ntile_width(M);
+  for (int c = c0; c < c1; ++c) {
+    unsigned char* cb = reinterpret_cast<unsigned char*>(dst16 + (size_t)(c - c0) * q4_chunk_u16(M));
+    for (int f = 0; f < 2; ++f) {
+      const uint8_t* src = (f ? qu : qg) + (size_t)c * CHUNK_J * (M / 2);
+      uint32_t* out = reinterpret_cast<uint32_t*>(cb + q4_off_codes(f, M));
+      for (size_t wi = 0; wi < (size_t)CHUNK_J * (M / 8); ++wi) {  // rows are contiguous in both layouts
+        const uint8_t* b = src + wi * 4;
+        out[wi] = (uint32_t)(b[0] & 15) | (uint32_t)(b[1] & 15) << 4 | (uint32_t)(b[2] & 15) << 8 | (uint32_t)(b[3] & 15) << 12 |
+                  (uint32_t)(b[0] >> 4) << 16 | (uint32_t)(b[1] >> 4) << 20 | (uint32_t)(b[2] >> 4) << 24 | (uint32_t)(b[3] >> 4) << 28;
+      }
+      std::memcpy(cb + q4_off_scales(f, M), (f ? zu : zg) + (size_t)c * CHUNK_J * (M / 64), (size_t)CHUNK_J * (M / 64) * 2);
+    }
+    uint32_t* dout = reinterpret_cast<uint32_t*>(cb + q4_off_codes(2, M));
+    std::memset(dout, 0, (size_t)32 * M);
+    for (int j = 0; j < CHUNK_J; ++j) {
+      const uint8_t* row = qd + ((size_t)c * CHUNK_J + j) * (M / 2);
+      const int sh = 4 * q4_fc2_nibble(j);
+      for (int m = 0; m < M; ++m) {
+        const uint32_t code = (m & 1) ? (row[m >> 1] >> 4) : (row[m >> 1] & 15);
+        dout[q4_fc2_word(j, m, NW)] |= code << sh;
+      }
+    }
+    std::memcpy(cb + q4_off_scales(2, M), zd + (size_t)c * M, (size_t)M * 2);
+  }
+}
+
+// Where the weights of a layer come from: bf16 arrays, or 4-bit codes with scales.
+struct WeightSource {
+  bool q4 = false;
+  const uint16_t *g = nullptr, *u = nullptr, *d = nullptr, *sg = nullptr, *su = nullptr, *sd = nullptr;     // bf16
+  const uint8_t *qg = nullptr, *qu = nullptr, *qd = nullptr, *sqg = nullptr, *squ = nullptr, *sqd = nullptr;  // codes
+  const uint16_t *zg = nullptr, *zu = nullptr, *zd = nullptr, *szg = nullptr, *szu = nullptr, *szd = nullptr;  // scales
+  // library storage of chunks [c, c+1) of routed expert e (e >= 0, hidden size H) or of the shared expert (e < 0)
+  void repack(int e, int c, int H, int M, uint16_t* dst) const {
+    if (!q4) {
+      if (e < 0) repack_chunks(sg, su, sd, M, c, c + 1, dst);
+      else repack_chunks(g + (size_t)e * H * M, u + (size_t)e * H * M, d + (size_t)e * H * M, M, c, c + 1, dst);
+    } else if (e < 0) {
+      repack_chunks_q4(sqg, squ, sqd, szg, szu, szd, M, c, c + 1, dst);
+    } else {
+      const size_t qo = (size_t)e * H * (M / 2), zo = (size_t)e * H * (M / 64), zdo = (size_t)e * (H / 64) * M;
+      repack_chunks_q4(qg + qo, qu + qo, qd + qo, zg + zo, zu + zo, zd + zdo, M, c, c + 1, dst);
+    }
+  }
+};
+
 void parallel_for(int n, int n_threads, const std::function<void(int)>& fn) {
   if (n <= 0) return;
   n_threads = std::max(1, std::min(n_threads, n));
@@ -118,7 +169,8 @@ struct si_layer {
   int M = 0, H = 0, E = 0, k = 0, Hs = 0, EX = 0, has_shared = 0, max_T = 0, device = 0;
   int n_gg = 0, n_cg = 0, n_cc = 0, s_gg = 0, s_cg = 0, s_cc = 0;          // columns
   int ch_gg = 0, ch_cg = 0, ch_cc = 0, sch_gg = 0, sch_cg = 0, sch_cc = 0;  // chunks
-  size_t ce = 0;                                                            // elements per chunk
+  size_t ce = 0;                                                            // uint16 units per chunk
+  int q4 = 0;                                                               // 4-bit storage form
   uint16_t* d_gg = nullptr;     // device [E][ch_gg] chunks
   uint16_t* d_sgg = nullptr;    // device [sch_gg] chunks
   uint16_t* h_routed = nullptr; // pinned [E][ch_cc + ch_cg] chunks (CC first, then CG)
@@ -256,9 +308,9 @@ int si_repack_chunks(const uint16_t* w_gate, const uint16_t* w_up, const uint16_
   return SI_OK;
 }
 
-int si_cc_compute(const uint16_t* x, const int32_t* idx, const float* w, int32_t T1, int32_t k, int32_t d_model,
-                  int32_t n_experts, const uint16_t* routed, uint64_t expert_stride, int32_t n_cc_chunks,
-                  const uint16_t* shared, int32_t s_cc_chunks, int32_t threads, float* ycc) {
+static int cc_compute_impl(const uint16_t* x, const int32_t* idx, const float* w, int32_t T1, int32_t k, int32_t d_model,
+                           int32_t n_experts, const uint16_t* routed, uint64_t expert_stride, int32_t n_cc_chunks,
+                           const uint16_t* shared, int32_t s_cc_chunks, int32_t threads, float* ycc, int q4) {
   if (!x || !idx || !w || !ycc || (!routed && n_cc_chunks > 0)) return fail(SI_EINVAL, "NULL pointer");
   if (T1 < 0 || k < 1 || d_model <= 0 || d_model % 8 != 0 || n_experts < 1 || n_cc_chunks < 0 || s_cc_chunks < 0 || threads < 1)
     return fail(SI_EINVAL, "bad argument");
@@ -269,11 +321,33 @@ int si_cc_compute(const uint16_t* x, const int32_t* idx, const float* w, int32_t
   job.x = x; job.idx = idx; job.w = w; job.T1 = T1; job.k = k; job.M = d_model; job.E = n_experts;
   job.routed = routed; job.expert_stride = (size_t)expert_stride; job.n_cc_chunks = n_cc_chunks;
   job.shared = s_cc_chunks > 0 ? shared : nullptr; job.s_cc_chunks = shared ? s_cc_chunks : 0; job.ycc = ycc;
+  job.q4 = q4;
   if (n_cc_chunks == 0 && !job.shared) { std::memset(ycc, 0, (size_t)T1 * d_model * 4); return SI_OK; }
   CcPool* pool = cc_pool_create(threads);
   cc_pool_run(pool, job);
   cc_pool_destroy(pool);
   return SI_OK;
+}
+
+int si_cc_compute(const uint16_t* x, const int32_t* idx, const float* w, int32_t T1, int32_t k, int32_t d_model,
+                  int32_t n_experts, const uint16_t* routed, uint64_t expert_stride, int32_t n_cc_chunks,
+                  const uint16_t* shared, int32_t s_cc_chunks, int32_t threads, float* ycc) {
+  return cc_compute_impl(x, idx, w, T1, k, d_model, n_experts, routed, expert_stride, n_cc_chunks, shared, s_cc_chunks, threads, ycc, 0);
+}
+
+int si_repack_chunks_q4(const si_q4_weights_t* w, int32_t d_ff, int32_t d_model, int32_t chunk0, int32_t n_chunks, uint16_t* out) {
+  if (!w || !w->q_gate || !w->q_up || !w->q_down || !w->z_gate || !w->z_up || !w->z_down || !out) return fail(SI_EINVAL, "NULL pointer");
+  if (d_model <= 0 || d_model % 64 != 0 || d_ff <= 0 || d_ff % CHUNK_J != 0) return fail(SI_EINVAL, "bad d_ff=%d / d_model=%d", d_ff, d_model);
+  if (chunk0 < 0 || n_chunks < 0 || (chunk0 + n_chunks) * CHUNK_J > d_ff) return fail(SI_EINVAL, "chunk range [%d,+%d) outside d_ff=%d", chunk0, n_chunks, d_ff);
+  repack_chunks_q4(w->q_gate, w->q_up, w->q_down, w->z_gate, w->z_up, w->z_down, d_model, chunk0, chunk0 + n_chunks, out);
+  return SI_OK;
+}
+
+int si_cc_compute_q4(const uint16_t* x, const int32_t* idx, const float* w, int32_t T1, int32_t k, int32_t d_model,
+                     int32_t n_experts, const uint16_t* routed, uint64_t expert_stride, int32_t n_cc_chunks,
+                     const uint16_t* shared, int32_t s_cc_chunks, int32_t threads, float* ycc) {
+  if (d_model % 64 != 0) return fail(SI_EINVAL, "d_model=%d must be a multiple of 64", d_model);
+  return cc_compute_impl(x, idx, w, T1, k, d_model, n_experts, routed, expert_stride, n_cc_chunks, shared, s_cc_chunks, threads, ycc, 1);
 }
 
 void si_layer_destroy(si_layer_t* L) {
@@ -298,17 +372,25 @@ void si_layer_destroy(si_layer_t* L) {
   delete L;
 }
 
-int si_layer_create(const si_layer_desc_t* desc, const uint16_t* w_gate, const uint16_t* w_up, const uint16_t* w_down,
-                    const uint16_t* shared_gate, const uint16_t* shared_up, const uint16_t* shared_down,
-                    si_layer_t** out) {
+}  // extern "C"
+
+namespace {
+
+int create_impl(const si_layer_desc_t* desc, const WeightSource& src, si_layer_t** out) {
   int g = 64;
   if (!out) return fail(SI_EINVAL, "out is NULL");
   *out = nullptr;
   int rc = validate_desc(desc, &g);
   if (rc) return rc;
-  if (!w_gate || !w_up || !w_down) return fail(SI_EINVAL, "expert weight pointer is NULL");
-  if (desc->d_ff_shared > 0 && (!shared_gate || !shared_up || !shared_down))
-    return fail(SI_EINVAL, "d_ff_shared > 0 but a shared weight pointer is NULL");
+  if (!src.q4) {
+    if (!src.g || !src.u || !src.d) return fail(SI_EINVAL, "expert weight pointer is NULL");
+    if (desc->d_ff_shared > 0 && (!src.sg || !src.su || !src.sd))
+      return fail(SI_EINVAL, "d_ff_shared > 0 but a shared weight pointer is NULL");
+  } else {
+    if (!src.qg || !src.qu || !src.qd || !src.zg || !src.zu || !src.zd) return fail(SI_EINVAL, "expert code or scale pointer is NULL");
+    if (desc->d_ff_shared > 0 && (!src.sqg || !src.squ || !src.sqd || !src.szg || !src.szu || !src.szd))
+      return fail(SI_EINVAL, "d_ff_shared > 0 but a shared code or scale pointer is NULL");
+  }
   int n_dev = 0;
   if (hipGetDeviceCount(&n_dev) != hipSuccess || desc->device < 0 || desc->device >= n_dev) {
     (void)hipGetLastError();
@@ -324,7 +406,8 @@ int si_layer_create(const si_layer_desc_t* desc, const uint16_t* w_gate, const u
   if (L->has_shared) split_counts(L->Hs, g, desc->r_gg, desc->r_cg, &L->s_gg, &L->s_cg, &L->s_cc);
   L->ch_gg = L->n_gg / CHUNK_J; L->ch_cg = L->n_cg / CHUNK_J; L->ch_cc = L->n_cc / CHUNK_J;
   L->sch_gg = L->s_gg / CHUNK_J; L->sch_cg = L->s_cg / CHUNK_J; L->sch_cc = L->s_cc / CHUNK_J;
-  L->ce = chunk_elems(L->M);
+  L->q4 = src.q4 ? 1 : 0;
+  L->ce = src.q4 ? q4_chunk_u16(L->M) : chunk_elems(L->M);
   const int M = L->M, E = L->E, k = L->k, T = L->max_T;
   const size_t ce = L->ce;
   const int hch = L->ch_cc + L->ch_cg, shch = L->sch_cc + L->sch_cg;
@@ -344,18 +427,17 @@ int si_layer_create(const si_layer_desc_t* desc, const uint16_t* w_gate, const u
     const int per = hch;  // chunks per expert on the host
     parallel_for(E * per, rp_threads, [&](int i) {
       int e = i / per, c = i % per;
-      repack_chunks(w_gate + (size_t)e * L->H * M, w_up + (size_t)e * L->H * M, w_down + (size_t)e * L->H * M, M, c, c + 1,
-                    L->h_routed + ((size_t)e * per + c) * ce);
+      src.repack(e, c, L->H, M, L->h_routed + ((size_t)e * per + c) * ce);
     });
-    parallel_for(shch, rp_threads, [&](int c) { repack_chunks(shared_gate, shared_up, shared_down, M, c, c + 1, L->h_shared + (size_t)c * ce); });
+    parallel_for(shch, rp_threads, [&](int c) { src.repack(-1, c, L->Hs, M, L->h_shared + (size_t)c * ce); });
     // GG parts: repack through a pinned bounce buffer, a group of chunks at a time
     const int bounce_chunks = std::max(1, (int)std::min<size_t>(256, ((size_t)256 << 20) / (ce * 2)));
     uint16_t* bounce = nullptr;
     if ((size_t)E * L->ch_gg + L->sch_gg > 0) TRY_OR_DESTROY(pin_alloc(&bounce, (size_t)bounce_chunks * ce));
-    auto upload = [&](const uint16_t* wg, const uint16_t* wu, const uint16_t* wd, int c_first, int n, uint16_t* dst) -> hipError_t {
+    auto upload = [&](int e, int Hx, int c_first, int n, uint16_t* dst) -> hipError_t {
       for (int c0 = 0; c0 < n; c0 += bounce_chunks) {
         int nb = std::min(bounce_chunks, n - c0);
-        parallel_for(nb, rp_threads, [&](int i) { repack_chunks(wg, wu, wd, M, c_first + c0 + i, c_first + c0 + i + 1, bounce + (size_t)i * ce); });
+        parallel_for(nb, rp_threads, [&](int i) { src.repack(e, c_first + c0 + i, Hx, M, bounce + (size_t)i * ce); });
         hipError_t e2 = hipMemcpy(dst + (size_t)c0 * ce, bounce, (size_t)nb * ce * 2, hipMemcpyHostToDevice);
         if (e2 != hipSuccess) return e2;
       }
@@ -363,9 +445,8 @@ int si_layer_create(const si_layer_desc_t* desc, const uint16_t* w_gate, const u
     };
     hipError_t ue = hipSuccess;
     for (int e = 0; e < E && ue == hipSuccess; ++e)
-      ue = upload(w_gate + (size_t)e * L->H * M, w_up + (size_t)e * L->H * M, w_down + (size_t)e * L->H * M, hch, L->ch_gg,
-                  L->d_gg + (size_t)e * L->ch_gg * ce);
-    if (ue == hipSuccess && L->has_shared) ue = upload(shared_gate, shared_up, shared_down, shch, L->sch_gg, L->d_sgg);
+      ue = upload(e, L->H, hch, L->ch_gg, L->d_gg + (size_t)e * L->ch_gg * ce);
+    if (ue == hipSuccess && L->has_shared) ue = upload(-1, L->Hs, shch, L->sch_gg, L->d_sgg);
     if (bounce) (void)hipHostFree(bounce);
     HIP_OR_DESTROY(ue);
   }
@@ -439,6 +520,33 @@ int si_layer_create(const si_layer_desc_t* desc, const uint16_t* w_gate, const u
   HIP_OR_DESTROY(hipDeviceSynchronize());
   *out = L;
   return SI_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int si_layer_create(const si_layer_desc_t* desc, const uint16_t* w_gate, const uint16_t* w_up, const uint16_t* w_down,
+                    const uint16_t* shared_gate, const uint16_t* shared_up, const uint16_t* shared_down,
+                    si_layer_t** out) {
+  WeightSource src;
+  src.g = w_gate; src.u = w_up; src.d = w_down; src.sg = shared_gate; src.su = shared_up; src.sd = shared_down;
+  return create_impl(desc, src, out);
+}
+
+int si_layer_create_q4(const si_layer_desc_t* desc, const si_q4_weights_t* routed, const si_q4_weights_t* shared,
+                       si_layer_t** out) {
+  if (!routed) return fail(SI_EINVAL, "routed is NULL");
+  if (desc && desc->d_ff_shared > 0 && !shared) return fail(SI_EINVAL, "d_ff_shared > 0 but shared is NULL");
+  WeightSource src;
+  src.q4 = true;
+  src.qg = routed->q_gate; src.qu = routed->q_up; src.qd = routed->q_down;
+  src.zg = routed->z_gate; src.zu = routed->z_up; src.zd = routed->z_down;
+  if (shared) {
+    src.sqg = shared->q_gate; src.squ = shared->q_up; src.sqd = shared->q_down;
+    src.szg = shared->z_gate; src.szu = shared->z_up; src.szd = shared->z_down;
+  }
+  return create_impl(desc, src, out);
 }
 
 int si_layer_split_info(const si_layer_t* L, int32_t* n_gg, int32_t* n_cg, int32_t* n_cc, int32_t* s_gg, int32_t* s_cg, int32_t* s_cc) {
@@ -595,6 +703,7 @@ int si_layer_forward(si_layer_t* L, const void* x_dev, const float* logits_dev, 
     job.routed = L->h_routed; job.expert_stride = (size_t)hch * ce; job.n_cc_chunks = L->ch_cc;
     job.shared = (L->has_shared && L->sch_cc > 0) ? L->h_shared : nullptr; job.s_cc_chunks = L->sch_cc;
     job.ycc = L->hycc;
+    job.q4 = L->q4;
     if (L->ch_cc == 0 && !job.shared) {
       std::memset(L->hycc, 0, (size_t)n_x1 * M * 4);
     } else {

@@ -153,3 +153,67 @@ def test_cc_workers_match_oracle_cc_partial(oracle, T1, threads):
     y2 = si.si_cc_compute(xd, np.zeros((T1, 1), np.int32), np.ones((T1, 1), np.float32), 1, packed, 0, 3, threads=threads)
     ref2 = oracle.layer_forward(xd, wd_["w_gate"][:, :192], wd_["w_up"][:, :192], wd_["w_down"][:, :192])
     assert np.max(np.abs(y2 - ref2)) <= 1e-4 * np.sqrt(np.mean(ref2 ** 2))
+
+
+# ------------------------------------------------------------------ 4-bit storage form
+def _codes(q):
+    """[.., M/2] bytes -> [.., M] codes (element m: low nibble of byte m/2 for even m)."""
+    return np.stack([q & 15, q >> 4], axis=-1).reshape(q.shape[:-1] + (q.shape[-1] * 2,)).astype(np.uint32)
+
+
+@pytest.mark.parametrize("M", [64, 192, 1024])
+def test_repack_layout_q4(M):
+    """Per chunk, bytes: gate codes | up codes | down codes | gate scales | up scales | down scales (32M each for the
+    codes, 2M each for the scales); nibble orders as the kernels expect them."""
+    rng = np.random.default_rng(2)
+    H, NW = 192, _ntile_width(M)
+    wq = {k: rng.integers(0, 256, (H, M // 2), dtype=np.uint8) for k in ("q_gate", "q_up", "q_down")}
+    wq.update({k: rng.integers(0, 65535, (H, M // 64), dtype=np.uint16) for k in ("z_gate", "z_up")})
+    wq["z_down"] = rng.integers(0, 65535, (H // 64, M), dtype=np.uint16)
+    out = si.si_repack_chunks_q4(wq, 1, 2).reshape(2, 51 * M)
+    for ci, c in enumerate((1, 2)):
+        raw = out[ci].view(np.uint8)
+        assert raw.size == 102 * M
+        for f, (qk, zk) in enumerate((("q_gate", "z_gate"), ("q_up", "z_up"))):
+            words = raw[32 * M * f:32 * M * (f + 1)].view(np.uint32).reshape(64, M // 8)
+            codes = _codes(wq[qk][c * 64:(c + 1) * 64]).reshape(64, M // 8, 8)
+            ref = np.zeros((64, M // 8), np.uint32)
+            for e in range(8):
+                ref |= codes[:, :, e] << np.uint32(4 * ((e >> 1) + 4 * (e & 1)))
+            assert np.array_equal(words, ref)
+            scales = raw[96 * M + 2 * M * f:96 * M + 2 * M * (f + 1)].view(np.uint16).reshape(64, M // 64)
+            assert np.array_equal(scales, wq[zk][c * 64:(c + 1) * 64])
+        words = raw[64 * M:96 * M].view(np.uint32).reshape(M // NW, 2, NW, 4)       # [tile][half][m][word]
+        codes = _codes(wq["q_down"][c * 64:(c + 1) * 64])                             # [64 j][M]
+        cj = codes.reshape(2, 4, 8, M // NW, NW)                                      # [half][word][e][tile][m]
+        ref = np.zeros((M // NW, 2, NW, 4), np.uint32)
+        for e in range(8):
+            nib = 2 * e if e < 4 else 2 * (e - 4) + 1
+            ref |= cj[:, :, e].transpose(2, 0, 3, 1) << np.uint32(4 * nib)
+        assert np.array_equal(words, ref)
+        assert np.array_equal(raw[100 * M:].view(np.uint16), wq["z_down"][c])
+    with pytest.raises(si.ScheInferError):
+        si.si_repack_chunks_q4(wq, 2, 2)
+
+
+@pytest.mark.parametrize("T1,threads", [(1, 3), (6, 4), (40, 4)])
+def test_cc_workers_q4_match_oracle_cc_partial(oracle, T1, threads):
+    cfg = synth.scaled(synth.CONFIGS["qwen_moe"], d_model=128, d_ff=256, d_ff_shared=384, n_experts=8, top_k=3)
+    wq = synth.make_weights_q4(cfg)
+    xb = synth.make_tokens(cfg, T1)
+    lg = synth.make_router_logits(cfg, xb)
+    r = oracle.route(lg, cfg.top_k)
+    n_cc, s_cc = 128, 192
+    nch = n_cc // 64 + 1                  # one extra chunk (CG) behind the CC range
+    routed = np.concatenate([si.si_repack_chunks_q4({k: wq[k][e] for k in ("q_gate", "q_up", "q_down", "z_gate", "z_up", "z_down")}, 0, nch)
+                             for e in range(cfg.n_experts)])
+    shared = si.si_repack_chunks_q4(wq, 0, s_cc // 64, prefix="s")
+    ycc = si.si_cc_compute(xb, r["idx"], r["w"].astype(np.float32), cfg.n_experts, routed, nch * 51 * cfg.d_model, n_cc // 64,
+                           shared=shared, s_cc_chunks=s_cc // 64, threads=threads, q4=True)
+    cut = {k: (v[:, :n_cc] if k.startswith(("q_", "z_g", "z_u")) else v) for k, v in wq.items() if not k.startswith("s")}
+    cut["z_down"] = wq["z_down"][:, :n_cc // 64]
+    for k in ("sq_gate", "sq_up", "sq_down", "sz_gate", "sz_up"):
+        cut[k] = wq[k][:s_cc]
+    cut["sz_down"] = wq["sz_down"][:s_cc // 64]
+    ref = oracle.layer_forward_q4(xb, cut, logits=lg, top_k=cfg.top_k)
+    assert np.max(np.abs(ycc - ref)) <= 1e-4 * np.sqrt(np.mean(ref ** 2))
