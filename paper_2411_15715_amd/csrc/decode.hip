@@ -227,6 +227,7 @@ static int pick_tb(int tb_hint) { return tb_hint <= 1 ? 1 : (tb_hint <= 2 ? 2 : 
 hipError_t launch_decode_gateup(const uint16_t* x, int M, const Plan& plan, int tb_hint, int expert_sel, int x2_only,
                                 int max_touched, const WeightView& wv, float* h, int ldh, hipStream_t stream) {
   if (wv.n_chunks <= 0) return hipSuccess;
+  if (wv.q4) return launch_decode_gateup_q4(x, M, plan, tb_hint, expert_sel, x2_only, max_touched, wv, h, ldh, stream);
   dim3 grid(wv.n_chunks * (CHUNK_J / GU_JPB), expert_sel >= 0 ? 1 : max_touched);
   const int tb = pick_tb(tb_hint);
   size_t lds = (size_t)tb * M * 2;
@@ -240,6 +241,9 @@ hipError_t launch_decode_down(const float* h, int ldh, int M, const Plan& plan, 
                               int max_touched, const WeightView& wv, int slot0, int chunks_per_slot, float* part,
                               size_t slot_stride, hipStream_t stream) {
   if (wv.n_chunks <= 0) return hipSuccess;
+  if (wv.q4)
+    return launch_decode_down_q4(h, ldh, M, plan, tb_hint, expert_sel, x2_only, max_touched, wv, slot0, chunks_per_slot, part,
+                                 slot_stride, stream);
   int n_slots = (wv.n_chunks + chunks_per_slot - 1) / chunks_per_slot;
   dim3 grid((M + DN_THREADS - 1) / DN_THREADS, n_slots, expert_sel >= 0 ? 1 : max_touched);
   const int tb = pick_tb(tb_hint);

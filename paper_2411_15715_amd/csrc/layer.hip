@@ -196,6 +196,8 @@ struct si_layer {
   float* d_h = nullptr;       // decode activations [rows_dec][ldh]
   int ldh_dec = 0, rows_dec = 0;
   float* d_part = nullptr;    // decode partials [3*DOWN_SLOTS][rows_dec][M]
+  uint16_t* d_deq = nullptr;  // 4-bit layers: bf16 copies of the chunks a prompt-phase GEMM is about to read
+  int deq_chunks = 0;         // capacity of d_deq in bf16 chunks
   uint16_t* d_hact = nullptr; // prefill activations
   size_t hact_elems = 0;
   float* d_yp = nullptr;      // prefill per-row outputs [MAX_KSPLIT][max_T*(k+shared)][M]
@@ -365,7 +367,7 @@ void si_layer_destroy(si_layer_t* L) {
   if (L->ev_t0) (void)hipEventDestroy(L->ev_t0);
   if (L->ev_t1) (void)hipEventDestroy(L->ev_t1);
   if (L->copy_stream) (void)hipStreamDestroy(L->copy_stream);
-  void* dev[] = {L->d_gg, L->d_sgg, L->d_plan, L->d_h, L->d_part, L->d_hact, L->d_yp, L->d_ycc};
+  void* dev[] = {L->d_gg, L->d_sgg, L->d_plan, L->d_h, L->d_part, L->d_hact, L->d_yp, L->d_ycc, L->d_deq};
   for (void* p : dev) if (p) (void)hipFree(p);
   void* pin[] = {L->h_routed, L->h_shared, L->hx, L->hidx, L->hw, L->hcount, L->hycc};
   for (void* p : pin) if (p) (void)hipHostFree(p);
@@ -502,6 +504,14 @@ int create_impl(const si_layer_desc_t* desc, const WeightSource& src, si_layer_t
   {
     // widest launch of the prefill path: the GG part, or one staged piece
     int cols = std::max({L->n_gg, L->s_gg, any_host ? L->stage_chunks * CHUNK_J : 0});
+    if (L->q4) {
+      // bf16 scratch for the prompt-phase GEMMs: 512 MiB, at least one chunk per routed expert
+      const size_t cb16 = chunk_elems(M) * 2;
+      L->deq_chunks = (int)std::max<size_t>((size_t)E, ((size_t)512 << 20) / cb16);
+      L->deq_chunks = std::min(L->deq_chunks, std::max(E, E * std::max({L->ch_gg, L->ch_cg, L->ch_cc, L->sch_gg, L->sch_cg, L->sch_cc, 1})));
+      TRY_OR_DESTROY(dev_alloc(&L->d_deq, (size_t)L->deq_chunks * chunk_elems(M)));
+      cols = L->deq_chunks * CHUNK_J;
+    }
     L->hact_elems = n_rows * (size_t)cols;
     if (T > SI_DECODE_AUTO_T || true) TRY_OR_DESTROY(dev_alloc(&L->d_hact, L->hact_elems));
     L->yp_slab = n_rows * (size_t)M;
@@ -732,7 +742,7 @@ int si_layer_forward(si_layer_t* L, const void* x_dev, const float* logits_dev, 
   auto run_part = [&](const uint16_t* base, size_t estride, int expert_sel, int is_shared, int c0, int n, int col_base,
                       int part, int part_chunk0, int x2_only, bool first_for_rows) -> int {
     if (n <= 0) return SI_OK;
-    WeightView wv{base, estride, c0, n, 0};
+    WeightView wv{base, estride, c0, n, 0, L->q4};
     const int esel = is_shared ? E : expert_sel;
     if (path == SI_DECODE) {
       wv.col0 = col_base;
@@ -754,15 +764,32 @@ int si_layer_forward(si_layer_t* L, const void* x_dev, const float* logits_dev, 
         bm = bm_call;
         n_rt = tiles_upper;
       }
-      const int ldh = n * CHUNK_J;
-      {
-        SegScope sc(L, stream, SI_K_PREFILL_GATEUP);
-        K_TRY(launch_prefill_gateup(x, M, L->plan, bm, esel, x2_only, n_rt, wv, L->d_hact, ldh, stream));
+      // bf16 layers: one pass over the chunk range.  4-bit layers: the range goes through the bf16 scratch in
+      // sub-pieces (dequantise, FC1, FC2 accumulating), as many chunks per expert as the scratch holds.
+      const int cap = !L->q4 ? n : std::max(1, esel >= 0 ? L->deq_chunks : L->deq_chunks / E);
+      for (int s0 = 0; s0 < n; s0 += cap) {
+        const int ns = std::min(cap, n - s0);
+        const bool first = first_for_rows && s0 == 0;
+        WeightView wg = wv;
+        if (L->q4) {
+          WeightView src{base, estride, c0 + s0, ns, 0, 1};
+          const size_t dst_stride = esel >= 0 ? 0 : (size_t)ns * chunk_elems(M);
+          {
+            SegScope sc(L, stream, SI_K_FILL);
+            K_TRY(launch_dequant_q4(src, M, L->plan, esel, x2_only, E, L->d_deq, dst_stride, stream));
+          }
+          wg = WeightView{L->d_deq, dst_stride, 0, ns, 0, 0};
+        }
+        const int ldh = ns * CHUNK_J;
+        {
+          SegScope sc(L, stream, SI_K_PREFILL_GATEUP);
+          K_TRY(launch_prefill_gateup(x, M, L->plan, bm, esel, x2_only, n_rt, wg, L->d_hact, ldh, stream));
+        }
+        SegScope sc(L, stream, SI_K_PREFILL_DOWN);
+        const int split = first ? split_call : std::min(split_call, std::max(1, ns / 8));
+        K_TRY(launch_prefill_down(L->d_hact, ldh, M, L->plan, bm, esel, x2_only, n_rt, wg, L->d_yp, L->yp_slab, split,
+                                  first ? 0 : 1, stream));
       }
-      SegScope sc(L, stream, SI_K_PREFILL_DOWN);
-      const int split = first_for_rows ? split_call : std::min(split_call, std::max(1, n / 8));
-      K_TRY(launch_prefill_down(L->d_hact, ldh, M, L->plan, bm, esel, x2_only, n_rt, wv, L->d_yp, L->yp_slab, split,
-                                first_for_rows ? 0 : 1, stream));
     }
     return SI_OK;
   };

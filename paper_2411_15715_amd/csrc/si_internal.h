@@ -62,6 +62,7 @@ struct WeightView {
   int chunk0;             // first chunk (relative to base / expert) to process
   int n_chunks;           // number of chunks to process
   int col0;               // hidden column (within the expert) of chunk0: indexes h / Hact columns
+  int q4;                 // chunks are in the 4-bit storage form (cc_worker.h); strides still in uint16 units
 };
 
 // decode.hip ---------------------------------------------------------------------------------
@@ -100,5 +101,17 @@ hipError_t launch_prefill_down(const uint16_t* hact, int ldh, int M, const Plan&
 hipError_t launch_prefill_combine(const float* yp, size_t slab_stride, int n_split, const float* ycc, int T, int k,
                                   int M, int n_x1, int has_shared, const Plan& plan, float* y, hipStream_t stream);
 hipError_t launch_fill_zero(float* p, size_t n, hipStream_t stream);
+
+// q4.hip -------------------------------------------------------------------------------------
+// the GEMV launchers of decode.hip hand over to these when wv.q4 is set
+hipError_t launch_decode_gateup_q4(const uint16_t* x, int M, const Plan& plan, int tb_hint, int expert_sel, int x2_only,
+                                   int max_touched, const WeightView& wv, float* h, int ldh, hipStream_t stream);
+hipError_t launch_decode_down_q4(const float* h, int ldh, int M, const Plan& plan, int tb_hint, int expert_sel, int x2_only,
+                                 int max_touched, const WeightView& wv, int slot0, int chunks_per_slot, float* part,
+                                 size_t slot_stride, hipStream_t stream);
+// 4-bit chunks [wv.chunk0, +wv.n_chunks) of one expert (expert_sel >= 0) or of every routed expert that has rows
+// -> bf16 chunks 0..n_chunks at dst (+ e * dst_estride)
+hipError_t launch_dequant_q4(const WeightView& wv, int M, const Plan& plan, int expert_sel, int x2_only, int n_experts,
+                             uint16_t* dst, size_t dst_estride, hipStream_t stream);
 
 }  // namespace si
