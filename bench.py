@@ -52,6 +52,8 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-gg-only", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
+    ap.add_argument("--q4", action="store_true",
+                    help="4-bit weights (codes + bf16 group scales) instead of bf16: same step, same metric")
     ap.add_argument("--solve", action="store_true",
                     help="instead of the throughput line: profile this machine (Eq. 3), solve r_CG* for the config's "
                          "r_GG and n_g* for its prompt length (Section IV), and measure the layer over a sweep of "
@@ -112,10 +114,14 @@ def run_steps(si, layer, wl, n_steps, n_g, stream, collect=None):
 
 def measure(si, torch, cfg, w, split, wl, steps, warmup, n_g):
     """Time `steps` steps (profiling off), then repeat them with per-launch events for kernel times."""
-    shared = tuple(w[k] for k in ("s_gate", "s_up", "s_down")) if cfg.d_ff_shared else None
-    layer = si.si_layer_create(cfg.d_model, cfg.d_ff, cfg.n_experts, cfg.top_k, w["w_gate"], w["w_up"], w["w_down"],
-                               split[0], split[1], split[2], max(cfg.t_prefill, cfg.t_decode),
-                               d_ff_shared=cfg.d_ff_shared, shared=shared)
+    if "q_gate" in w:
+        layer = si.si_layer_create_q4(cfg.d_model, cfg.d_ff, cfg.n_experts, cfg.top_k, w, split[0], split[1], split[2],
+                                      max(cfg.t_prefill, cfg.t_decode), d_ff_shared=cfg.d_ff_shared)
+    else:
+        shared = tuple(w[k] for k in ("s_gate", "s_up", "s_down")) if cfg.d_ff_shared else None
+        layer = si.si_layer_create(cfg.d_model, cfg.d_ff, cfg.n_experts, cfg.top_k, w["w_gate"], w["w_up"], w["w_down"],
+                                   split[0], split[1], split[2], max(cfg.t_prefill, cfg.t_decode),
+                                   d_ff_shared=cfg.d_ff_shared, shared=shared)
     try:
         info = si.si_layer_split_info(layer)
         stream = torch.cuda.current_stream().cuda_stream
@@ -151,7 +157,7 @@ def measure(si, torch, cfg, w, split, wl, steps, warmup, n_g):
     return elapsed, stats, info, {"decode_call_us": 1e6 * t_dec, "prefill_call_us": 1e6 * t_pre}
 
 
-def kernel_table(si, cfg, info, wl, stats, steps, n_g):
+def kernel_table(si, cfg, info, wl, stats, steps, n_g, q4=False):
     """Per kernel class: launches, mean duration, algorithmic bytes / flops per step, achieved rates.
 
     Algorithmic work (weight bytes are read once per call, bf16):
@@ -159,7 +165,10 @@ def kernel_table(si, cfg, info, wl, stats, steps, n_g):
       decode down   : touched experts x part columns x M x 2 B
       prefill gateup: (token, expert) pairs x part columns x M x 4 flop ; weight bytes as above
       prefill down  : pairs x part columns x M x 2 flop
-    Columns of the CC part count only when they run on the GPU (CG', the n_g tokens of X2)."""
+    Columns of the CC part count only when they run on the GPU (CG', the n_g tokens of X2).
+    4-bit weights: the decode kernels read 0.5 B of codes + 2/64 B of scales per weight; the prefill GEMMs read the
+    bf16 copies made by the dequantisation kernel (whose time is in the "fill" class)."""
+    wb_dec = 0.5 + 2.0 / 64 if q4 else 2.0
     M, H, Hs, k = cfg.d_model, cfg.d_ff, cfg.d_ff_shared, cfg.top_k
     gpu_cols = info["n_gg"] + info["n_cg"]
     gpu_cols_s = info["s_gg"] + info["s_cg"]
@@ -168,8 +177,8 @@ def kernel_table(si, cfg, info, wl, stats, steps, n_g):
     dec_bytes_gu = dec_bytes_dn = 0.0
     for _, _, lg in wl.dec:
         nt = Workload.touched(cfg, lg)
-        dec_bytes_gu += (nt * gpu_cols + gpu_cols_s) * M * 2 * 2
-        dec_bytes_dn += (nt * gpu_cols + gpu_cols_s) * M * 2
+        dec_bytes_gu += (nt * gpu_cols + gpu_cols_s) * M * 2 * wb_dec
+        dec_bytes_dn += (nt * gpu_cols + gpu_cols_s) * M * wb_dec
     ntp = Workload.touched(cfg, wl.lp)
     cc_cols_gpu = info["n_cc"] if n_g > 0 else 0
     cc_cols_gpu_s = info["s_cc"] if n_g > 0 else 0
@@ -247,14 +256,17 @@ def roofline_of(name, ent, cfg_name=None, split=None):
 def cpu_baseline(cfg, w, wl, seconds):
     """The oracle, as it stands, on a bounded sample of the step's tokens (prefill tokens, all routed)."""
     import oracle
-    shared = tuple(w[k] for k in ("s_gate", "s_up", "s_down")) if cfg.d_ff_shared else None
+    shared = tuple(w[k] for k in ("s_gate", "s_up", "s_down")) if cfg.d_ff_shared and "s_gate" in w else None
     threads = oracle.get_threads()
 
     def run(n):
         sel = np.linspace(0, cfg.t_prefill - 1, n).astype(np.int32)
         t0 = time.perf_counter()
-        oracle.layer_forward(wl.xp_bits, w["w_gate"], w["w_up"], w["w_down"], logits=wl.lp, top_k=cfg.top_k,
-                             shared=shared, sel=sel)
+        if "q_gate" in w:
+            oracle.layer_forward_q4(wl.xp_bits, w, logits=wl.lp, top_k=cfg.top_k, sel=sel)
+        else:
+            oracle.layer_forward(wl.xp_bits, w["w_gate"], w["w_up"], w["w_down"], logits=wl.lp, top_k=cfg.top_k,
+                                 shared=shared, sel=sel)
         return time.perf_counter() - t0
 
     t1 = run(2)
@@ -457,7 +469,10 @@ def main():
     split = tuple(float(v) for v in args.split.split(",")) if args.split else cfg.split
     n_g = args.n_g if args.n_g >= 0 else (cfg.t_prefill if split[2] > 0 else 0)
     t0 = time.perf_counter()
-    w = synth.make_weights(cfg, threads=min(16, os.cpu_count() or 8))
+    if args.q4:
+        w = synth.make_weights_q4(cfg, threads=min(16, os.cpu_count() or 8))
+    else:
+        w = synth.make_weights(cfg, threads=min(16, os.cpu_count() or 8))
     if args.solve:
         solver_study(args, si, torch, cfg, w, split[0])
         return
@@ -470,7 +485,7 @@ def main():
 
     elapsed, stats, info, calls = measure(si, torch, cfg, w, split, wl, args.steps, args.warmup, n_g)
     ms_per_step = 1e3 * elapsed / args.steps
-    ktab = kernel_table(si, cfg, info, wl, stats, args.steps, n_g)
+    ktab = kernel_table(si, cfg, info, wl, stats, args.steps, n_g, q4=args.q4)
     weight_kernels = [k for k in ktab if "bound" in ktab[k]]
     dominant = max(weight_kernels, key=lambda k: ktab[k]["ms_per_step"])
     pre = [st for kind, st in stats if kind == "prefill"]
@@ -498,7 +513,8 @@ def main():
     out = {
         "metric": "FFN/MoE layer tokens/s (decode+prefill)", "value": round(tokens_per_step / (ms_per_step / 1e3), 2),
         "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int4 weights x bf16 activations, f32 accumulate" if args.q4 else "bf16", "data": "synthetic",
         "config": {"workload": "%s-shaped layer: E=%d top-%d M=%d H=%d%s, step = 1 prefill call of %d tokens + %d decode "
                                "calls of %d token(s)" % (cfg.name, cfg.n_experts, cfg.top_k, cfg.d_model, cfg.d_ff,
                                                          (" + shared H=%d" % cfg.d_ff_shared) if cfg.d_ff_shared else "",
@@ -512,7 +528,7 @@ def main():
     }
     if not args.no_gg_only and tuple(split) != (1.0, 0.0, 0.0):
         e2, stats2, info2, calls2 = measure(si, torch, cfg, w, (1.0, 0.0, 0.0), wl, args.steps, args.warmup, 0)
-        k2 = kernel_table(si, cfg, info2, wl, stats2, args.steps, 0)
+        k2 = kernel_table(si, cfg, info2, wl, stats2, args.steps, 0, q4=args.q4)
         pre2 = [st for kind, st in stats2 if kind == "prefill"]
         dec2 = [st for kind, st in stats2 if kind == "decode"]
         out["gg_only"] = {
