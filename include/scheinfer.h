@@ -130,6 +130,28 @@ int si_layer_create(const si_layer_desc_t* desc, const uint16_t* w_gate, const u
                     const uint16_t* shared_down, si_layer_t** out);
 
 /*
+ * Whole-expert placement: instead of slicing every routed expert by the three rates, each expert lives entirely
+ * in one place, placement[e] = 0 (GG: resident in GPU memory), 1 (CG: pinned host memory, streamed when the
+ * expert receives tokens) or 2 (CC: computed by the host workers; on the GPU through CG' for the X2 tokens).
+ * The output is the same as for any slicing (Section III-B: the partition changes where a product is formed, not
+ * its value); what changes is which bytes cross the host link for a given routing, e.g. keeping the most
+ * frequently chosen experts resident.  placement: HOST [n_experts].  The rates of `desc` still slice the shared
+ * expert, if any.  Otherwise as si_layer_create.
+ */
+int si_layer_create_placed(const si_layer_desc_t* desc, const uint16_t* w_gate, const uint16_t* w_up,
+                           const uint16_t* w_down, const uint16_t* shared_gate, const uint16_t* shared_up,
+                           const uint16_t* shared_down, const uint8_t* placement, si_layer_t** out);
+
+/*
+ * A placement from expert frequencies (a heuristic of this library, not of the paper): the n_gg experts with the
+ * largest freq[e] become GG; the others are taken in descending frequency and given to CG while CG's share of
+ * the frequency mass handed out so far stays at or below cg_share, else to CC (cg_share = the r_CG / (r_CG +
+ * r_CC) that the slicing-rate solver balances link and host with).  Ties: lower expert index first.
+ * freq HOST [n_experts] >= 0; placement HOST [n_experts], written.
+ */
+int si_place_experts(const double* freq, int32_t n_experts, int32_t n_gg, double cg_share, uint8_t* placement);
+
+/*
  * The same layer from 4-bit weights (the paper evaluates INT4 models, Section V-A, without naming a format;
  * this one is the library's own): a weight is a code c in 0..15 standing for (c - 8) * scale.
  *   q_gate, q_up, q_down  HOST uint8 [n_experts][d_ff][d_model/2]: element m of row j is the low nibble of byte
@@ -139,6 +161,7 @@ int si_layer_create(const si_layer_desc_t* desc, const uint16_t* w_gate, const u
  *   z_down                HOST bf16 [n_experts][d_ff/64][d_model]: one scale per 64 consecutive j of a column (the
  *                         contraction index of FC2)
  * `shared`: the shared expert's arrays without the leading [n_experts], or NULL when d_ff_shared == 0.
+ * `placement`: NULL (slice by the rates) or HOST [n_experts] as for si_layer_create_placed.
  * Everything else (slicing, placement, forward, stats) is as for si_layer_create; the parts keep the 4-bit
  * form in HBM, in pinned memory and on the host link (102*d_model bytes per 64 hidden columns instead of
  * 384*d_model).  Generation-phase kernels and the host workers multiply codes and scales in fp32 (exact); the
@@ -154,7 +177,7 @@ typedef struct {
   const uint16_t* z_down;
 } si_q4_weights_t;
 int si_layer_create_q4(const si_layer_desc_t* desc, const si_q4_weights_t* routed, const si_q4_weights_t* shared,
-                       si_layer_t** out);
+                       const uint8_t* placement, si_layer_t** out);
 
 /* Hidden-column counts actually used (routed expert n_*, shared expert s_*; any pointer may be
  * NULL).  Tests read the counts from here instead of re-deriving the rounding. */

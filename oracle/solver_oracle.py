@@ -200,3 +200,22 @@ def greedy_memory(t_star, n_m, budget: float):
         _, j, i, cost = best
         cur[j] = i
         left -= cost
+
+
+def place_experts(freq, n_gg: int, cg_share: float):
+    """Whole-expert placement heuristic (this build's, not the paper's): the n_gg most frequent experts are GG (0);
+    the rest, in descending frequency (ties: lower index first), go to CG (1) while CG's share of the frequency
+    handed out so far stays <= cg_share, else to CC (2)."""
+    order = sorted(range(len(freq)), key=lambda e: (-freq[e], e))
+    place = [0] * len(freq)
+    cg = total = 0.0
+    for r, e in enumerate(order):
+        if r < n_gg:
+            continue
+        if cg + freq[e] <= cg_share * (total + freq[e]):
+            place[e] = 1
+            cg += freq[e]
+        else:
+            place[e] = 2
+        total += freq[e]
+    return place

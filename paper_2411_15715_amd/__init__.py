@@ -20,7 +20,7 @@ SI_DECODE_AUTO_T, SI_DECODE_MAX_T = 8, 16
 EXPORTS = ["si_layer_create", "si_layer_split_info", "si_split_counts", "si_layer_forward", "si_route",
            "si_layer_stats", "si_layer_set_profiling", "si_repack_chunks", "si_cc_compute", "si_layer_destroy", "si_last_error", "si_version",
            "si_stack_create", "si_stack_forward", "si_stack_destroy",
-           "si_layer_create_q4", "si_repack_chunks_q4", "si_cc_compute_q4",
+           "si_layer_create_q4", "si_repack_chunks_q4", "si_cc_compute_q4", "si_layer_create_placed", "si_place_experts",
            # scheinfer_solver.h
            "si_fit_linear", "si_model_times", "si_simulate", "si_solve_split", "si_model_times_ng", "si_solve_ng",
            "si_assign_gpu_memory", "si_profile"]
@@ -134,7 +134,11 @@ def lib():
         L.si_last_error.restype = ctypes.c_char_p
         pq = ctypes.POINTER(si_q4_weights_t)
         L.si_layer_create_q4.restype = ctypes.c_int
-        L.si_layer_create_q4.argtypes = [ctypes.POINTER(si_layer_desc_t), pq, pq, ctypes.POINTER(vp)]
+        L.si_layer_create_q4.argtypes = [ctypes.POINTER(si_layer_desc_t), pq, pq, vp, ctypes.POINTER(vp)]
+        L.si_layer_create_placed.restype = ctypes.c_int
+        L.si_layer_create_placed.argtypes = [ctypes.POINTER(si_layer_desc_t), vp, vp, vp, vp, vp, vp, vp, ctypes.POINTER(vp)]
+        L.si_place_experts.restype = ctypes.c_int
+        L.si_place_experts.argtypes = [vp, i32, i32, ctypes.c_double, vp]
         L.si_repack_chunks_q4.restype = ctypes.c_int
         L.si_repack_chunks_q4.argtypes = [pq, i32, i32, i32, i32, vp]
         L.si_cc_compute_q4.restype = ctypes.c_int
@@ -197,16 +201,41 @@ def si_split_counts(d_ff, granule, r_gg, r_cg):
     return tuple(v.value for v in n)
 
 
+def _placement_ptr(placement, n_experts):
+    import numpy as np
+    if placement is None:
+        return None, None
+    a = np.ascontiguousarray(placement, np.uint8)
+    if a.shape != (n_experts,):
+        raise ValueError("placement must have one entry per expert")
+    return a, ctypes.c_void_p(a.ctypes.data)
+
+
 def si_layer_create(d_model, d_ff, n_experts, top_k, w_gate, w_up, w_down, r_gg, r_cg, r_cc, max_tokens,
-                    d_ff_shared=0, shared=None, granule=0, cc_threads=0, device=0, stage_mib=0, n_stage=0):
-    """Returns the opaque layer handle (an int).  Weights are host NumPy uint16 arrays."""
+                    d_ff_shared=0, shared=None, granule=0, cc_threads=0, device=0, stage_mib=0, n_stage=0, placement=None):
+    """Returns the opaque layer handle (an int).  Weights are host NumPy uint16 arrays.  placement: None (slice by
+    the rates) or one of 0 (GG) / 1 (CG) / 2 (CC) per expert (whole-expert placement)."""
     desc = si_layer_desc_t(d_model, d_ff, n_experts, top_k, d_ff_shared, r_gg, r_cg, r_cc, granule, max_tokens,
                            cc_threads, device, stage_mib, n_stage)
     sg, su, sd = shared if shared is not None else (None, None, None)
     out = ctypes.c_void_p(None)
-    _check(lib().si_layer_create(ctypes.byref(desc), _host_ptr(w_gate), _host_ptr(w_up), _host_ptr(w_down),
-                                 _host_ptr(sg), _host_ptr(su), _host_ptr(sd), ctypes.byref(out)))
+    keep, pp = _placement_ptr(placement, n_experts)
+    if pp is None:
+        _check(lib().si_layer_create(ctypes.byref(desc), _host_ptr(w_gate), _host_ptr(w_up), _host_ptr(w_down),
+                                     _host_ptr(sg), _host_ptr(su), _host_ptr(sd), ctypes.byref(out)))
+    else:
+        _check(lib().si_layer_create_placed(ctypes.byref(desc), _host_ptr(w_gate), _host_ptr(w_up), _host_ptr(w_down),
+                                            _host_ptr(sg), _host_ptr(su), _host_ptr(sd), pp, ctypes.byref(out)))
     return out.value
+
+
+def si_place_experts(freq, n_gg, cg_share):
+    """Placement (list of 0 / 1 / 2 per expert) from expert frequencies."""
+    import numpy as np
+    f = np.ascontiguousarray(freq, np.float64)
+    out = np.zeros(f.size, np.uint8)
+    _check(lib().si_place_experts(ctypes.c_void_p(f.ctypes.data), f.size, int(n_gg), float(cg_share), ctypes.c_void_p(out.ctypes.data)))
+    return out.tolist()
 
 
 def _q4_struct(w, prefix=""):
@@ -224,7 +253,7 @@ def _q4_struct(w, prefix=""):
 
 
 def si_layer_create_q4(d_model, d_ff, n_experts, top_k, wq, r_gg, r_cg, r_cc, max_tokens, d_ff_shared=0, granule=0,
-                       cc_threads=0, device=0, stage_mib=0, n_stage=0):
+                       cc_threads=0, device=0, stage_mib=0, n_stage=0, placement=None):
     """Layer from 4-bit weights: wq holds q_gate, q_up, q_down, z_gate, z_up, z_down (and sq_* / sz_* of the shared
     expert when d_ff_shared > 0) as NumPy arrays.  Returns the opaque layer handle."""
     desc = si_layer_desc_t(d_model, d_ff, n_experts, top_k, d_ff_shared, r_gg, r_cg, r_cc, granule, max_tokens,
@@ -235,7 +264,8 @@ def si_layer_create_q4(d_model, d_ff, n_experts, top_k, wq, r_gg, r_cg, r_cc, ma
         sh, keep2 = _q4_struct(wq, "s")
         shared = ctypes.byref(sh)
     out = ctypes.c_void_p(None)
-    _check(lib().si_layer_create_q4(ctypes.byref(desc), ctypes.byref(routed), shared, ctypes.byref(out)))
+    keep3, pp = _placement_ptr(placement, n_experts)
+    _check(lib().si_layer_create_q4(ctypes.byref(desc), ctypes.byref(routed), shared, pp, ctypes.byref(out)))
     return out.value
 
 

@@ -104,6 +104,11 @@ class CcPool {
   }
 
  private:
+  int cc_chunks(int e) const {
+    const CcJob& j = job_;
+    return e >= j.E ? j.s_cc_chunks : j.e_cc_chunks ? j.e_cc_chunks[e] : j.n_cc_chunks;
+  }
+
   // expert-sorted row lists of the X1 tokens (built on the host from idx; order as the GPU's)
   void plan() {
     const CcJob& j = job_;
@@ -125,11 +130,12 @@ class CcPool {
     for (int e = 0; e < EX; ++e) n_blocks += (row_begin_[e + 1] - row_begin_[e] + RB - 1) / RB;
     int want = 4 * n_threads_;
     n_slices_ = n_blocks >= want ? 1 : (want + (n_blocks > 0 ? n_blocks : 1) - 1) / (n_blocks > 0 ? n_blocks : 1);
-    int max_chunks = std::max(j.n_cc_chunks, j.shared ? j.s_cc_chunks : 0);
+    int max_chunks = j.shared ? j.s_cc_chunks : 0;
+    for (int e = 0; e < j.E; ++e) max_chunks = std::max(max_chunks, cc_chunks(e));
     if (n_slices_ > max_chunks) n_slices_ = max_chunks > 0 ? max_chunks : 1;
     items_.clear();
     for (int e = 0; e < EX; ++e) {
-      const int nch = e < j.E ? j.n_cc_chunks : j.s_cc_chunks;
+      const int nch = cc_chunks(e);
       if (nch == 0) continue;
       for (int r = row_begin_[e]; r < row_begin_[e + 1]; r += RB)
         for (int z = 0; z < n_slices_; ++z) {
@@ -145,7 +151,8 @@ class CcPool {
     const CcJob& j = job_;
     const int M = j.M;
     const int PW = panel_width(M), NW = ntile_width(M);
-    const uint16_t* ebase = it.expert < j.E ? j.routed + (size_t)it.expert * j.expert_stride : j.shared;
+    const uint16_t* ebase = it.expert >= j.E ? j.shared
+                            : j.e_off ? j.routed + j.e_off[it.expert] : j.routed + (size_t)it.expert * j.expert_stride;
     xf.resize((size_t)RB * M);
     for (int r = 0; r < it.nrows; ++r) {
       int pr = row_pair_[it.row0 + r];
@@ -257,7 +264,7 @@ class CcPool {
       if (s < j.k) { row = inv_[(size_t)t * j.k + s]; wgt = j.w[(size_t)t * j.k + s]; }
       else { row = row_begin_[j.E] + t; wgt = 1.f; }
       const int e = s < j.k ? j.idx[(size_t)t * j.k + s] : j.E;
-      if ((e < j.E ? j.n_cc_chunks : j.s_cc_chunks) == 0) continue;
+      if (cc_chunks(e) == 0) continue;
       for (int z = 0; z < n_slices_; ++z) {
         const float* src = &scratch_[((size_t)z * n_rows_ + row) * M];
         for (int m = 0; m < M; ++m) out[m] += wgt * src[m];

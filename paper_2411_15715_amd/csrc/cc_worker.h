@@ -71,6 +71,10 @@ struct CcJob {
   int s_cc_chunks;
   float* ycc;             // host [T1][M] fp32, overwritten
   int q4;                 // chunks are in the 4-bit storage form (expert_stride still in uint16 units)
+  // per-expert storage (whole-expert placement), both null or both set: expert e starts at routed + e_off[e]
+  // (uint16 units) and has e_cc_chunks[e] CC chunks; they replace expert_stride / n_cc_chunks
+  const uint64_t* e_off;
+  const int32_t* e_cc_chunks;
 };
 void cc_pool_run(CcPool*, const CcJob& job);   // blocks until done
 void cc_pool_start(CcPool*, const CcJob& job); // asynchronous

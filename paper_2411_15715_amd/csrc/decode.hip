@@ -54,7 +54,9 @@ __global__ __launch_bounds__(GU_THREADS) void k_decode_gateup(const uint16_t* __
   const int blocks_per_chunk = CHUNK_J / GU_JPB;
   const int chunk = wv.chunk0 + blockIdx.x / blocks_per_chunk;
   const int jj0 = (blockIdx.x % blocks_per_chunk) * GU_JPB + wid * GU_JPW;  // first j of this wave in the chunk
-  const uint16_t* cbase = wv.base + (size_t)e * wv.expert_stride + (size_t)chunk * 3 * CHUNK_J * M;
+  int se;
+  if (!storage_index(wv, e, se)) return;
+  const uint16_t* cbase = wv.base + (size_t)se * wv.expert_stride + (size_t)chunk * 3 * CHUNK_J * M;
   // gate / up blocks are [M/PW panels][64 j][PW m]: one wave load = 512 contiguous m of one row
   const u32x4* gblk = reinterpret_cast<const u32x4*>(cbase);
   const u32x4* ublk = reinterpret_cast<const u32x4*>(cbase + (size_t)CHUNK_J * M);
@@ -133,7 +135,9 @@ __global__ __launch_bounds__(DN_THREADS) void k_decode_down(const float* __restr
   const bool active = m < M;
   const int mm = active ? m : 0;
   const int NW = ntile_width(M);
-  const uint16_t* ebase = wv.base + (size_t)e * wv.expert_stride;
+  int se;
+  if (!storage_index(wv, e, se)) return;
+  const uint16_t* ebase = wv.base + (size_t)se * wv.expert_stride;
   float* out = part + (size_t)(slot0 + s) * slot_stride;
 
   extern __shared__ float s_h[];  // [TB][n_j] activations of this slot

@@ -171,6 +171,15 @@ struct si_layer {
   int ch_gg = 0, ch_cg = 0, ch_cc = 0, sch_gg = 0, sch_cg = 0, sch_cc = 0;  // chunks
   size_t ce = 0;                                                            // uint16 units per chunk
   int q4 = 0;                                                               // 4-bit storage form
+  // whole-expert placement: place[e] in {0 GG, 1 CG, 2 CC}; every routed expert keeps all its H/64 chunks in one
+  // place.  ch_gg / ch_cg / ch_cc then hold H/64 when any expert is placed there (else 0), so that everything
+  // sized from them (staging, slots, workers) stays valid; per-expert counts come from e_chunks().
+  int placed = 0;
+  std::vector<uint8_t> place;
+  std::vector<int32_t> gg_map;   // index of expert e in d_gg (-1: not resident); shared expert entry: 0
+  std::vector<uint64_t> h_off;   // uint16 offset of expert e in h_routed
+  std::vector<int32_t> e_cc;     // CC chunks per routed expert (for the workers)
+  int32_t* d_emap = nullptr;     // device copy of gg_map
   uint16_t* d_gg = nullptr;     // device [E][ch_gg] chunks
   uint16_t* d_sgg = nullptr;    // device [sch_gg] chunks
   uint16_t* h_routed = nullptr; // pinned [E][ch_cc + ch_cg] chunks (CC first, then CG)
@@ -218,6 +227,14 @@ struct si_layer {
   std::vector<Seg> segs;
   hipEvent_t ev_t0 = nullptr, ev_t1 = nullptr;
   si_stats_t last{};
+
+  // chunks of part (0 GG, 1 CG, 2 CC) that expert e holds (e == E: the shared expert)
+  int e_chunks(int e, int part) const {
+    if (e >= E) return part == 0 ? sch_gg : part == 1 ? sch_cg : sch_cc;
+    if (placed) return place[e] == part ? H / CHUNK_J : 0;
+    return part == 0 ? ch_gg : part == 1 ? ch_cg : ch_cc;
+  }
+  const uint16_t* host_base(int e) const { return e >= E ? h_shared : h_routed + h_off[e]; }
 };
 
 namespace {
@@ -367,7 +384,7 @@ void si_layer_destroy(si_layer_t* L) {
   if (L->ev_t0) (void)hipEventDestroy(L->ev_t0);
   if (L->ev_t1) (void)hipEventDestroy(L->ev_t1);
   if (L->copy_stream) (void)hipStreamDestroy(L->copy_stream);
-  void* dev[] = {L->d_gg, L->d_sgg, L->d_plan, L->d_h, L->d_part, L->d_hact, L->d_yp, L->d_ycc, L->d_deq};
+  void* dev[] = {L->d_gg, L->d_sgg, L->d_plan, L->d_h, L->d_part, L->d_hact, L->d_yp, L->d_ycc, L->d_deq, L->d_emap};
   for (void* p : dev) if (p) (void)hipFree(p);
   void* pin[] = {L->h_routed, L->h_shared, L->hx, L->hidx, L->hw, L->hcount, L->hycc};
   for (void* p : pin) if (p) (void)hipHostFree(p);
@@ -378,7 +395,7 @@ void si_layer_destroy(si_layer_t* L) {
 
 namespace {
 
-int create_impl(const si_layer_desc_t* desc, const WeightSource& src, si_layer_t** out) {
+int create_impl(const si_layer_desc_t* desc, const WeightSource& src, const uint8_t* placement, si_layer_t** out) {
   int g = 64;
   if (!out) return fail(SI_EINVAL, "out is NULL");
   *out = nullptr;
@@ -408,28 +425,61 @@ int create_impl(const si_layer_desc_t* desc, const WeightSource& src, si_layer_t
   if (L->has_shared) split_counts(L->Hs, g, desc->r_gg, desc->r_cg, &L->s_gg, &L->s_cg, &L->s_cc);
   L->ch_gg = L->n_gg / CHUNK_J; L->ch_cg = L->n_cg / CHUNK_J; L->ch_cc = L->n_cc / CHUNK_J;
   L->sch_gg = L->s_gg / CHUNK_J; L->sch_cg = L->s_cg / CHUNK_J; L->sch_cc = L->s_cc / CHUNK_J;
+  int n_place[3] = {0, 0, 0};
+  if (placement) {
+    L->placed = 1;
+    L->place.assign(placement, placement + L->E);
+    for (int e = 0; e < L->E; ++e) {
+      if (placement[e] > 2) { const int v = placement[e]; delete L; return fail(SI_EINVAL, "placement[%d]=%d must be 0 (GG), 1 (CG) or 2 (CC)", e, v); }
+      n_place[placement[e]]++;
+    }
+    const int Hch = L->H / CHUNK_J;
+    L->ch_gg = n_place[0] ? Hch : 0; L->ch_cg = n_place[1] ? Hch : 0; L->ch_cc = n_place[2] ? Hch : 0;
+    L->n_gg = L->ch_gg * CHUNK_J; L->n_cg = L->ch_cg * CHUNK_J; L->n_cc = L->ch_cc * CHUNK_J;
+  }
   L->q4 = src.q4 ? 1 : 0;
   L->ce = src.q4 ? q4_chunk_u16(L->M) : chunk_elems(L->M);
   const int M = L->M, E = L->E, k = L->k, T = L->max_T;
   const size_t ce = L->ce;
   const int hch = L->ch_cc + L->ch_cg, shch = L->sch_cc + L->sch_cg;
+  // per-expert storage: index in d_gg, offset in h_routed, CC chunks
+  L->gg_map.assign(L->EX, 0);
+  L->h_off.assign(L->E, 0);
+  L->e_cc.assign(L->E, 0);
+  size_t gg_experts = 0, host_units = 0;
+  for (int e = 0; e < L->E; ++e) {
+    const int g_e = L->e_chunks(e, 0), h_e = L->e_chunks(e, 1) + L->e_chunks(e, 2);
+    L->gg_map[e] = g_e > 0 || !L->placed ? (int32_t)gg_experts : -1;
+    if (g_e > 0 || !L->placed) ++gg_experts;
+    L->h_off[e] = host_units;
+    host_units += (size_t)h_e * L->ce;
+    L->e_cc[e] = L->e_chunks(e, 2);
+  }
 
 #define TRY_OR_DESTROY(expr) do { int _rc = (expr); if (_rc) { si_layer_destroy(L); return _rc; } } while (0)
 #define HIP_OR_DESTROY(expr) do { hipError_t _e = (expr); if (_e != hipSuccess) { fail(SI_EHIP, "%s failed: %s", #expr, hipGetErrorString(_e)); si_layer_destroy(L); return SI_EHIP; } } while (0)
 
   // ---- placement: GG -> device, CC | CG -> pinned host (CG' aliases the CC range)
-  TRY_OR_DESTROY(dev_alloc(&L->d_gg, (size_t)E * L->ch_gg * ce));
+  TRY_OR_DESTROY(dev_alloc(&L->d_gg, gg_experts * L->ch_gg * ce));
   TRY_OR_DESTROY(dev_alloc(&L->d_sgg, (size_t)L->sch_gg * ce));
-  TRY_OR_DESTROY(pin_alloc(&L->h_routed, (size_t)E * hch * ce));
+  TRY_OR_DESTROY(pin_alloc(&L->h_routed, host_units));
+  if (L->placed) {
+    TRY_OR_DESTROY(dev_alloc(&L->d_emap, (size_t)L->EX));
+    HIP_OR_DESTROY(hipMemcpy(L->d_emap, L->gg_map.data(), (size_t)L->EX * 4, hipMemcpyHostToDevice));
+  }
   TRY_OR_DESTROY(pin_alloc(&L->h_shared, (size_t)shch * ce));
   const int hw_threads = (int)std::max(1u, std::thread::hardware_concurrency());
   const int rp_threads = std::min(16, hw_threads);
   {
     // host parts: repack straight into the pinned buffers
-    const int per = hch;  // chunks per expert on the host
-    parallel_for(E * per, rp_threads, [&](int i) {
-      int e = i / per, c = i % per;
-      src.repack(e, c, L->H, M, L->h_routed + ((size_t)e * per + c) * ce);
+    // host chunks of expert e: its CC range then its CG range = source chunks [0, CC + CG) in both modes (a placed
+    // expert has all its chunks in one of the two)
+    std::vector<std::pair<int, int>> host_items;
+    for (int e = 0; e < E; ++e)
+      for (int c = 0; c < L->e_chunks(e, 1) + L->e_chunks(e, 2); ++c) host_items.push_back({e, c});
+    parallel_for((int)host_items.size(), rp_threads, [&](int i) {
+      const int e = host_items[i].first, c = host_items[i].second;
+      src.repack(e, c, L->H, M, L->h_routed + L->h_off[e] + (size_t)c * ce);
     });
     parallel_for(shch, rp_threads, [&](int c) { src.repack(-1, c, L->Hs, M, L->h_shared + (size_t)c * ce); });
     // GG parts: repack through a pinned bounce buffer, a group of chunks at a time
@@ -447,7 +497,8 @@ int create_impl(const si_layer_desc_t* desc, const WeightSource& src, si_layer_t
     };
     hipError_t ue = hipSuccess;
     for (int e = 0; e < E && ue == hipSuccess; ++e)
-      ue = upload(e, L->H, hch, L->ch_gg, L->d_gg + (size_t)e * L->ch_gg * ce);
+      if (L->e_chunks(e, 0) > 0)
+        ue = upload(e, L->H, L->placed ? 0 : hch, L->ch_gg, L->d_gg + (size_t)L->gg_map[e] * L->ch_gg * ce);
     if (ue == hipSuccess && L->has_shared) ue = upload(-1, L->Hs, shch, L->sch_gg, L->d_sgg);
     if (bounce) (void)hipHostFree(bounce);
     HIP_OR_DESTROY(ue);
@@ -541,11 +592,20 @@ int si_layer_create(const si_layer_desc_t* desc, const uint16_t* w_gate, const u
                     si_layer_t** out) {
   WeightSource src;
   src.g = w_gate; src.u = w_up; src.d = w_down; src.sg = shared_gate; src.su = shared_up; src.sd = shared_down;
-  return create_impl(desc, src, out);
+  return create_impl(desc, src, nullptr, out);
+}
+
+int si_layer_create_placed(const si_layer_desc_t* desc, const uint16_t* w_gate, const uint16_t* w_up, const uint16_t* w_down,
+                           const uint16_t* shared_gate, const uint16_t* shared_up, const uint16_t* shared_down,
+                           const uint8_t* placement, si_layer_t** out) {
+  if (!placement) return fail(SI_EINVAL, "placement is NULL");
+  WeightSource src;
+  src.g = w_gate; src.u = w_up; src.d = w_down; src.sg = shared_gate; src.su = shared_up; src.sd = shared_down;
+  return create_impl(desc, src, placement, out);
 }
 
 int si_layer_create_q4(const si_layer_desc_t* desc, const si_q4_weights_t* routed, const si_q4_weights_t* shared,
-                       si_layer_t** out) {
+                       const uint8_t* placement, si_layer_t** out) {
   if (!routed) return fail(SI_EINVAL, "routed is NULL");
   if (desc && desc->d_ff_shared > 0 && !shared) return fail(SI_EINVAL, "d_ff_shared > 0 but shared is NULL");
   WeightSource src;
@@ -556,7 +616,7 @@ int si_layer_create_q4(const si_layer_desc_t* desc, const si_q4_weights_t* route
     src.sqg = shared->q_gate; src.squ = shared->q_up; src.sqd = shared->q_down;
     src.szg = shared->z_gate; src.szu = shared->z_up; src.szd = shared->z_down;
   }
-  return create_impl(desc, src, out);
+  return create_impl(desc, src, placement, out);
 }
 
 int si_layer_split_info(const si_layer_t* L, int32_t* n_gg, int32_t* n_cg, int32_t* n_cc, int32_t* s_gg, int32_t* s_cg, int32_t* s_cc) {
@@ -711,6 +771,7 @@ int si_layer_forward(si_layer_t* L, const void* x_dev, const float* logits_dev, 
     CcJob job{};
     job.x = L->hx; job.idx = L->hidx; job.w = L->hw; job.T1 = n_x1; job.k = k; job.M = M; job.E = E;
     job.routed = L->h_routed; job.expert_stride = (size_t)hch * ce; job.n_cc_chunks = L->ch_cc;
+    if (L->placed) { job.e_off = L->h_off.data(); job.e_cc_chunks = L->e_cc.data(); }
     job.shared = (L->has_shared && L->sch_cc > 0) ? L->h_shared : nullptr; job.s_cc_chunks = L->sch_cc;
     job.ycc = L->hycc;
     job.q4 = L->q4;
@@ -727,7 +788,9 @@ int si_layer_forward(si_layer_t* L, const void* x_dev, const float* logits_dev, 
   auto rows_x2 = [&](int e) { return need_sync ? L->hcount[e] - L->hcount[EX + e] : n_g; };
   const int max_touched = std::min(EX, T * k + L->has_shared);
   const int tiles_upper = (T * k) / bm_call + E;  // bound on the routed row tiles
-  const int cps_gg = cps_of(L->ch_gg), cps_cg = cps_of(L->ch_cg), cps_cc = cps_of(L->ch_cc);
+  // (whole-expert placement: every routed expert has H/64 chunks wherever it lives)
+  const int cps_gg = cps_of(L->placed ? L->H / CHUNK_J : L->ch_gg), cps_cg = cps_of(L->placed ? L->H / CHUNK_J : L->ch_cg),
+            cps_cc = cps_of(L->placed ? L->H / CHUNK_J : L->ch_cc);
   const int scps_gg = cps_of(L->sch_gg), scps_cg = cps_of(L->sch_cg), scps_cc = cps_of(L->sch_cc);
   const size_t slot_stride = (size_t)L->rows_dec * M;
   // k-splits of the prefill down projection: enough blocks to fill 256 CUs when there are few row tiles
@@ -742,7 +805,14 @@ int si_layer_forward(si_layer_t* L, const void* x_dev, const float* logits_dev, 
   auto run_part = [&](const uint16_t* base, size_t estride, int expert_sel, int is_shared, int c0, int n, int col_base,
                       int part, int part_chunk0, int x2_only, bool first_for_rows) -> int {
     if (n <= 0) return SI_OK;
-    WeightView wv{base, estride, c0, n, 0, L->q4};
+    WeightView wv{base, estride, c0, n, 0, L->q4, nullptr};
+    if (L->placed && !is_shared) {
+      // every expert has all its chunks in one place: one slot range and one column range serve all parts, and
+      // the launch over all resident experts finds each expert's storage through the map
+      part = 0;
+      col_base = (part_chunk0 + 0) * CHUNK_J;
+      if (expert_sel < 0) wv.e_map = L->d_emap;
+    }
     const int esel = is_shared ? E : expert_sel;
     if (path == SI_DECODE) {
       wv.col0 = col_base;
@@ -772,13 +842,13 @@ int si_layer_forward(si_layer_t* L, const void* x_dev, const float* logits_dev, 
         const bool first = first_for_rows && s0 == 0;
         WeightView wg = wv;
         if (L->q4) {
-          WeightView src{base, estride, c0 + s0, ns, 0, 1};
+          WeightView src{base, estride, c0 + s0, ns, 0, 1, wv.e_map};
           const size_t dst_stride = esel >= 0 ? 0 : (size_t)ns * chunk_elems(M);
           {
             SegScope sc(L, stream, SI_K_FILL);
             K_TRY(launch_dequant_q4(src, M, L->plan, esel, x2_only, E, L->d_deq, dst_stride, stream));
           }
-          wg = WeightView{L->d_deq, dst_stride, 0, ns, 0, 0};
+          wg = WeightView{L->d_deq, dst_stride, 0, ns, 0, 0, nullptr};
         }
         const int ldh = ns * CHUNK_J;
         {
@@ -802,9 +872,15 @@ int si_layer_forward(si_layer_t* L, const void* x_dev, const float* logits_dev, 
     if (path == SI_PREFILL) {
       SegScope sc(L, stream, SI_K_FILL);
       for (int q = 0; q < split_call; ++q) {
-        if (L->ch_gg == 0) K_TRY(launch_fill_zero(L->d_yp + q * L->yp_slab, (size_t)T * k * M, stream));
+        if (L->ch_gg == 0 || L->placed) K_TRY(launch_fill_zero(L->d_yp + q * L->yp_slab, (size_t)T * k * M, stream));
         if (L->has_shared && L->sch_gg == 0) K_TRY(launch_fill_zero(L->d_yp + q * L->yp_slab + (size_t)T * k * M, (size_t)T * M, stream));
       }
+    }
+    if (path == SI_DECODE && L->placed) {
+      // rows of experts that no launch of this call writes (CC experts of X1 tokens) must read as zero in the merge
+      SegScope sc(L, stream, SI_K_FILL);
+      const int n_slots = ceil_div(L->H / CHUNK_J, cps_of(L->H / CHUNK_J));
+      for (int q = 0; q < n_slots; ++q) K_TRY(launch_fill_zero(L->d_part + (size_t)q * slot_stride, (size_t)T * k * M, stream));
     }
     if (E == 1) rc = run_part(L->d_gg, 0, 0, 0, 0, L->ch_gg, hch * CHUNK_J, 0, 0, 0, true);
     else rc = run_part(L->d_gg, (size_t)L->ch_gg * ce, -1, 0, 0, L->ch_gg, hch * CHUNK_J, 0, 0, 0, true);
@@ -816,7 +892,7 @@ int si_layer_forward(si_layer_t* L, const void* x_dev, const float* logits_dev, 
     st.bytes_gg = 0;
     for (int e = 0; e < EX; ++e) {
       const bool touched = need_sync ? L->hcount[e] > 0 : true;
-      if (touched) st.bytes_gg += (double)(e < E ? L->ch_gg : L->sch_gg) * ce * 2;
+      if (touched) st.bytes_gg += (double)L->e_chunks(e, 0) * ce * 2;
     }
     if (!need_sync && E > 1) st.bytes_gg = -1;  // not known on the host without the counts
   }
@@ -826,8 +902,9 @@ int si_layer_forward(si_layer_t* L, const void* x_dev, const float* logits_dev, 
     for (int e = 0; e < EX; ++e) {
       if (rows_all(e) <= 0) continue;
       const bool sh = e >= E;
-      const int n_cc_e = sh ? L->sch_cc : L->ch_cc, n_cg_e = sh ? L->sch_cg : L->ch_cg;
-      const uint16_t* hbase = sh ? L->h_shared : L->h_routed + (size_t)e * hch * ce;
+      const int n_cc_e = L->e_chunks(e, 2), n_cg_e = L->e_chunks(e, 1);
+      if (n_cc_e + n_cg_e == 0) continue;
+      const uint16_t* hbase = L->host_base(e);
       for (int part = 1; part <= 2; ++part) {  // CG on all rows, then CG' (the CC range) on the X2 rows
         const int x2_only = part == 2;
         if (part == 2 && (!need_cgp || rows_x2(e) <= 0)) continue;
@@ -879,7 +956,7 @@ int si_layer_forward(si_layer_t* L, const void* x_dev, const float* logits_dev, 
       cc_pool_wait(L->pool);
       st.cc_ms = std::chrono::duration<float, std::milli>(std::chrono::steady_clock::now() - cc0).count();
       double b = 0;
-      for (int e = 0; e < EX; ++e) if (L->hcount[EX + e] > 0) b += (double)(e < E ? L->ch_cc : L->sch_cc) * ce * 2;
+      for (int e = 0; e < EX; ++e) if (L->hcount[EX + e] > 0) b += (double)L->e_chunks(e, 2) * ce * 2;
       st.bytes_cc = b;
     }
     HIP_TRY(hipMemcpyAsync(L->d_ycc, L->hycc, (size_t)n_x1 * M * 4, hipMemcpyHostToDevice, stream));
@@ -893,6 +970,10 @@ int si_layer_forward(si_layer_t* L, const void* x_dev, const float* logits_dev, 
       DecodeCombineArgs a{};
       a.part = L->d_part; a.slot_stride = slot_stride;
       a.n_slots_gg = ceil_div(L->ch_gg, cps_gg); a.n_slots_cg = ceil_div(L->ch_cg, cps_cg); a.n_slots_cc = need_cgp ? ceil_div(L->ch_cc, cps_cc) : 0;
+      if (L->placed) {  // all parts of the routed experts share the first slot range
+        a.n_slots_gg = ceil_div(L->H / CHUNK_J, cps_of(L->H / CHUNK_J));
+        a.n_slots_cg = a.n_slots_cc = 0;
+      }
       a.s_slots_gg = ceil_div(L->sch_gg, scps_gg); a.s_slots_cg = ceil_div(L->sch_cg, scps_cg); a.s_slots_cc = need_cgp ? ceil_div(L->sch_cc, scps_cc) : 0;
       a.ycc = ycc_dev; a.T = T; a.k = k; a.M = M; a.n_x1 = n_x1; a.has_shared = L->has_shared;
       K_TRY(launch_decode_combine(a, L->plan, y_dev, stream));

@@ -103,7 +103,7 @@ __device__ inline bool map_block(int b, int N, int n_cu, int& L, int& half, int&
   return true;
 }
 
-struct TileInfo { int e, row0, row_end; };
+struct TileInfo { int e, row0, row_end, se; };  // se: index of the expert inside the launch's weight storage
 
 // Number of logical tile ids with work in this launch (row tiles of BM rows x inner tiles).
 template <int BM>
@@ -233,7 +233,7 @@ __device__ __forceinline__ void gateup_body(const uint16_t* __restrict__ x, int 
   using S = Shape<BM>;
   const int tid = threadIdx.x, lane = tid % WAVE, w = tid / WAVE;
   const int wr = w >> 2, wc = w & 3;
-  const uint16_t* ebase = wv.base + (size_t)ti.e * wv.expert_stride;
+  const uint16_t* ebase = wv.base + (size_t)ti.se * wv.expert_stride;
 
   // loader: a wave instruction fills 8 LDS rows (1 KB); lane/8 is the row, lane%8 the slot inside the
   // 128-byte row, which holds logical piece slot ^ ((row >> 1) & 7)
@@ -296,6 +296,7 @@ __global__ __launch_bounds__(THREADS, 1) void k_prefill_gateup(const uint16_t* _
   int tc;
   TileInfo ti;
   if (!block_tile<BM, BM == 256>(p, expert_sel, x2_only, n_ctiles, n_cu, tc, ti)) return;
+  if (!storage_index(wv, ti.e, ti.se)) return;
   if (BM == 256) {
     const int rows = ti.row_end - ti.row0;
     if (rows <= 64) gateup_body<64>(x, M, p, tc, ti, wv, hact, ldh, lds);
@@ -324,7 +325,7 @@ __device__ __forceinline__ void down_body(const uint16_t* __restrict__ hact, int
   const int tid = threadIdx.x, lane = tid % WAVE, w = tid / WAVE;
   const int wr = w >> 2, wc = w & 3;
   const int n0 = nt * BN;
-  const uint16_t* ebase = wv.base + (size_t)ti.e * wv.expert_stride;
+  const uint16_t* ebase = wv.base + (size_t)ti.se * wv.expert_stride;
   float* out = yp + (size_t)split * slab_stride;
 
   const int lrow = lane >> 3, lpp = lane & 7;
@@ -393,6 +394,7 @@ __global__ __launch_bounds__(THREADS, 1) void k_prefill_down(const uint16_t* __r
   TileInfo ti;
   // remap always: one expert's Hact rows (A operand) stay in one L2
   if (!block_tile<BM, true>(p, expert_sel, x2_only, n_ntiles * n_split, n_cu, inner, ti)) return;
+  if (!storage_index(wv, ti.e, ti.se)) return;
   if (BM == 256) {
     const int rows = ti.row_end - ti.row0;
     if (rows <= 64) down_body<64>(hact, ldh, M, inner, ti, n_ntiles, n_split, wv, yp, slab_stride, accumulate, lds);

@@ -77,7 +77,9 @@ __global__ __launch_bounds__(QGU_THREADS) void k_decode_gateup_q4(const uint16_t
   constexpr int blocks_per_chunk = CHUNK_J / QGU_JPB;
   const int chunk = wv.chunk0 + blockIdx.x / blocks_per_chunk;
   const int jj0 = (blockIdx.x % blocks_per_chunk) * QGU_JPB + wid * QGU_JPW;
-  const unsigned char* cb = reinterpret_cast<const unsigned char*>(wv.base + (size_t)e * wv.expert_stride + (size_t)chunk * q4_chunk_u16(M));
+  int se;
+  if (!storage_index(wv, e, se)) return;
+  const unsigned char* cb = reinterpret_cast<const unsigned char*>(wv.base + (size_t)se * wv.expert_stride + (size_t)chunk * q4_chunk_u16(M));
   const u32x4* gq = reinterpret_cast<const u32x4*>(cb + q4_off_codes(0, M));
   const u32x4* uq = reinterpret_cast<const u32x4*>(cb + q4_off_codes(1, M));
   const uint16_t* gs = reinterpret_cast<const uint16_t*>(cb + q4_off_scales(0, M));
@@ -171,7 +173,9 @@ __global__ __launch_bounds__(QDN_THREADS) void k_decode_down_q4(const float* __r
   const bool active = m < M;
   const int mm = active ? m : 0;
   const int NW = ntile_width(M);
-  const uint16_t* ebase = wv.base + (size_t)e * wv.expert_stride;
+  int se;
+  if (!storage_index(wv, e, se)) return;
+  const uint16_t* ebase = wv.base + (size_t)se * wv.expert_stride;
   float* out = part + (size_t)(slot0 + s) * slot_stride;
 
   extern __shared__ float s_hq[];  // [TB][n_j] activations of this slot, then [TB][n_c] their sums per chunk
@@ -240,8 +244,9 @@ __device__ inline uint32_t pack_bf16x2(float a, float b) {
 // 4-bit chunks [c0, c0+n) of the selected experts -> bf16 chunks 0..n of `dst` (expert e at dst + e*dst_estride),
 // value = bf16((code - 8) * scale).  One thread per 32-bit word of codes (8 weights -> one 16-byte store).
 // grid: (n * 24, experts): 8 blocks of work per gate block, 8 per up block, 8 per down block of a chunk.
-__global__ __launch_bounds__(256) void k_dequant_q4(const uint16_t* __restrict__ src, size_t src_estride, int c0, int M,
-                                                    Plan p, int expert_sel, int x2_only, uint16_t* __restrict__ dst,
+__global__ __launch_bounds__(256) void k_dequant_q4(const uint16_t* __restrict__ src, size_t src_estride,
+                                                    const int32_t* __restrict__ e_map, int c0, int M, Plan p,
+                                                    int expert_sel, int x2_only, uint16_t* __restrict__ dst,
                                                     size_t dst_estride) {
   int e, de;
   if (expert_sel >= 0) {
@@ -253,8 +258,10 @@ __global__ __launch_bounds__(256) void k_dequant_q4(const uint16_t* __restrict__
     if (e >= p.n_routed) return;
   }
   if (p.off[e + 1] - p.off[e] - (x2_only ? p.count1[e] : 0) <= 0) return;  // no rows: nobody reads these weights
+  const int se = e_map ? e_map[e] : e;
+  if (se < 0) return;
   const int c = blockIdx.x / 24, sec = (blockIdx.x % 24) / 8, oct = blockIdx.x % 8;
-  const unsigned char* cb = reinterpret_cast<const unsigned char*>(src + (size_t)e * src_estride + (size_t)(c0 + c) * q4_chunk_u16(M));
+  const unsigned char* cb = reinterpret_cast<const unsigned char*>(src + (size_t)se * src_estride + (size_t)(c0 + c) * q4_chunk_u16(M));
   uint16_t* ob = dst + (size_t)de * dst_estride + (size_t)c * 3 * CHUNK_J * M + (size_t)sec * CHUNK_J * M;
   const uint32_t* q = reinterpret_cast<const uint32_t*>(cb + q4_off_codes(sec, M));
   const uint16_t* z = reinterpret_cast<const uint16_t*>(cb + q4_off_scales(sec, M));
@@ -323,8 +330,8 @@ hipError_t launch_dequant_q4(const WeightView& wv, int M, const Plan& plan, int 
                              uint16_t* dst, size_t dst_estride, hipStream_t stream) {
   if (wv.n_chunks <= 0) return hipSuccess;
   dim3 grid(wv.n_chunks * 24, expert_sel >= 0 ? 1 : n_experts);
-  hipLaunchKernelGGL(k_dequant_q4, grid, dim3(256), 0, stream, wv.base, wv.expert_stride, wv.chunk0, M, plan, expert_sel,
-                     x2_only, dst, dst_estride);
+  hipLaunchKernelGGL(k_dequant_q4, grid, dim3(256), 0, stream, wv.base, wv.expert_stride, wv.e_map, wv.chunk0, M, plan,
+                     expert_sel, x2_only, dst, dst_estride);
   return hipGetLastError();
 }
 

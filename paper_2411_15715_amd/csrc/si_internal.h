@@ -63,7 +63,17 @@ struct WeightView {
   int n_chunks;           // number of chunks to process
   int col0;               // hidden column (within the expert) of chunk0: indexes h / Hact columns
   int q4;                 // chunks are in the 4-bit storage form (cc_worker.h); strides still in uint16 units
+  const int32_t* e_map;   // device [experts] or null: storage index of expert e inside `base` (-1: the expert has
+                          // no weights in this storage and the launch skips it); null = expert e is at index e
 };
+
+#if defined(__HIPCC__)
+// storage index of expert e for this launch; false when the launch has nothing for the expert
+__device__ inline bool storage_index(const WeightView& wv, int e, int& se) {
+  se = wv.e_map ? wv.e_map[e] : e;
+  return se >= 0;
+}
+#endif
 
 // decode.hip ---------------------------------------------------------------------------------
 // h[row][j] = SiLU(x_row . Wg[j]) * (x_row . Wu[j]) for the rows of the selected experts.

@@ -331,4 +331,32 @@ int si_assign_gpu_memory(const double* t_star, const double* n_m, int32_t n_laye
   }
 }
 
+int si_place_experts(const double* freq, int32_t n_experts, int32_t n_gg, double cg_share, uint8_t* placement) {
+  if (!freq || !placement) return set_error(SI_EINVAL, "si_place_experts: NULL pointer");
+  if (n_experts < 1 || n_gg < 0 || n_gg > n_experts || !(cg_share >= 0.0 && cg_share <= 1.0))
+    return set_error(SI_EINVAL, "si_place_experts: need n_experts >= 1, 0 <= n_gg <= n_experts, cg_share in [0,1]");
+  std::vector<int> order(n_experts);
+  for (int e = 0; e < n_experts; ++e) {
+    if (!(freq[e] >= 0.0) || !std::isfinite(freq[e])) return set_error(SI_EINVAL, "si_place_experts: freq[%d] must be finite and >= 0", e);
+    order[e] = e;
+  }
+  std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return freq[a] > freq[b]; });
+  double cg = 0.0, all = 0.0;
+  for (int r = 0; r < n_experts; ++r) {
+    const int e = order[r];
+    if (r < n_gg) {
+      placement[e] = 0;
+      continue;
+    }
+    if (cg + freq[e] <= cg_share * (all + freq[e])) {
+      placement[e] = 1;
+      cg += freq[e];
+    } else {
+      placement[e] = 2;
+    }
+    all += freq[e];
+  }
+  return SI_OK;
+}
+
 }  // extern "C"

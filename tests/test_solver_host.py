@@ -177,3 +177,32 @@ def test_profile_rejects_bad_arguments_before_any_gpu_call():
         with pytest.raises(si.ScheInferError) as ei:
             si.si_profile(**kw)
         assert ei.value.code == si.SI_EINVAL
+
+
+def test_place_experts_matches_oracle_and_its_contract():
+    rng = np.random.default_rng(12)
+    for _ in range(200):
+        E = int(rng.integers(1, 65))
+        freq = rng.zipf(1.5, E).astype(np.float64) if rng.random() < 0.5 else rng.random(E)
+        if rng.random() < 0.3:
+            freq = np.round(freq, 1)          # ties
+        n_gg = int(rng.integers(0, E + 1))
+        share = float(rng.choice([0.0, 0.25, 0.5, 0.8, 1.0]))
+        got = si.si_place_experts(freq, n_gg, share)
+        assert got == so.place_experts(freq.tolist(), n_gg, share)
+        # contract: exactly n_gg resident experts and none of the others is more frequent than any of them
+        gg = [e for e in range(E) if got[e] == 0]
+        rest = [e for e in range(E) if got[e] != 0]
+        assert len(gg) == n_gg
+        if gg and rest:
+            assert min(freq[e] for e in gg) >= max(freq[e] for e in rest)
+        # CG's share of the streamed-or-host frequency mass never exceeds cg_share
+        mass = sum(freq[e] for e in rest)
+        if mass > 0:
+            assert sum(freq[e] for e in rest if got[e] == 1) <= share * mass + 1e-12
+        if share == 0.0:
+            assert all(got[e] == 2 for e in rest if freq[e] > 0)
+    with pytest.raises(si.ScheInferError):
+        si.si_place_experts([1.0, 2.0], 3, 0.5)
+    with pytest.raises(si.ScheInferError):
+        si.si_place_experts([1.0, -2.0], 1, 0.5)
