@@ -58,6 +58,9 @@ def parse_args():
                     help="instead of the throughput line: profile this machine (Eq. 3), solve r_CG* for the config's "
                          "r_GG and n_g* for its prompt length (Section IV), and measure the layer over a sweep of "
                          "r_CG and of n_g next to the solved values")
+    ap.add_argument("--place", action="store_true",
+                    help="instead of the throughput line: whole-expert placement against uniform slicing at equal GPU "
+                         "memory (MoE configs), decode calls of the config, bytes streamed and call time")
     ap.add_argument("--stack", type=int, default=0,
                     help="instead of the throughput line: a stack of this many layers of the config's shape under GPU-memory "
                          "budgets of 25/50/75 %% of its weights; greedy per-layer r_GG (Section IV-A.4) against the same "
@@ -442,6 +445,52 @@ def stack_study(args, si, torch, cfg, w):
                       "r_cg_star_by_r_gg": [round(s["r_cg"], 4) for s in sols], "budgets": rows}))
 
 
+def placement_study(args, si, torch, cfg, w):
+    """Whole-expert placement against uniform slicing at the same GPU-memory budget: with a skewed router the
+    most frequently chosen experts are kept resident, so fewer bytes cross the host link per call."""
+    assert cfg.n_experts > 1, "--place needs an MoE config"
+    M, H, E, k = cfg.d_model, cfg.d_ff, cfg.n_experts, cfg.top_k
+    shared = tuple(w[kk] for kk in ("s_gate", "s_up", "s_down")) if cfg.d_ff_shared else None
+    stream = torch.cuda.current_stream().cuda_stream
+    wl = Workload(cfg, args.decode_calls)
+    # expert frequencies from the prompt batch (host arithmetic on the router logits, an input)
+    order = np.argsort(-wl.lp, axis=1, kind="stable")[:, :k]
+    freq = np.bincount(order.ravel(), minlength=E).astype(np.float64)
+
+    def run(split, placement):
+        layer = si.si_layer_create(M, H, E, k, w["w_gate"], w["w_up"], w["w_down"], split[0], split[1], split[2],
+                                   cfg.t_decode, d_ff_shared=cfg.d_ff_shared, shared=shared, placement=placement)
+        try:
+            ts, streamed = [], []
+            si.si_layer_set_profiling(layer, 1)
+            for r in range(4):
+                for xd, ld, _ in wl.dec:
+                    torch.cuda.synchronize()
+                    t0 = time.perf_counter()
+                    si.si_layer_forward(layer, xd.data_ptr(), ld.data_ptr(), cfg.t_decode, 0, si.SI_DECODE, wl.yd.data_ptr(), stream=stream)
+                    torch.cuda.synchronize()
+                    if r:
+                        ts.append(time.perf_counter() - t0)
+                        streamed.append(si.si_layer_stats(layer)["bytes_streamed"])
+            return float(np.mean(ts)), float(np.mean(streamed))
+        finally:
+            si.si_layer_destroy(layer)
+
+    rows = []
+    for frac in (0.125, 0.25, 0.5):
+        n_gg = int(round(frac * E))
+        t_u, b_u = run((frac, 1.0 - frac, 0.0), None)
+        place = si.si_place_experts(freq, n_gg, 1.0)
+        t_p, b_p = run((1.0, 0.0, 0.0), place)
+        mass = float(sum(freq[e] for e in range(E) if place[e] == 0) / freq.sum())
+        rows.append({"gpu_fraction_of_routed_weights": frac, "resident_experts": n_gg, "routing_mass_resident": round(mass, 3),
+                     "uniform_ms": round(1e3 * t_u, 4), "uniform_streamed_MB": round(b_u / 1e6, 2),
+                     "placed_ms": round(1e3 * t_p, 4), "placed_streamed_MB": round(b_p / 1e6, 2),
+                     "speedup": round(t_u / t_p, 3)})
+    print(json.dumps({"placement_study": cfg.name, "tokens_per_call": cfg.t_decode, "experts": E, "top_k": k,
+                      "decode_calls": len(wl.dec), "rows": rows}))
+
+
 def synth_tokens(cfg, T):
     import synth
     return synth.make_tokens(cfg, T, stream=7)
@@ -478,6 +527,9 @@ def main():
         return
     if args.stack:
         stack_study(args, si, torch, cfg, w)
+        return
+    if args.place:
+        placement_study(args, si, torch, cfg, w)
         return
     wl = Workload(cfg, args.decode_calls)
     t_gen = time.perf_counter() - t0
