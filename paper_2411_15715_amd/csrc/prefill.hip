@@ -76,21 +76,19 @@ __device__ inline void block_barrier() {
 //  * XCD-aware remap: consecutive hardware block ids go round-robin over the 8 XCDs; give each XCD a
 //    contiguous range of logical ids so that the row tiles that read the same weights share an L2.  The
 //    ranges are cut from the number of ids that really have work (known on the device only), so that no
-//    XCD is handed a range of empty ids.  In the first GEMM only for the 256-row tiles (several row tiles
-//    per expert, MFMA bound).  With the small tiles an expert has one or two row tiles, nothing is shared,
-//    and the remap would make the 8 XCDs stream 8 regions of memory a whole expert apart (same low address
-//    bits): measured 453 -> 394 us on the weight stream of the Mixtral-shaped gate/up GEMM without it.
+//    XCD is handed a range of empty ids (with ranges cut from the grid's upper bound the remap cost more than
+//    it saved on small tiles: the last XCD idled while the others carried its share).
 //  * Tail split (256-row launches): N tiles on n_cu compute units run in ceil(N / n_cu) rounds; when the
 //    last round is at most half full its tiles are cut into two 128-row halves, each a block of its own,
 //    so that the round costs about half a round (LLaMA-shaped gate/up GEMM: 896 tiles = 3.5 rounds).
-template <int BM, bool REMAP>
+template <int BM>
 __device__ inline bool map_block(int b, int N, int n_cu, int& L, int& half, int& halves) {
   int r = BM == 256 ? N % n_cu : 0;
   if (2 * r > n_cu) r = 0;
   const int main_n = N - r;
   const int per = (main_n + 7) / 8;
   if (b < 8 * per) {
-    L = REMAP ? (b % 8) * per + b / 8 : b;
+    L = (b % 8) * per + b / 8;
     half = 0;
     halves = 1;
     return L < main_n;
@@ -149,11 +147,11 @@ __device__ inline bool decode_tile(const Plan& p, int expert_sel, int x2_only, i
 }
 
 // block id -> tile of this block (false: nothing to do)
-template <int BM, bool REMAP>
+template <int BM>
 __device__ inline bool block_tile(const Plan& p, int expert_sel, int x2_only, int n_inner, int n_cu, int& inner,
                                   TileInfo& ti) {
   int L, half, halves;
-  if (!map_block<BM, REMAP>(blockIdx.x, launch_extent<BM>(p, expert_sel, x2_only, n_inner), n_cu, L, half, halves))
+  if (!map_block<BM>(blockIdx.x, launch_extent<BM>(p, expert_sel, x2_only, n_inner), n_cu, L, half, halves))
     return false;
   if (!decode_tile<BM>(p, expert_sel, x2_only, L, n_inner, inner, ti)) return false;
   if (halves == 2) {
@@ -295,7 +293,7 @@ __global__ __launch_bounds__(THREADS, 1) void k_prefill_gateup(const uint16_t* _
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
   int tc;
   TileInfo ti;
-  if (!block_tile<BM, BM == 256>(p, expert_sel, x2_only, n_ctiles, n_cu, tc, ti)) return;
+  if (!block_tile<BM>(p, expert_sel, x2_only, n_ctiles, n_cu, tc, ti)) return;
   if (!storage_index(wv, ti.e, ti.se)) return;
   if (BM == 256) {
     const int rows = ti.row_end - ti.row0;
@@ -392,8 +390,8 @@ __global__ __launch_bounds__(THREADS, 1) void k_prefill_down(const uint16_t* __r
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
   int inner;
   TileInfo ti;
-  // remap always: one expert's Hact rows (A operand) stay in one L2
-  if (!block_tile<BM, true>(p, expert_sel, x2_only, n_ntiles * n_split, n_cu, inner, ti)) return;
+  // (XCD ranges: one expert's Hact rows, the A operand, stay in one L2)
+  if (!block_tile<BM>(p, expert_sel, x2_only, n_ntiles * n_split, n_cu, inner, ti)) return;
   if (!storage_index(wv, ti.e, ti.se)) return;
   if (BM == 256) {
     const int rows = ti.row_end - ti.row0;
