@@ -32,7 +32,7 @@ def pick_tokens(r_or, T, n_g, seed, n=N_SAMPLE):
     return np.array(sorted(sel), np.int32)
 
 
-def check_config(oracle, name, splits, decode_reps=2, prefill_ng=None):
+def check_config(oracle, name, splits, decode_reps=2, prefill_ng=None, placement=None):
     cfg = synth.CONFIGS[name]
     w = synth.make_weights(cfg, threads=16)
     shared = tuple(w[k] for k in ("s_gate", "s_up", "s_down")) if cfg.d_ff_shared else None
@@ -41,7 +41,8 @@ def check_config(oracle, name, splits, decode_reps=2, prefill_ng=None):
     r_or = oracle.route(lp, cfg.top_k) if lp is not None else None
     refs = {}
     for split in splits:
-        L = GpuLayer(cfg, w, split, max_tokens=max(cfg.t_prefill, cfg.t_decode))
+        pl = placement(r_or) if placement is not None else None
+        L = GpuLayer(cfg, w, split, max_tokens=max(cfg.t_prefill, cfg.t_decode), placement=pl)
         try:
             for rep in range(decode_reps):
                 xd = synth.make_tokens(cfg, cfg.t_decode, stream=200 + rep)
@@ -94,3 +95,12 @@ def test_phimoe_full_sweep(oracle):
 
 def test_mixtral_8x22b_full_sweep(oracle):
     check_config(oracle, "mixtral_8x22b", [(1.0, 0.0, 0.0), (0.4, 0.4, 0.2)], decode_reps=1, prefill_ng=[-256])
+
+
+def test_qwen_moe_full_whole_expert_placement(oracle):
+    # the 16 most used of the 64 experts resident, the rest split between CG and CC; the rates slice the shared expert
+    def place(r_or):
+        pl = si.si_place_experts(r_or["count"].astype(np.float64), 16, 0.5)
+        assert pl.count(0) == 16 and pl.count(1) > 0 and pl.count(2) > 0
+        return pl
+    check_config(oracle, "qwen_moe", [(0.5, 0.3, 0.2)], prefill_ng=[0, 1024], placement=place)

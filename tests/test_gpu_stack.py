@@ -130,3 +130,19 @@ def test_stack_argument_checks():
     finally:
         si.si_layer_destroy(a)
         si.si_layer_destroy(b)
+
+
+def test_stack_full_size_llama_decode(oracle):
+    """Two LLaMA-2-70B-shaped layers at full size (the launch configuration of `bench.py --stack`): a resident
+    layer followed by one split between link and host, generation step of one token, prefetch on."""
+    base = synth.CONFIGS["llama2_70b"]
+    cfgs = [dataclasses.replace(base, seed=300 + i) for i in range(2)]
+    weights = [synth.make_weights(c, threads=16) for c in cfgs]
+    S = GpuStack(cfgs, weights, [(1.0, 0.0, 0.0), (0.0, 0.25, 0.75)], max_tokens=1)
+    try:
+        x1 = synth.make_tokens(base, 1, stream=11)
+        ho = oracle.stack_forward(x1, _oracle_layers(cfgs, weights, None))
+        for pf in (3, 3, 0):
+            assert_parity(S.forward(x1, None, mode=si.SI_DECODE, prefetch=pf), ho)
+    finally:
+        S.close()
