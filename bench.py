@@ -50,6 +50,7 @@ def parse_args():
     ap.add_argument("--decode-calls", type=int, default=16)
     ap.add_argument("--n-g", type=int, default=-1, help="prefill tokens on CG' (default: all when r_cc > 0)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-peaks", action="store_true", help="skip the measurement of this machine's own HBM / MFMA / link peaks")
     ap.add_argument("--no-gg-only", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     ap.add_argument("--q4", action="store_true",
@@ -245,15 +246,24 @@ def eq6_prediction(st):
     return max(tau_g + merge, tau_c)
 
 
+MEASURED_PEAKS = None  # filled by main() from si_measure_peaks(): what the simplest kernels reach on this machine
+
+
 def roofline_of(name, ent, cfg_name=None, split=None):
     traffic = PMC_TRAFFIC.get((cfg_name, tuple(split) if split is not None else None, name))
     if ent["bound"] == "hbm":
         a, p, unit = ent["GBps"], HBM_PEAK_GBS, "GB/s"
+        measured = MEASURED_PEAKS["hbm_read_gbs"] if MEASURED_PEAKS else None
     else:
         a, p, unit = ent["TFLOPs"], MFMA_BF16_PEAK_TF, "TFLOP/s"
-    return {"kernel": name, "bound": ent["bound"], "achieved": round(a, 2), "peak": p, "unit": unit,
-            "frac": round(a / p, 4), "traffic": traffic, "avg_launch_us": round(ent["avg_launch_us"], 2),
-            "launches_per_step": ent["launches_per_step"]}
+        measured = MEASURED_PEAKS["mfma_bf16_tflops"] if MEASURED_PEAKS else None
+    out = {"kernel": name, "bound": ent["bound"], "achieved": round(a, 2), "peak": p, "unit": unit,
+           "frac": round(a / p, 4), "traffic": traffic, "avg_launch_us": round(ent["avg_launch_us"], 2),
+           "launches_per_step": ent["launches_per_step"]}
+    if measured:
+        out["measured_peak"] = round(measured, 1)
+        out["frac_of_measured_peak"] = round(a / measured, 4)
+    return out
 
 
 def cpu_baseline(cfg, w, wl, seconds):
@@ -275,9 +285,19 @@ def cpu_baseline(cfg, w, wl, seconds):
     t1 = run(2)
     n = int(max(2, min(cfg.t_prefill, seconds / max(t1 / 2, 1e-6))))
     t = run(n)
+    # the same oracle on one thread, on a sample a tenth as long
+    oracle.set_threads(1)
+    try:
+        t_one = run(2)
+        n_one = int(max(2, min(n, 0.2 * seconds / max(t_one / 2, 1e-6))))
+        t_one = run(n_one)
+    finally:
+        oracle.set_threads(threads)
     return {"value": round(n / t, 3), "unit": "tokens/s", "cores": threads, "kind": "oracle",
             "sample": "%d of the %d prefill tokens of the step (routing for all tokens, full fp64 layer output for "
-                      "the sampled ones), %.1f s" % (n, cfg.t_prefill, t)}
+                      "the sampled ones), %.1f s" % (n, cfg.t_prefill, t),
+            "single_thread": {"value": round(n_one / t_one, 3), "unit": "tokens/s", "cores": 1,
+                              "sample": "%d tokens, %.1f s" % (n_one, t_one)}}
 
 
 def solver_study(args, si, torch, cfg, w, r_gg):
@@ -514,6 +534,9 @@ def main():
             torch.add(src, 0.0, out=dst)
         torch.cuda.synchronize()
         del src, dst
+    global MEASURED_PEAKS
+    if not args.no_peaks:
+        MEASURED_PEAKS = si.si_measure_peaks(0)
     cfg = synth.CONFIGS[args.config]
     split = tuple(float(v) for v in args.split.split(",")) if args.split else cfg.split
     n_g = args.n_g if args.n_g >= 0 else (cfg.t_prefill if split[2] > 0 else 0)
@@ -556,6 +579,8 @@ def main():
                 "copy_ms_per_step": copy_ms / args.steps,
                 "overlap_prefill": float(np.mean([s["overlap"] for s in pre])),
                 "overlap_decode": float(np.mean([s["overlap"] for s in dec])),
+                "gg_kernel_time_under_copies_prefill": float(np.mean([s["gg_in_copy"] for s in pre])),
+                "gg_kernel_time_under_copies_decode": float(np.mean([s["gg_in_copy"] for s in dec])),
                 "cc_ms_per_step": sum(s["cc_ms"] for _, s in stats) / args.steps,
                 "eq6_predicted_prefill_ms": float(np.mean([eq6_prediction(s) for s in pre])),
                 "eq6_predicted_decode_ms": float(np.mean([eq6_prediction(s) for s in dec])),
@@ -577,6 +602,7 @@ def main():
         "kernels": {k: {kk: (round(vv, 4) if isinstance(vv, float) else vv) for kk, vv in v.items()} for k, v in ktab.items()},
         "host_link": link,
         "input_generation_s": round(t_gen, 1),
+        "measured_peaks": {k: (round(v, 1) if isinstance(v, float) else v) for k, v in MEASURED_PEAKS.items()} if MEASURED_PEAKS else None,
     }
     if not args.no_gg_only and tuple(split) != (1.0, 0.0, 0.0):
         e2, stats2, info2, calls2 = measure(si, torch, cfg, w, (1.0, 0.0, 0.0), wl, args.steps, args.warmup, 0)

@@ -115,6 +115,8 @@ typedef struct {
   float staged_ms;    /* part of gpu_ms spent in kernels that read a staged (CG / CG') piece */
   float handoff_ms;   /* host wait for the token assignment to reach the host (0 if not needed) */
   float enqueue_ms;   /* host wall time spent inside the forward call (Stream-B) */
+  float gg_in_copy;   /* share of the resident-part (GG) kernel time that ran while a weight copy was in flight
+                         (1.0 = the GG compute is completely hidden under the copies; 0 when nothing is copied) */
 } si_stats_t;
 
 /*

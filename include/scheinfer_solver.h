@@ -150,6 +150,21 @@ typedef struct {
 
 int si_profile(const si_profile_desc_t* desc, si_profile_result_t* out);
 
+/*
+ * What this machine sustains on the resources that bound the layer, from the simplest kernels that can reach
+ * them (each the best of 4 runs): a read-only stream over 2 GiB of device memory, a 1 GiB device-to-device copy
+ * (bytes read + written), a register-resident bf16 MFMA loop on every compute unit, one 256 MiB copy from pinned
+ * host memory.  Needs a GPU and ~3.3 GiB of free device memory; allocates and frees its own buffers.
+ */
+typedef struct {
+  double hbm_read_gbs;
+  double hbm_copy_gbs;
+  double mfma_bf16_tflops;
+  double h2d_gbs;
+  int32_t n_cu;
+} si_peaks_t;
+int si_measure_peaks(int32_t device, si_peaks_t* out);
+
 #ifdef __cplusplus
 }
 #endif

@@ -23,7 +23,7 @@ EXPORTS = ["si_layer_create", "si_layer_split_info", "si_split_counts", "si_laye
            "si_layer_create_q4", "si_repack_chunks_q4", "si_cc_compute_q4", "si_layer_create_placed", "si_place_experts",
            # scheinfer_solver.h
            "si_fit_linear", "si_model_times", "si_simulate", "si_solve_split", "si_model_times_ng", "si_solve_ng",
-           "si_assign_gpu_memory", "si_profile"]
+           "si_assign_gpu_memory", "si_profile", "si_measure_peaks"]
 SI_MAX_EDGE_POINTS, SI_PROFILE_MAX_SIZES = 24, 12
 
 
@@ -50,7 +50,8 @@ class si_stats_t(ctypes.Structure):
                 ("bytes_gg", ctypes.c_double), ("bytes_cc", ctypes.c_double), ("overlap", ctypes.c_float),
                 ("n_copies", ctypes.c_int32), ("n_touched", ctypes.c_int32), ("path", ctypes.c_int32),
                 ("kernel_ms", ctypes.c_float * 8), ("kernel_launches", ctypes.c_int32 * 8),
-                ("staged_ms", ctypes.c_float), ("handoff_ms", ctypes.c_float), ("enqueue_ms", ctypes.c_float)]
+                ("staged_ms", ctypes.c_float), ("handoff_ms", ctypes.c_float), ("enqueue_ms", ctypes.c_float),
+                ("gg_in_copy", ctypes.c_float)]
 
 
 class si_perf_model_t(ctypes.Structure):
@@ -75,6 +76,11 @@ class si_ng_solution_t(ctypes.Structure):
     _fields_ = [("n_g", ctypes.c_int32), ("t_fin", ctypes.c_double), ("which_case", ctypes.c_int32),
                 ("n_points", ctypes.c_int32), ("x", ctypes.c_double * SI_MAX_EDGE_POINTS),
                 ("y", ctypes.c_double * SI_MAX_EDGE_POINTS)]
+
+
+class si_peaks_t(ctypes.Structure):
+    _fields_ = [("hbm_read_gbs", ctypes.c_double), ("hbm_copy_gbs", ctypes.c_double), ("mfma_bf16_tflops", ctypes.c_double),
+                ("h2d_gbs", ctypes.c_double), ("n_cu", ctypes.c_int32)]
 
 
 class si_profile_desc_t(ctypes.Structure):
@@ -166,6 +172,8 @@ def lib():
         L.si_solve_ng.argtypes = [pm, i32, i32, i32, f64, i32, f64, f64, ctypes.POINTER(si_ng_solution_t)]
         L.si_assign_gpu_memory.restype = ctypes.c_int
         L.si_assign_gpu_memory.argtypes = [vp, vp, i32, i32, f64, vp]
+        L.si_measure_peaks.restype = ctypes.c_int
+        L.si_measure_peaks.argtypes = [i32, ctypes.POINTER(si_peaks_t)]
         L.si_profile.restype = ctypes.c_int
         L.si_profile.argtypes = [ctypes.POINTER(si_profile_desc_t), ctypes.POINTER(si_profile_result_t)]
         _lib = L
@@ -446,3 +454,10 @@ def si_profile(d_model, d_ff, tokens, mode=SI_AUTO, n_sizes=0, reps=0, cc_thread
     return {"model": {n: getattr(out.model, n) for n in _MODEL_KEYS}, "r2_g": out.r2_g, "r2_c": out.r2_c,
             "r2_c2g": out.r2_c2g, "sigma_launch": out.sigma_launch, "n_gemm": list(out.n_gemm[:k]),
             "t_g": list(out.t_g[:k]), "t_c": list(out.t_c[:k]), "bytes": list(out.bytes[:k]), "t_c2g": list(out.t_c2g[:k])}
+
+
+def si_measure_peaks(device=0) -> dict:
+    """Measured HBM read / copy GB/s, bf16 MFMA TFLOP/s and host-to-device GB/s of this machine."""
+    out = si_peaks_t()
+    _check(lib().si_measure_peaks(device, ctypes.byref(out)))
+    return {n: getattr(out, n) for n, _ in si_peaks_t._fields_}

@@ -1012,6 +1012,26 @@ int si_layer_stats(si_layer_t* L, si_stats_t* out) {
     }
     float mx = std::max(st.copy_ms, std::max(st.gpu_ms, st.cc_ms));
     st.overlap = st.total_ms > 0.f ? mx / st.total_ms : 0.f;
+    // share of the resident-part (GG) kernel time that ran while a weight copy was in flight
+    std::vector<std::pair<float, float>> copies;
+    auto offset = [&](hipEvent_t e, float* o) { return hipEventElapsedTime(o, L->ev_t0, e); };
+    for (const Seg& s : L->segs)
+      if (s.kind == SEG_COPY) {
+        float a = 0.f, b = 0.f;
+        if (offset(s.a, &a) == hipSuccess && offset(s.b, &b) == hipSuccess) copies.push_back({a, b});
+        else (void)hipGetLastError();  // a prefetched copy may have been recorded before this call's first event
+      }
+    float gg_ms = 0.f, gg_cov = 0.f;
+    for (const Seg& s : L->segs) {
+      const bool weight_kernel = s.kind == SI_K_DECODE_GATEUP || s.kind == SI_K_DECODE_DOWN || s.kind == SI_K_PREFILL_GATEUP || s.kind == SI_K_PREFILL_DOWN;
+      if (!weight_kernel || s.staged) continue;
+      float a = 0.f, b = 0.f;
+      HIP_TRY(offset(s.a, &a));
+      HIP_TRY(offset(s.b, &b));
+      gg_ms += b - a;
+      for (const auto& c : copies) gg_cov += std::max(0.f, std::min(b, c.second) - std::max(a, c.first));  // copies do not overlap each other
+    }
+    st.gg_in_copy = gg_ms > 0.f && !copies.empty() ? std::min(1.f, gg_cov / gg_ms) : 0.f;
   }
   *out = st;
   return SI_OK;
