@@ -36,10 +36,13 @@ extern "C" {
 #define SI_EHIP (-3)   /* a HIP runtime call failed (text in si_last_error) */
 #define SI_ESTATE (-4) /* call not valid for this layer, e.g. T > max_tokens */
 
-#define SI_AUTO 0    /* decode path when T <= SI_DECODE_AUTO_T, else prefill path */
+#define SI_AUTO 0    /* decode path when T <= SI_DECODE_AUTO_T and an expert receives on average at most
+                        SI_DECODE_AUTO_ROWS rows (ceil(T*top_k/n_experts)), else prefill path: the GEMV kernels pass
+                        over an expert's weights once per 4 of its rows, the GEMM kernels once per 64..256 */
 #define SI_DECODE 1  /* expert GEMV path (bandwidth bound), T <= SI_DECODE_MAX_T */
 #define SI_PREFILL 2 /* grouped MFMA GEMM path */
 #define SI_DECODE_AUTO_T 8
+#define SI_DECODE_AUTO_ROWS 4
 #define SI_DECODE_MAX_T 16
 
 typedef struct si_layer si_layer_t; /* opaque */

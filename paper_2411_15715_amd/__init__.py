@@ -15,7 +15,7 @@ LIB_PATH = os.path.join(_HERE, "libscheinfer.so")
 
 SI_OK, SI_EINVAL, SI_ENOMEM, SI_EHIP, SI_ESTATE = 0, -1, -2, -3, -4
 SI_AUTO, SI_DECODE, SI_PREFILL = 0, 1, 2
-SI_DECODE_AUTO_T, SI_DECODE_MAX_T = 8, 16
+SI_DECODE_AUTO_T, SI_DECODE_AUTO_ROWS, SI_DECODE_MAX_T = 8, 4, 16
 
 EXPORTS = ["si_layer_create", "si_layer_split_info", "si_split_counts", "si_layer_forward", "si_route",
            "si_layer_stats", "si_layer_set_profiling", "si_repack_chunks", "si_cc_compute", "si_layer_destroy", "si_last_error", "si_version",

@@ -8,6 +8,7 @@
 // result does not depend on scheduling.  A second pass sums slices and slots per token.
 #include <atomic>
 #include <condition_variable>
+#include <cstdlib>
 #include <cstring>
 #include <mutex>
 #include <thread>
@@ -15,6 +16,7 @@
 
 #include <algorithm>
 #include <cmath>
+#include <immintrin.h>
 
 #include "cc_worker.h"
 
@@ -58,6 +60,69 @@ inline float bf16_to_f32(uint16_t b) {
 inline float hsum(v8f v) { return ((v[0] + v[4]) + (v[2] + v[6])) + ((v[1] + v[5]) + (v[3] + v[7])); }
 
 inline float silu_f(float z) { return z / (1.f + std::exp(-z)); }
+
+// ---- AVX-512 (with BF16 dot products) versions of the two steps on the bf16 storage form, chosen at run time.
+// FC1: x and the weights are both bf16, so vdpbf16ps forms the products exactly and accumulates them in fp32,
+// 32 weights per instruction and no conversions.  FC2: h stays fp32; weights are widened 16 at a time.
+#define SI_AVX512 __attribute__((target("avx512f,avx512bw,avx512vl,avx512dq,avx512bf16")))
+
+bool cpu_has_avx512_bf16() {
+  static const bool ok = __builtin_cpu_supports("avx512f") && __builtin_cpu_supports("avx512bw") &&
+                         __builtin_cpu_supports("avx512vl") && __builtin_cpu_supports("avx512dq") &&
+                         __builtin_cpu_supports("avx512bf16");
+  return ok;
+}
+
+// h[r][jj] for the 64 hidden columns of one chunk; xrow[r] points at the bf16 token (M elements)
+SI_AVX512 void fc1_chunk_avx512(const uint16_t* gblk, const uint16_t* ublk, const uint16_t* const* xrow, int nrows, int M,
+                                int PW, float* hbuf, int rb) {
+  for (int jj = 0; jj < CHUNK_J; ++jj) {
+    __m512 ag[8], au[8];
+    for (int r = 0; r < rb; ++r) { ag[r] = _mm512_setzero_ps(); au[r] = _mm512_setzero_ps(); }
+    for (int p0 = 0; p0 < M; p0 += PW) {
+      const uint16_t* grow = gblk + ((size_t)(p0 / PW) * CHUNK_J + jj) * PW;
+      const uint16_t* urow = ublk + ((size_t)(p0 / PW) * CHUNK_J + jj) * PW;
+      for (int m = 0; m < PW; m += 32) {
+        const __m512bh wg = (__m512bh)_mm512_loadu_si512(grow + m), wu = (__m512bh)_mm512_loadu_si512(urow + m);
+        for (int r = 0; r < nrows; ++r) {
+          const __m512bh xv = (__m512bh)_mm512_loadu_si512(xrow[r] + p0 + m);
+          ag[r] = _mm512_dpbf16_ps(ag[r], wg, xv);
+          au[r] = _mm512_dpbf16_ps(au[r], wu, xv);
+        }
+      }
+    }
+    for (int r = 0; r < nrows; ++r) {
+      const float g = _mm512_reduce_add_ps(ag[r]), u = _mm512_reduce_add_ps(au[r]);
+      hbuf[(size_t)r * CHUNK_J + jj] = g / (1.f + std::exp(-g)) * u;
+    }
+  }
+}
+
+// out[r][m] += sum_j h[r][j] Wd[j][m] over the 64 j of one chunk; down block [M/NW][8 q][NW m][8 i]
+SI_AVX512 void fc2_chunk_avx512(const uint16_t* db, const float* hbuf, int nrows, int M, int NW, float* const* out) {
+  for (int m = 0; m < M; m += 2) {
+    __m512 acc[8];
+    for (int r = 0; r < nrows; ++r) acc[r] = _mm512_setzero_ps();
+    for (int q = 0; q < 8; ++q) {
+      // 16 bf16: columns m and m+1, rows 8q..8q+7 each (m is even and NW is even, so both lie in one tile)
+      const __m256i raw = _mm256_loadu_si256(reinterpret_cast<const __m256i*>(db + dn_off(q * 8, m, NW)));
+      const __m512 w = _mm512_castsi512_ps(_mm512_slli_epi32(_mm512_cvtepu16_epi32(raw), 16));
+      for (int r = 0; r < nrows; ++r) {
+        const __m512 hv = _mm512_broadcast_f32x8(_mm256_loadu_ps(hbuf + (size_t)r * CHUNK_J + q * 8));
+        acc[r] = _mm512_fmadd_ps(hv, w, acc[r]);
+      }
+    }
+    for (int r = 0; r < nrows; ++r) {
+      const __m256 lo = _mm512_castps512_ps256(acc[r]), hi = _mm512_extractf32x8_ps(acc[r], 1);
+      // sum of the 8 lanes of each half
+      __m256 t = _mm256_hadd_ps(lo, hi);          // (l0+l1, l2+l3, h0+h1, h2+h3 | l4+l5, l6+l7, h4+h5, h6+h7)
+      t = _mm256_hadd_ps(t, t);                   // (l0..3, h0..3, .. | l4..7, h4..7, ..)
+      const __m128 s = _mm_add_ps(_mm256_castps256_ps128(t), _mm256_extractf128_ps(t, 1));
+      out[r][m] += _mm_cvtss_f32(s);
+      out[r][m + 1] += _mm_cvtss_f32(_mm_shuffle_ps(s, s, 1));
+    }
+  }
+}
 
 struct Item {
   int expert;      // E = shared
@@ -166,6 +231,21 @@ class CcPool {
     hbuf.resize((size_t)RB * CHUNK_J);
     if (j.q4) {
       run_chunks_q4(it, ebase, xf, hbuf);
+      return;
+    }
+    if (cpu_has_avx512_bf16() && !force_generic_) {
+      const uint16_t* xrow[RB];
+      float* orow[RB];
+      for (int r = 0; r < it.nrows; ++r) {
+        const int pr = row_pair_[it.row0 + r];
+        xrow[r] = j.x + (size_t)(pr >= 0 ? pr / j.k : -pr - 1) * M;
+        orow[r] = &scratch_[((size_t)it.slice * n_rows_ + it.row0 + r) * M];
+      }
+      for (int c = it.c0; c < it.c1; ++c) {
+        const uint16_t* cb = ebase + (size_t)c * 3 * CHUNK_J * M;
+        fc1_chunk_avx512(cb, cb + (size_t)CHUNK_J * M, xrow, it.nrows, M, PW, hbuf.data(), RB);
+        fc2_chunk_avx512(cb + (size_t)2 * CHUNK_J * M, hbuf.data(), it.nrows, M, NW, orow);
+      }
       return;
     }
     for (int c = it.c0; c < it.c1; ++c) {
@@ -312,6 +392,7 @@ class CcPool {
     }
   }
 
+  bool force_generic_ = std::getenv("SI_CC_GENERIC") != nullptr;  // run the portable loops even where AVX-512 exists (tests)
   int n_threads_;
   std::vector<std::thread> threads_;
   std::mutex mu_, inv_mu_;

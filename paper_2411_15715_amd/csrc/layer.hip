@@ -564,7 +564,7 @@ int create_impl(const si_layer_desc_t* desc, const WeightSource& src, const uint
       cols = L->deq_chunks * CHUNK_J;
     }
     L->hact_elems = n_rows * (size_t)cols;
-    if (T > SI_DECODE_AUTO_T || true) TRY_OR_DESTROY(dev_alloc(&L->d_hact, L->hact_elems));
+    TRY_OR_DESTROY(dev_alloc(&L->d_hact, L->hact_elems));
     L->yp_slab = n_rows * (size_t)M;
     TRY_OR_DESTROY(dev_alloc(&L->d_yp, (size_t)MAX_KSPLIT * L->yp_slab));
   }
@@ -710,7 +710,8 @@ int si_layer_forward(si_layer_t* L, const void* x_dev, const float* logits_dev, 
   if (T == 0) return SI_OK;
   if (!x_dev || !y_dev) return fail(SI_EINVAL, "x_dev or y_dev is NULL");
   if (L->E > 1 && !logits_dev) return fail(SI_EINVAL, "logits_dev is NULL for a layer with %d experts", L->E);
-  const int path = mode == SI_AUTO ? (T <= SI_DECODE_AUTO_T ? SI_DECODE : SI_PREFILL) : mode;
+  const bool few_rows = T <= SI_DECODE_AUTO_T && ceil_div(T * L->k, L->E) <= SI_DECODE_AUTO_ROWS;
+  const int path = mode == SI_AUTO ? (few_rows ? SI_DECODE : SI_PREFILL) : mode;
   if (path == SI_DECODE && T > SI_DECODE_MAX_T) return fail(SI_ESTATE, "SI_DECODE needs T <= %d (T=%d)", SI_DECODE_MAX_T, T);
   HIP_TRY(hipSetDevice(L->device));
   hipStream_t stream = (hipStream_t)stream_v;

@@ -103,7 +103,7 @@ extern "C" int si_profile(const si_profile_desc_t* desc, si_profile_result_t* ou
   if (d.n_sizes < 2 || d.n_sizes > SI_PROFILE_MAX_SIZES || d.reps < 1 || d.copy_max_mib < 1 || d.copy_max_mib > 4096)
     return set_error(SI_EINVAL, "si_profile: n_sizes in 2..%d, reps >= 1, copy_max_mib in 1..4096", SI_PROFILE_MAX_SIZES);
   int mode = d.mode;
-  if (mode == SI_AUTO) mode = d.tokens <= SI_DECODE_AUTO_T ? SI_DECODE : SI_PREFILL;
+  if (mode == SI_AUTO) mode = d.tokens <= SI_DECODE_AUTO_ROWS ? SI_DECODE : SI_PREFILL;  // a dense layer: rows = tokens
   if (mode != SI_DECODE && mode != SI_PREFILL) return set_error(SI_EINVAL, "si_profile: bad mode");
   if (mode == SI_DECODE && d.tokens > SI_DECODE_MAX_T) return set_error(SI_EINVAL, "si_profile: decode path takes at most %d tokens", SI_DECODE_MAX_T);
   // distinct hidden sizes h_i = d_ff*(i+1)/n_sizes rounded down to 64 columns

@@ -126,10 +126,16 @@ def _pack_host(w, key_g, key_u, key_d, n_chunks):
     return np.concatenate([si.si_repack_chunks(g[e], u[e], d[e], 0, n_chunks) for e in range(E)])
 
 
+@pytest.mark.parametrize("generic", [False, True])
 @pytest.mark.parametrize("T1,threads", [(1, 3), (5, 4), (40, 4)])
-def test_cc_workers_match_oracle_cc_partial(oracle, T1, threads):
+def test_cc_workers_match_oracle_cc_partial(oracle, T1, threads, generic, monkeypatch):
     """The CC partial (columns [0, n_cc) of every expert, Eq. 2) from the host workers equals the
-    oracle evaluated on those columns alone."""
+    oracle evaluated on those columns alone.  Both code paths of the workers: the AVX-512 BF16 one (taken where
+    the CPU has it) and the portable one."""
+    if generic:
+        monkeypatch.setenv("SI_CC_GENERIC", "1")
+    else:
+        monkeypatch.delenv("SI_CC_GENERIC", raising=False)
     cfg = synth.scaled(synth.CONFIGS["qwen_moe"], d_model=128, d_ff=256, d_ff_shared=384, n_experts=8, top_k=3)
     w = synth.make_weights(cfg)
     xb = synth.make_tokens(cfg, T1)
