@@ -69,6 +69,8 @@ typedef struct {
   int32_t device;      /* HIP device ordinal */
   int32_t stage_mib;   /* size of one staging buffer for CG copies in MiB; 0 -> 256 */
   int32_t n_stage;     /* number of staging buffers (>= 2); 0 -> 2 (double buffering) */
+  int32_t deq_mib;     /* 4-bit layers only: device scratch in MiB for the bf16 copies the prompt-phase GEMMs read
+                          (never more than the largest part needs); 0 -> 2048 */
 } si_layer_desc_t;
 
 /* Optional device outputs of the token-assignment step; any pointer may be NULL.

@@ -32,7 +32,7 @@ class si_layer_desc_t(ctypes.Structure):
                 ("top_k", ctypes.c_int32), ("d_ff_shared", ctypes.c_int32), ("r_gg", ctypes.c_float),
                 ("r_cg", ctypes.c_float), ("r_cc", ctypes.c_float), ("granule", ctypes.c_int32),
                 ("max_tokens", ctypes.c_int32), ("cc_threads", ctypes.c_int32), ("device", ctypes.c_int32),
-                ("stage_mib", ctypes.c_int32), ("n_stage", ctypes.c_int32)]
+                ("stage_mib", ctypes.c_int32), ("n_stage", ctypes.c_int32), ("deq_mib", ctypes.c_int32)]
 
 
 class si_q4_weights_t(ctypes.Structure):
@@ -261,11 +261,11 @@ def _q4_struct(w, prefix=""):
 
 
 def si_layer_create_q4(d_model, d_ff, n_experts, top_k, wq, r_gg, r_cg, r_cc, max_tokens, d_ff_shared=0, granule=0,
-                       cc_threads=0, device=0, stage_mib=0, n_stage=0, placement=None):
+                       cc_threads=0, device=0, stage_mib=0, n_stage=0, placement=None, deq_mib=0):
     """Layer from 4-bit weights: wq holds q_gate, q_up, q_down, z_gate, z_up, z_down (and sq_* / sz_* of the shared
     expert when d_ff_shared > 0) as NumPy arrays.  Returns the opaque layer handle."""
     desc = si_layer_desc_t(d_model, d_ff, n_experts, top_k, d_ff_shared, r_gg, r_cg, r_cc, granule, max_tokens,
-                           cc_threads, device, stage_mib, n_stage)
+                           cc_threads, device, stage_mib, n_stage, deq_mib)
     routed, keep = _q4_struct(wq)
     shared = None
     if d_ff_shared:
