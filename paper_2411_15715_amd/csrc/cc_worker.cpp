@@ -124,6 +124,134 @@ SI_AVX512 void fc2_chunk_avx512(const uint16_t* db, const float* hbuf, int nrows
   }
 }
 
+
+// ---- AVX-512 versions for the 4-bit storage form.  Codes become bf16 pairs without any widening: for a 32-bit
+// word w of gate / up codes, ((w >> 4p) & 0x000F000F) | 0x43004300 holds the bf16 values 128 + code of elements
+// 2p and 2p+1 of the word (exact), and vdpbf16ps multiplies them with the matching bf16 pair of x.  Per group of
+// 64 weights: x.W = scale * (sum x (128 + code) - 136 sum x).  The pairs of x (and of h for FC2, split into a
+// bf16 head and a bf16 remainder so that h keeps ~16 significant bits) are laid out once per token in the order
+// the shifted words deliver the codes.
+struct Q4X {                      // per token: M/128 blocks of 128 elements = 16 code words
+  std::vector<uint32_t> pairs;    // [block][p][16]  lane i = x pair (elements 8i+2p, 8i+2p+1 of the block)
+  std::vector<float> wsum;        // [block][16]     lane i = sum of the 8 x values of word i
+};
+
+SI_AVX512 void q4_prepare_x(const uint16_t* x, int M, Q4X* o) {
+  const int nb = M / 128;
+  o->pairs.resize((size_t)nb * 64);
+  o->wsum.resize((size_t)nb * 16);
+  const uint32_t* xp = reinterpret_cast<const uint32_t*>(x);
+  for (int b = 0; b < nb; ++b) {
+    uint32_t(*lane)[16] = reinterpret_cast<uint32_t(*)[16]>(&o->pairs[(size_t)b * 64]);
+    float* sum = &o->wsum[(size_t)b * 16];
+    for (int i = 0; i < 16; ++i) {
+      float s = 0.f;
+      for (int pp = 0; pp < 4; ++pp) {
+        const uint32_t u = xp[64 * b + 4 * i + pp];
+        lane[pp][i] = u;
+        s += bf16_to_f32((uint16_t)(u & 0xffffu)) + bf16_to_f32((uint16_t)(u >> 16));
+      }
+      sum[i] = s;
+    }
+  }
+}
+
+SI_AVX512 inline __m512i q4_pairs(__m512i w, int shift, __m512i mask, __m512i magic) {
+  // (w >> shift) & mask | magic in two instructions (shift, ternary logic 0xEA = (a & b) | c)
+  return _mm512_ternarylogic_epi32(_mm512_srli_epi32(w, shift), mask, magic, 0xEA);
+}
+
+// h[r][jj] for the 64 hidden columns of one chunk (M a multiple of 128)
+SI_AVX512 void fc1_chunk_q4_avx512(const uint32_t* gq, const uint32_t* uq, const uint16_t* gs, const uint16_t* us,
+                                   const Q4X* xs, int nrows, int M, float* hbuf) {
+  const __m512i mask = _mm512_set1_epi32(0x000F000F), magic = _mm512_set1_epi32(0x43004300);
+  const __m512 off = _mm512_set1_ps(136.f);
+  const int nb = M / 128, MG = M / 64;
+  for (int jj = 0; jj < CHUNK_J; ++jj) {
+    __m512 ag[8], au[8];
+    for (int r = 0; r < nrows; ++r) { ag[r] = _mm512_setzero_ps(); au[r] = _mm512_setzero_ps(); }
+    const uint32_t* grow = gq + (size_t)jj * (M / 8);
+    const uint32_t* urow = uq + (size_t)jj * (M / 8);
+    for (int b = 0; b < nb; ++b) {
+      const __m512i wg = _mm512_loadu_si512(grow + 16 * b), wu = _mm512_loadu_si512(urow + 16 * b);
+      __m512i pg[4], pu[4];
+      for (int pp = 0; pp < 4; ++pp) { pg[pp] = q4_pairs(wg, 4 * pp, mask, magic); pu[pp] = q4_pairs(wu, 4 * pp, mask, magic); }
+      // words 0..7 of the block belong to scale group 2b, words 8..15 to group 2b+1
+      const __m512 sg = _mm512_mask_blend_ps(0xFF00, _mm512_set1_ps(bf16_to_f32(gs[(size_t)jj * MG + 2 * b])),
+                                             _mm512_set1_ps(bf16_to_f32(gs[(size_t)jj * MG + 2 * b + 1])));
+      const __m512 su = _mm512_mask_blend_ps(0xFF00, _mm512_set1_ps(bf16_to_f32(us[(size_t)jj * MG + 2 * b])),
+                                             _mm512_set1_ps(bf16_to_f32(us[(size_t)jj * MG + 2 * b + 1])));
+      for (int r = 0; r < nrows; ++r) {
+        const uint32_t* xp = &xs[r].pairs[(size_t)b * 64];
+        __m512 dg = _mm512_setzero_ps(), du = _mm512_setzero_ps();
+        for (int pp = 0; pp < 4; ++pp) {
+          const __m512bh xv = (__m512bh)_mm512_loadu_si512(xp + 16 * pp);
+          dg = _mm512_dpbf16_ps(dg, (__m512bh)pg[pp], xv);
+          du = _mm512_dpbf16_ps(du, (__m512bh)pu[pp], xv);
+        }
+        const __m512 corr = _mm512_mul_ps(off, _mm512_loadu_ps(&xs[r].wsum[(size_t)b * 16]));
+        ag[r] = _mm512_fmadd_ps(sg, _mm512_sub_ps(dg, corr), ag[r]);
+        au[r] = _mm512_fmadd_ps(su, _mm512_sub_ps(du, corr), au[r]);
+      }
+    }
+    for (int r = 0; r < nrows; ++r) {
+      const float g = _mm512_reduce_add_ps(ag[r]), u = _mm512_reduce_add_ps(au[r]);
+      hbuf[(size_t)r * CHUNK_J + jj] = g / (1.f + std::exp(-g)) * u;
+    }
+  }
+}
+
+// out[r][m] += scale[m] * (sum_j h[r][j] code[j][m] - 8 sum_j h[r][j]) over the 64 j of one chunk.
+// Down codes: [M/NW][2 halves][NW m][16 bytes]; inside a word element e sits at nibble 2e (e < 4) or 2(e-4)+1, so
+// the shift by 4q pairs up elements (0,2), (4,6), (1,3), (5,7) for q = 0..3.
+SI_AVX512 void fc2_chunk_q4_avx512(const uint32_t* dq, const uint16_t* ds, const float* hbuf, int nrows, int M, int NW,
+                                   float* const* out) {
+  static const int EA[4] = {0, 4, 1, 5}, EB[4] = {2, 6, 3, 7};
+  const __m512i mask = _mm512_set1_epi32(0x000F000F), magic = _mm512_set1_epi32(0x43004300);
+  // per row: pairs of h in the order above, as bf16 head and bf16 remainder; lane = (m_local 0..3, word k 0..3)
+  alignas(64) uint32_t hh[8][2][4][16], hl[8][2][4][16];
+  float hsum[8];
+  for (int r = 0; r < nrows; ++r) {
+    const float* h = hbuf + (size_t)r * CHUNK_J;
+    auto head = [](float v) { uint32_t u; std::memcpy(&u, &v, 4); return u & 0xffff0000u; };
+    auto as_f = [](uint32_t u) { float v; std::memcpy(&v, &u, 4); return v; };
+    auto tail = [&](float v) { return head(v - as_f(head(v))); };
+    // the offset term uses the sum of exactly the values the dot products see (head + remainder), so that the
+    // 128 * sum h parts cancel to rounding
+    float s = 0.f;
+    for (int jx = 0; jx < CHUNK_J; ++jx) s += as_f(head(h[jx])) + as_f(tail(h[jx]));
+    hsum[r] = s;
+    for (int half = 0; half < 2; ++half)
+      for (int q = 0; q < 4; ++q)
+        for (int k = 0; k < 4; ++k) {
+          const float a = h[32 * half + 8 * k + EA[q]], b = h[32 * half + 8 * k + EB[q]];
+          const uint32_t ph = (head(a) >> 16) | head(b), pl = (tail(a) >> 16) | tail(b);
+          for (int ml = 0; ml < 4; ++ml) { hh[r][half][q][ml * 4 + k] = ph; hl[r][half][q][ml * 4 + k] = pl; }
+        }
+  }
+  for (int m = 0; m < M; m += 4) {
+    const size_t i0 = (((size_t)(m / NW) * 2) * NW + (m % NW)) * 4;  // word index of (half 0, column m)
+    const __m512i w0 = _mm512_loadu_si512(dq + i0), w1 = _mm512_loadu_si512(dq + i0 + (size_t)NW * 4);
+    __m512i p0[4], p1[4];
+    for (int q = 0; q < 4; ++q) { p0[q] = q4_pairs(w0, 4 * q, mask, magic); p1[q] = q4_pairs(w1, 4 * q, mask, magic); }
+    for (int r = 0; r < nrows; ++r) {
+      __m512 acc = _mm512_setzero_ps();
+      for (int q = 0; q < 4; ++q) {
+        acc = _mm512_dpbf16_ps(acc, (__m512bh)p0[q], (__m512bh)_mm512_load_si512(hh[r][0][q]));
+        acc = _mm512_dpbf16_ps(acc, (__m512bh)p0[q], (__m512bh)_mm512_load_si512(hl[r][0][q]));
+        acc = _mm512_dpbf16_ps(acc, (__m512bh)p1[q], (__m512bh)_mm512_load_si512(hh[r][1][q]));
+        acc = _mm512_dpbf16_ps(acc, (__m512bh)p1[q], (__m512bh)_mm512_load_si512(hl[r][1][q]));
+      }
+      alignas(64) float lanes[16];
+      _mm512_store_ps(lanes, acc);
+      for (int ml = 0; ml < 4; ++ml) {
+        const float dot = (lanes[4 * ml] + lanes[4 * ml + 1]) + (lanes[4 * ml + 2] + lanes[4 * ml + 3]);
+        out[r][m + ml] += bf16_to_f32(ds[m + ml]) * (dot - 136.f * hsum[r]);
+      }
+    }
+  }
+}
+
 struct Item {
   int expert;      // E = shared
   int row0, nrows; // range in the expert's row list
@@ -229,6 +357,24 @@ class CcPool {
       }
     }
     hbuf.resize((size_t)RB * CHUNK_J);
+    if (j.q4 && cpu_has_avx512_bf16() && !force_generic_ && M % 128 == 0) {
+      Q4X xq[RB];
+      float* orow[RB];
+      for (int r = 0; r < it.nrows; ++r) {
+        const int pr = row_pair_[it.row0 + r];
+        q4_prepare_x(j.x + (size_t)(pr >= 0 ? pr / j.k : -pr - 1) * M, M, &xq[r]);
+        orow[r] = &scratch_[((size_t)it.slice * n_rows_ + it.row0 + r) * M];
+      }
+      for (int c = it.c0; c < it.c1; ++c) {
+        const unsigned char* cb = reinterpret_cast<const unsigned char*>(ebase + (size_t)c * q4_chunk_u16(M));
+        fc1_chunk_q4_avx512(reinterpret_cast<const uint32_t*>(cb + q4_off_codes(0, M)), reinterpret_cast<const uint32_t*>(cb + q4_off_codes(1, M)),
+                            reinterpret_cast<const uint16_t*>(cb + q4_off_scales(0, M)), reinterpret_cast<const uint16_t*>(cb + q4_off_scales(1, M)),
+                            xq, it.nrows, M, hbuf.data());
+        fc2_chunk_q4_avx512(reinterpret_cast<const uint32_t*>(cb + q4_off_codes(2, M)), reinterpret_cast<const uint16_t*>(cb + q4_off_scales(2, M)),
+                            hbuf.data(), it.nrows, M, NW, orow);
+      }
+      return;
+    }
     if (j.q4) {
       run_chunks_q4(it, ebase, xf, hbuf);
       return;

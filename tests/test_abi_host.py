@@ -202,8 +202,13 @@ def test_repack_layout_q4(M):
         si.si_repack_chunks_q4(wq, 2, 2)
 
 
+@pytest.mark.parametrize("generic", [False, True])
 @pytest.mark.parametrize("T1,threads", [(1, 3), (6, 4), (40, 4)])
-def test_cc_workers_q4_match_oracle_cc_partial(oracle, T1, threads):
+def test_cc_workers_q4_match_oracle_cc_partial(oracle, T1, threads, generic, monkeypatch):
+    if generic:
+        monkeypatch.setenv("SI_CC_GENERIC", "1")
+    else:
+        monkeypatch.delenv("SI_CC_GENERIC", raising=False)
     cfg = synth.scaled(synth.CONFIGS["qwen_moe"], d_model=128, d_ff=256, d_ff_shared=384, n_experts=8, top_k=3)
     wq = synth.make_weights_q4(cfg)
     xb = synth.make_tokens(cfg, T1)
