@@ -306,7 +306,7 @@ def solver_study(args, si, torch, cfg, w, r_gg):
     fixed there, the prompt-phase n_g* (Section IV-B); then measure the real layer at the solved values and on a
     sweep around them (the shape of the paper's slicing-rate ablation, Section V-E.2)."""
     M, H, E, k = cfg.d_model, cfg.d_ff, cfg.n_experts, cfg.top_k
-    shared = tuple(w[kk] for kk in ("s_gate", "s_up", "s_down")) if cfg.d_ff_shared else None
+    shared = tuple(w[kk] for kk in ("s_gate", "s_up", "s_down")) if cfg.d_ff_shared and "s_gate" in w else None
     stream = torch.cuda.current_stream().cuda_stream
     wl = Workload(cfg, args.decode_calls)
     R = 1.0 - r_gg
@@ -314,9 +314,15 @@ def solver_study(args, si, torch, cfg, w, r_gg):
     def touched_mean(calls):
         return float(np.mean([Workload.touched(cfg, lg) for _, _, lg in calls]))
 
+    q4 = "q_gate" in w
+
     def layer_times(split, n_g, reps):
-        layer = si.si_layer_create(M, H, E, k, w["w_gate"], w["w_up"], w["w_down"], split[0], split[1], split[2],
-                                   max(cfg.t_prefill, cfg.t_decode), d_ff_shared=cfg.d_ff_shared, shared=shared)
+        if q4:
+            layer = si.si_layer_create_q4(M, H, E, k, w, split[0], split[1], split[2], max(cfg.t_prefill, cfg.t_decode),
+                                          d_ff_shared=cfg.d_ff_shared)
+        else:
+            layer = si.si_layer_create(M, H, E, k, w["w_gate"], w["w_up"], w["w_down"], split[0], split[1], split[2],
+                                       max(cfg.t_prefill, cfg.t_decode), d_ff_shared=cfg.d_ff_shared, shared=shared)
         try:
             info = si.si_layer_split_info(layer)
             dec, pre = [], []
@@ -349,12 +355,12 @@ def solver_study(args, si, torch, cfg, w, r_gg):
         rows_dec = max(1, int(round(cfg.t_decode * k / e_dec)))
     rows_pre = max(1, cfg.t_prefill * k // E)
     t0 = time.perf_counter()
-    prof_dec = si.si_profile(M, H, rows_dec, mode=si.SI_DECODE, n_sizes=6, reps=5)
-    prof_pre = si.si_profile(M, H, rows_pre, mode=si.SI_PREFILL, n_sizes=5, reps=3)
+    prof_dec = si.si_profile(M, H, rows_dec, mode=si.SI_DECODE, n_sizes=6, reps=5, q4=q4)
+    prof_pre = si.si_profile(M, H, rows_pre, mode=si.SI_PREFILL, n_sizes=5, reps=3, q4=q4)
     t_prof = time.perf_counter() - t0
 
     # --- Solver, generation phase: n_l = 3 GEMMs (gate, up, down) per expert that received tokens
-    n_w = 2.0 * M * H
+    n_w = (0.5 + 2.0 / 64 if q4 else 2.0) * M * H   # bytes of one GEMM's weights on the link
     n_l_dec = int(round(3 * e_dec))
     sol = si.si_solve_split(prof_dec["model"], float(rows_dec) * M * H, n_w, n_l_dec, r_gg, r_step=64.0 / H)
     sweep = sorted({round(f * R, 6) for f in (0.0, 0.25, 0.5, 0.75, 1.0)} | {round(sol["r_cg"], 6)})
@@ -388,7 +394,7 @@ def solver_study(args, si, torch, cfg, w, r_gg):
     star = [r for r in rows if r["solved"]][0]
     fixed = [r for r in rows if not r["solved"]]
     out = {
-        "solver_study": cfg.name, "r_gg": r_gg, "profile_seconds": round(t_prof, 1),
+        "solver_study": cfg.name, "weights": "4-bit" if q4 else "bf16", "r_gg": r_gg, "profile_seconds": round(t_prof, 1),
         "model_decode": prof_dec["model"], "r2_decode": [prof_dec["r2_g"], prof_dec["r2_c"], prof_dec["r2_c2g"]],
         "model_prefill": prof_pre["model"], "r2_prefill": [prof_pre["r2_g"], prof_pre["r2_c"], prof_pre["r2_c2g"]],
         "sigma_launch": prof_dec["sigma_launch"], "rows_decode": rows_dec, "rows_prefill": rows_pre,

@@ -137,6 +137,7 @@ typedef struct {
   int32_t device;
   int32_t copy_max_mib; /* largest copy; 0 -> 256 */
   uint32_t seed;        /* of the synthetic weights */
+  int32_t q4;           /* 0: bf16 layers; 1: layers in the 4-bit storage form (Table I has a column pair for each) */
 } si_profile_desc_t;
 
 typedef struct {

@@ -87,7 +87,7 @@ class si_profile_desc_t(ctypes.Structure):
     _fields_ = [("d_model", ctypes.c_int32), ("d_ff", ctypes.c_int32), ("tokens", ctypes.c_int32),
                 ("mode", ctypes.c_int32), ("n_sizes", ctypes.c_int32), ("reps", ctypes.c_int32),
                 ("cc_threads", ctypes.c_int32), ("device", ctypes.c_int32), ("copy_max_mib", ctypes.c_int32),
-                ("seed", ctypes.c_uint32)]
+                ("seed", ctypes.c_uint32), ("q4", ctypes.c_int32)]
 
 
 class si_profile_result_t(ctypes.Structure):
@@ -445,9 +445,9 @@ def si_assign_gpu_memory(t_star, n_m, budget):
     return pick.tolist()
 
 
-def si_profile(d_model, d_ff, tokens, mode=SI_AUTO, n_sizes=0, reps=0, cc_threads=0, device=0, copy_max_mib=0, seed=1) -> dict:
+def si_profile(d_model, d_ff, tokens, mode=SI_AUTO, n_sizes=0, reps=0, cc_threads=0, device=0, copy_max_mib=0, seed=1, q4=False) -> dict:
     """Measure this machine and fit Eq. 3; returns the model, the r^2 values and the raw points."""
-    desc = si_profile_desc_t(d_model, d_ff, tokens, mode, n_sizes, reps, cc_threads, device, copy_max_mib, seed)
+    desc = si_profile_desc_t(d_model, d_ff, tokens, mode, n_sizes, reps, cc_threads, device, copy_max_mib, seed, int(bool(q4)))
     out = si_profile_result_t()
     _check(lib().si_profile(ctypes.byref(desc), ctypes.byref(out)))
     k = out.n_points

@@ -53,7 +53,7 @@ double median(std::vector<double> v) {
 // Median over `reps` forward calls of a dense layer of hidden size h placed entirely on the GPU
 // (gpu = true: seconds in the gate/up and down kernels) or on the host (seconds in the CC workers).
 int time_layer(const si_profile_desc_t& d, int mode, int h, bool gpu, const uint16_t* wg, const uint16_t* wu,
-               const uint16_t* wd, const void* x_dev, float* y_dev, int reps, double* seconds) {
+               const uint16_t* wd, const si_q4_weights_t* q4, const void* x_dev, float* y_dev, int reps, double* seconds) {
   si_layer_desc_t ld;
   std::memset(&ld, 0, sizeof ld);
   ld.d_model = d.d_model;
@@ -67,7 +67,8 @@ int time_layer(const si_profile_desc_t& d, int mode, int h, bool gpu, const uint
   ld.device = d.device;
   ld.stage_mib = 1;
   si_layer_t* L = nullptr;
-  int rc = si_layer_create(&ld, wg, wu, wd, nullptr, nullptr, nullptr, &L);
+  // the first h rows of the [d_ff][..] arrays are a layer of hidden size h in either storage form
+  int rc = q4 ? si_layer_create_q4(&ld, q4, nullptr, nullptr, &L) : si_layer_create(&ld, wg, wu, wd, nullptr, nullptr, nullptr, &L);
   if (rc != SI_OK) return rc;
   std::vector<double> samples;
   rc = si_layer_set_profiling(L, 1);
@@ -119,6 +120,9 @@ extern "C" int si_profile(const si_profile_desc_t* desc, si_profile_result_t* ou
   const size_t wn = (size_t)d.d_ff * d.d_model;
   const size_t copy_max = (size_t)d.copy_max_mib << 20;
   std::vector<uint16_t> wg, wu, wd;
+  std::vector<uint8_t> qg, qu, qd;   // 4-bit form: any byte is a valid pair of codes
+  std::vector<uint16_t> zg, zu, zd;
+  si_q4_weights_t q4w{};
   void* x_dev = nullptr;
   float* y_dev = nullptr;
   void* pin = nullptr;
@@ -129,12 +133,32 @@ extern "C" int si_profile(const si_profile_desc_t* desc, si_profile_result_t* ou
   {
     PROF_HIP(hipSetDevice(d.device));
     const int threads = (int)std::max(1u, std::min(16u, std::thread::hardware_concurrency()));
-    wg.resize(wn);
-    wu.resize(wn);
-    wd.resize(wn);
-    fill_weights(wg.data(), wn, d.seed * 3 + 0, threads);
-    fill_weights(wu.data(), wn, d.seed * 3 + 1, threads);
-    fill_weights(wd.data(), wn, d.seed * 3 + 2, threads);
+    if (!d.q4) {
+      wg.resize(wn);
+      wu.resize(wn);
+      wd.resize(wn);
+      fill_weights(wg.data(), wn, d.seed * 3 + 0, threads);
+      fill_weights(wu.data(), wn, d.seed * 3 + 1, threads);
+      fill_weights(wd.data(), wn, d.seed * 3 + 2, threads);
+    } else {
+      // codes: the bytes of pseudo-random bf16 patterns; scales: small positive bf16 values (sign bit cleared).
+      // z_down is [d_ff/64][d_model]: its first h/64 rows belong to the first h hidden columns.
+      std::vector<uint16_t> tmp(wn / 4);
+      for (auto* q : {&qg, &qu, &qd}) {
+        fill_weights(tmp.data(), tmp.size(), d.seed * 3 + (uint32_t)(q - &qg) + 11, threads);
+        q->resize(wn / 2);
+        std::memcpy(q->data(), tmp.data(), wn / 2);
+      }
+      zg.resize(wn / 64);
+      zu.resize(wn / 64);
+      zd.resize(wn / 64);
+      fill_weights(zg.data(), zg.size(), d.seed * 3 + 21, 1);
+      fill_weights(zu.data(), zu.size(), d.seed * 3 + 22, 1);
+      fill_weights(zd.data(), zd.size(), d.seed * 3 + 23, 1);
+      for (auto* z : {&zg, &zu, &zd})
+        for (auto& v : *z) v &= 0x7fffu;
+      q4w = si_q4_weights_t{qg.data(), qu.data(), qd.data(), zg.data(), zu.data(), zd.data()};
+    }
     std::vector<uint16_t> xh((size_t)d.tokens * d.d_model);
     fill_weights(xh.data(), xh.size(), d.seed * 3 + 7, 1);
     for (auto& v : xh) v = (uint16_t)(v + (4u << 7));  // activations 16 times larger than the weights
@@ -146,10 +170,10 @@ extern "C" int si_profile(const si_profile_desc_t* desc, si_profile_result_t* ou
     for (int i = 0; i < np; ++i) {
       out->n_gemm[i] = (double)d.tokens * d.d_model * hs[i];
       double s = 0.0;
-      rc = time_layer(d, mode, hs[i], true, wg.data(), wu.data(), wd.data(), x_dev, y_dev, d.reps, &s);
+      rc = time_layer(d, mode, hs[i], true, wg.data(), wu.data(), wd.data(), d.q4 ? &q4w : nullptr, x_dev, y_dev, d.reps, &s);
       if (rc != SI_OK) goto done;
       out->t_g[i] = s / 3.0;
-      rc = time_layer(d, mode, hs[i], false, wg.data(), wu.data(), wd.data(), x_dev, y_dev, d.reps, &s);
+      rc = time_layer(d, mode, hs[i], false, wg.data(), wu.data(), wd.data(), d.q4 ? &q4w : nullptr, x_dev, y_dev, d.reps, &s);
       if (rc != SI_OK) goto done;
       out->t_c[i] = s / 3.0;
     }
