@@ -357,6 +357,18 @@ def solver_study(args, si, torch, cfg, w, r_gg):
     t0 = time.perf_counter()
     prof_dec = si.si_profile(M, H, rows_dec, mode=si.SI_DECODE, n_sizes=6, reps=5, q4=q4)
     prof_pre = si.si_profile(M, H, rows_pre, mode=si.SI_PREFILL, n_sizes=5, reps=3, q4=q4)
+    # The token assignment moves along the token axis at full hidden size, so the prompt-phase GEMM models are
+    # fitted along that axis: full-size GEMMs at several row counts (the start-up term then carries the cost of
+    # streaming the weights once, which a fit over the hidden size at a fixed row count cannot see).
+    rows_axis = sorted({r for r in (8, 64, 256, rows_pre) if r <= rows_pre})
+    pts = [si.si_profile(M, H, r, mode=si.SI_PREFILL, n_sizes=2, reps=2, q4=q4) for r in rows_axis]
+    n_ax = [p["n_gemm"][-1] for p in pts]
+    model_pre = dict(prof_pre["model"])
+    if len(rows_axis) >= 2:
+        a, b, r2_gt = si.si_fit_linear(n_ax, [p["t_g"][-1] for p in pts], nonneg=True)
+        model_pre["alpha_g"], model_pre["beta_g"] = a, b
+        a, b, r2_ct = si.si_fit_linear(n_ax, [p["t_c"][-1] for p in pts], nonneg=True)
+        model_pre["alpha_c"], model_pre["beta_c"] = a, b
     t_prof = time.perf_counter() - t0
 
     # --- Solver, generation phase: n_l = 3 GEMMs (gate, up, down) per expert that received tokens
@@ -376,7 +388,7 @@ def solver_study(args, si, torch, cfg, w, r_gg):
         sol_ng = None
         if is_star:
             # --- Solver, prompt phase, rates fixed at the generation-phase optimum
-            sol_ng = si.si_solve_ng(prof_pre["model"], rows_pre, M, H, n_w, n_l_pre, split[0], split[1])
+            sol_ng = si.si_solve_ng(model_pre, rows_pre, M, H, n_w, n_l_pre, split[0], split[1])
             # the model counts rows of one expert's GEMM; the layer takes n_g in tokens
             ng_tokens = int(round(sol_ng["n_g"] * T / rows_pre))
             ngs = sorted({0, T // 4, T // 2, 3 * T // 4, T, min(T, ng_tokens)})
@@ -396,7 +408,8 @@ def solver_study(args, si, torch, cfg, w, r_gg):
     out = {
         "solver_study": cfg.name, "weights": "4-bit" if q4 else "bf16", "r_gg": r_gg, "profile_seconds": round(t_prof, 1),
         "model_decode": prof_dec["model"], "r2_decode": [prof_dec["r2_g"], prof_dec["r2_c"], prof_dec["r2_c2g"]],
-        "model_prefill": prof_pre["model"], "r2_prefill": [prof_pre["r2_g"], prof_pre["r2_c"], prof_pre["r2_c2g"]],
+        "model_prefill": model_pre, "model_prefill_rows_fitted": rows_axis,
+        "r2_prefill": [prof_pre["r2_g"], prof_pre["r2_c"], prof_pre["r2_c2g"]],
         "sigma_launch": prof_dec["sigma_launch"], "rows_decode": rows_dec, "rows_prefill": rows_pre,
         "n_l_decode": n_l_dec, "n_l_prefill": n_l_pre,
         "r_cg_solved": sol["r_cg"], "case": sol["case"], "t_fin_model_ms": round(1e3 * sol["t_fin"], 4),
