@@ -186,6 +186,17 @@ typedef struct {
 int si_layer_create_q4(const si_layer_desc_t* desc, const si_q4_weights_t* routed, const si_q4_weights_t* shared,
                        const uint8_t* placement, si_layer_t** out);
 
+/*
+ * Change the slicing rates of an existing layer (e.g. to the r_CG* that si_solve_split returned for measurements
+ * taken on this very layer).  The library holds every chunk exactly once, either resident or in pinned memory, in
+ * a form that does not depend on the rates; re-slicing moves the chunks whose place changes across the host link
+ * and reallocates the two buffers (both old and new exist during the call).  Synchronises the device; not meant
+ * for the hot path (Section III-B: the paper slices once and keeps the rates of the generation phase).
+ * Errors: SI_EINVAL (rates), SI_ESTATE (layer created with whole-expert placement), SI_ENOMEM, SI_EHIP; on
+ * SI_ENOMEM / SI_EHIP the layer keeps working with the rates si_layer_split_info reports.
+ */
+int si_layer_resplit(si_layer_t* layer, float r_gg, float r_cg, float r_cc);
+
 /* Hidden-column counts actually used (routed expert n_*, shared expert s_*; any pointer may be
  * NULL).  Tests read the counts from here instead of re-deriving the rounding. */
 int si_layer_split_info(const si_layer_t* layer, int32_t* n_gg, int32_t* n_cg, int32_t* n_cc,

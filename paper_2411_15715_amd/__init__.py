@@ -20,7 +20,7 @@ SI_DECODE_AUTO_T, SI_DECODE_AUTO_ROWS, SI_DECODE_MAX_T = 8, 4, 16
 EXPORTS = ["si_layer_create", "si_layer_split_info", "si_split_counts", "si_layer_forward", "si_route",
            "si_layer_stats", "si_layer_set_profiling", "si_repack_chunks", "si_cc_compute", "si_layer_destroy", "si_last_error", "si_version",
            "si_stack_create", "si_stack_forward", "si_stack_destroy",
-           "si_layer_create_q4", "si_repack_chunks_q4", "si_cc_compute_q4", "si_layer_create_placed", "si_place_experts",
+           "si_layer_create_q4", "si_repack_chunks_q4", "si_cc_compute_q4", "si_layer_create_placed", "si_place_experts", "si_layer_resplit",
            # scheinfer_solver.h
            "si_fit_linear", "si_model_times", "si_simulate", "si_solve_split", "si_model_times_ng", "si_solve_ng",
            "si_assign_gpu_memory", "si_profile", "si_measure_peaks"]
@@ -143,6 +143,8 @@ def lib():
         L.si_layer_create_q4.argtypes = [ctypes.POINTER(si_layer_desc_t), pq, pq, vp, ctypes.POINTER(vp)]
         L.si_layer_create_placed.restype = ctypes.c_int
         L.si_layer_create_placed.argtypes = [ctypes.POINTER(si_layer_desc_t), vp, vp, vp, vp, vp, vp, vp, ctypes.POINTER(vp)]
+        L.si_layer_resplit.restype = ctypes.c_int
+        L.si_layer_resplit.argtypes = [vp, f32, f32, f32]
         L.si_place_experts.restype = ctypes.c_int
         L.si_place_experts.argtypes = [vp, i32, i32, ctypes.c_double, vp]
         L.si_repack_chunks_q4.restype = ctypes.c_int
@@ -275,6 +277,11 @@ def si_layer_create_q4(d_model, d_ff, n_experts, top_k, wq, r_gg, r_cg, r_cc, ma
     keep3, pp = _placement_ptr(placement, n_experts)
     _check(lib().si_layer_create_q4(ctypes.byref(desc), ctypes.byref(routed), shared, pp, ctypes.byref(out)))
     return out.value
+
+
+def si_layer_resplit(layer, r_gg, r_cg, r_cc):
+    """Change the slicing rates of an existing layer (moves chunks between GPU and pinned host memory)."""
+    _check(lib().si_layer_resplit(layer, r_gg, r_cg, r_cc))
 
 
 def si_layer_split_info(layer):

@@ -396,6 +396,37 @@ void si_layer_destroy(si_layer_t* L) {
 
 namespace {
 
+// Staging ring (Stream-C) and host workers, sized independently of the slicing rates so that a layer can be
+// re-sliced without touching them: a decode piece must hold whole down-projection slots of the largest part an
+// expert could have (all of its chunks).
+int setup_staging(si_layer* L) {
+  if (L->d_stage.empty()) {
+    const size_t stage_bytes = (size_t)(L->desc.stage_mib == 0 ? 256 : L->desc.stage_mib) << 20;
+    const int sc = (int)std::max<size_t>(1, stage_bytes / (L->ce * 2));
+    const int cps_max = std::max({ceil_div(L->H / CHUNK_J, DOWN_SLOTS), ceil_div(L->Hs / CHUNK_J, DOWN_SLOTS), 8});
+    L->stage_chunks = std::max(sc, cps_max);
+    L->d_stage.assign(L->n_stage, nullptr);
+    L->ev_ready.assign(L->n_stage, nullptr);
+    L->ev_free.assign(L->n_stage, nullptr);
+    L->slot_used.assign(L->n_stage, 0);
+    for (int i = 0; i < L->n_stage; ++i) {
+      int rc = dev_alloc(&L->d_stage[i], (size_t)L->stage_chunks * L->ce);
+      if (rc) return rc;
+      HIP_TRY(hipEventCreateWithFlags(&L->ev_ready[i], hipEventDisableTiming));
+      HIP_TRY(hipEventCreateWithFlags(&L->ev_free[i], hipEventDisableTiming));
+    }
+  }
+  return SI_OK;
+}
+
+int setup_pool(si_layer* L) {
+  if (!L->pool && L->ch_cc + L->sch_cc > 0) {
+    const int hw_threads = (int)std::max(1u, std::thread::hardware_concurrency());
+    L->pool = cc_pool_create(L->desc.cc_threads == 0 ? std::min(16, hw_threads) : L->desc.cc_threads);
+  }
+  return SI_OK;
+}
+
 int create_impl(const si_layer_desc_t* desc, const WeightSource& src, const uint8_t* placement, si_layer_t** out) {
   int g = 64;
   if (!out) return fail(SI_EINVAL, "out is NULL");
@@ -508,22 +539,7 @@ int create_impl(const si_layer_desc_t* desc, const WeightSource& src, const uint
   // ---- staging ring for CG / CG' copies (Stream-C)
   L->n_stage = desc->n_stage == 0 ? 2 : desc->n_stage;
   const bool any_host = hch + shch > 0;
-  if (any_host) {
-    size_t stage_bytes = (size_t)(desc->stage_mib == 0 ? 256 : desc->stage_mib) << 20;
-    int sc = (int)std::max<size_t>(1, stage_bytes / (ce * 2));
-    // a decode piece must hold whole down-projection slots
-    int cps_max = std::max({ceil_div(L->ch_cg, DOWN_SLOTS), ceil_div(L->ch_cc, DOWN_SLOTS), ceil_div(L->sch_cg, DOWN_SLOTS), ceil_div(L->sch_cc, DOWN_SLOTS), 8});
-    L->stage_chunks = std::max(sc, cps_max);
-    L->d_stage.assign(L->n_stage, nullptr);
-    L->ev_ready.assign(L->n_stage, nullptr);
-    L->ev_free.assign(L->n_stage, nullptr);
-    L->slot_used.assign(L->n_stage, 0);
-    for (int i = 0; i < L->n_stage; ++i) {
-      TRY_OR_DESTROY(dev_alloc(&L->d_stage[i], (size_t)L->stage_chunks * ce));
-      HIP_OR_DESTROY(hipEventCreateWithFlags(&L->ev_ready[i], hipEventDisableTiming));
-      HIP_OR_DESTROY(hipEventCreateWithFlags(&L->ev_free[i], hipEventDisableTiming));
-    }
-  }
+  if (any_host) TRY_OR_DESTROY(setup_staging(L));
   HIP_OR_DESTROY(hipStreamCreateWithFlags(&L->copy_stream, hipStreamNonBlocking));
   L->own_copy_stream = L->copy_stream;
   HIP_OR_DESTROY(hipEventCreateWithFlags(&L->ev_host, hipEventDisableTiming));
@@ -554,8 +570,8 @@ int create_impl(const si_layer_desc_t* desc, const WeightSource& src, const uint
   TRY_OR_DESTROY(dev_alloc(&L->d_h, (size_t)L->rows_dec * L->ldh_dec));
   TRY_OR_DESTROY(dev_alloc(&L->d_part, (size_t)3 * DOWN_SLOTS * L->rows_dec * M));
   {
-    // widest launch of the prefill path: the GG part, or one staged piece
-    int cols = std::max({L->n_gg, L->s_gg, any_host ? L->stage_chunks * CHUNK_J : 0});
+    // widest launch whatever the slicing rates: a part never has more columns than its expert
+    int cols = std::max(L->H, L->Hs);
     if (L->q4) {
       // bf16 scratch for the prompt-phase GEMMs (default 2 GiB: the fewer sub-pieces, the fewer short launches;
       // measured 1.88 / 1.59 / 1.47 ms per Mixtral-shaped prompt call with 0.5 / 2 / 4 GiB), at least one chunk per
@@ -563,7 +579,7 @@ int create_impl(const si_layer_desc_t* desc, const WeightSource& src, const uint
       const size_t cb16 = chunk_elems(M) * 2;
       const size_t deq_mib = desc->deq_mib == 0 ? 2048 : (size_t)desc->deq_mib;
       L->deq_chunks = (int)std::max<size_t>((size_t)E, (deq_mib << 20) / cb16);
-      L->deq_chunks = std::min(L->deq_chunks, std::max(E, E * std::max({L->ch_gg, L->ch_cg, L->ch_cc, L->sch_gg, L->sch_cg, L->sch_cc, 1})));
+      L->deq_chunks = std::min(L->deq_chunks, std::max(E, E * std::max({L->H / CHUNK_J, L->Hs / CHUNK_J, 1})));
       TRY_OR_DESTROY(dev_alloc(&L->d_deq, (size_t)L->deq_chunks * chunk_elems(M)));
       cols = L->deq_chunks * CHUNK_J;
     }
@@ -578,10 +594,7 @@ int create_impl(const si_layer_desc_t* desc, const WeightSource& src, const uint
   TRY_OR_DESTROY(pin_alloc(&L->hw, n_pairs));
   TRY_OR_DESTROY(pin_alloc(&L->hcount, (size_t)2 * L->EX));
   TRY_OR_DESTROY(pin_alloc(&L->hycc, (size_t)T * M));
-  if (L->ch_cc + L->sch_cc > 0) {
-    int nt = desc->cc_threads == 0 ? std::min(16, hw_threads) : desc->cc_threads;
-    L->pool = cc_pool_create(nt);
-  }
+  TRY_OR_DESTROY(setup_pool(L));
   HIP_OR_DESTROY(hipDeviceSynchronize());
   *out = L;
   return SI_OK;
@@ -621,6 +634,82 @@ int si_layer_create_q4(const si_layer_desc_t* desc, const si_q4_weights_t* route
     src.szg = shared->z_gate; src.szu = shared->z_up; src.szd = shared->z_down;
   }
   return create_impl(desc, src, placement, out);
+}
+
+int si_layer_resplit(si_layer_t* L, float r_gg, float r_cg, float r_cc) {
+  if (!L) return fail(SI_EINVAL, "layer is NULL");
+  if (L->placed) return fail(SI_ESTATE, "a layer with whole-expert placement has no slicing rates to change");
+  si_layer_desc_t d = L->desc;
+  d.r_gg = r_gg; d.r_cg = r_cg; d.r_cc = r_cc;
+  int g = 64;
+  if (int rc = validate_desc(&d, &g)) return rc;
+  HIP_TRY(hipSetDevice(L->device));
+  int n_gg, n_cg, n_cc, s_gg = 0, s_cg = 0, s_cc = 0;
+  split_counts(L->H, g, r_gg, r_cg, &n_gg, &n_cg, &n_cc);
+  if (L->has_shared) split_counts(L->Hs, g, r_gg, r_cg, &s_gg, &s_cg, &s_cc);
+  // nothing may be in flight on the old buffers
+  HIP_TRY(hipStreamSynchronize(L->copy_stream));
+  HIP_TRY(hipDeviceSynchronize());
+  const size_t ce = L->ce;
+
+  // Move the chunks of one expert set (n_exp experts of `total` chunks each) from the old boundary between host
+  // and device (host_old chunks on the host, the rest resident) to the new one.  Chunk c of expert e sits at
+  // host[e*host_n + c] for c < host_n, else at dev[e*(total - host_n) + c - host_n].
+  auto move = [&](int n_exp, int total, int host_old, int host_new, uint16_t** host, uint16_t** dev) -> int {
+    if (host_old == host_new) return SI_OK;
+    uint16_t *nh = nullptr, *nd = nullptr;
+    int rc = pin_alloc(&nh, (size_t)n_exp * host_new * ce);
+    if (rc == SI_OK) rc = dev_alloc(&nd, (size_t)n_exp * (total - host_new) * ce);
+    const int keep_h = std::min(host_old, host_new), keep_d0 = std::max(host_old, host_new);
+    const int gg_old = total - host_old, gg_new = total - host_new;
+    for (int e = 0; e < n_exp && rc == SI_OK; ++e) {
+      hipError_t he = hipSuccess;
+      if (keep_h > 0) std::memcpy(nh + (size_t)e * host_new * ce, *host + (size_t)e * host_old * ce, (size_t)keep_h * ce * 2);
+      if (host_new > host_old)  // chunks [host_old, host_new) leave the GPU
+        he = hipMemcpy(nh + ((size_t)e * host_new + host_old) * ce, *dev + (size_t)e * gg_old * ce,
+                       (size_t)(host_new - host_old) * ce * 2, hipMemcpyDeviceToHost);
+      else                      // chunks [host_new, host_old) become resident
+        he = hipMemcpy(nd + (size_t)e * gg_new * ce, *host + ((size_t)e * host_old + host_new) * ce,
+                       (size_t)(host_old - host_new) * ce * 2, hipMemcpyHostToDevice);
+      if (he == hipSuccess && total > keep_d0)  // chunks [keep_d0, total) stay resident
+        he = hipMemcpy(nd + ((size_t)e * gg_new + (keep_d0 - host_new)) * ce, *dev + ((size_t)e * gg_old + (keep_d0 - host_old)) * ce,
+                       (size_t)(total - keep_d0) * ce * 2, hipMemcpyDeviceToDevice);
+      if (he != hipSuccess) rc = fail(SI_EHIP, "copy while re-slicing failed: %s", hipGetErrorString(he));
+    }
+    if (rc != SI_OK) {
+      if (nh) (void)hipHostFree(nh);
+      if (nd) (void)hipFree(nd);
+      return rc;
+    }
+    if (*host) (void)hipHostFree(*host);
+    if (*dev) (void)hipFree(*dev);
+    *host = nh;
+    *dev = nd;
+    return SI_OK;
+  };
+  const int Hch = L->H / CHUNK_J, sHch = L->Hs / CHUNK_J;
+  // Routed experts first, then the shared expert; each set either moves completely or keeps its old buffers, and
+  // the counts of a set change with its buffers, so the layer stays usable if the second move runs out of memory.
+  int rc = move(L->E, Hch, L->ch_cc + L->ch_cg, (n_cc + n_cg) / CHUNK_J, &L->h_routed, &L->d_gg);
+  if (rc == SI_OK) {
+    L->n_gg = n_gg; L->n_cg = n_cg; L->n_cc = n_cc;
+    L->ch_gg = n_gg / CHUNK_J; L->ch_cg = n_cg / CHUNK_J; L->ch_cc = n_cc / CHUNK_J;
+    for (int e = 0; e < L->E; ++e) { L->h_off[e] = (uint64_t)e * (L->ch_cc + L->ch_cg) * ce; L->e_cc[e] = L->ch_cc; }
+    if (L->has_shared) rc = move(1, sHch, L->sch_cc + L->sch_cg, (s_cc + s_cg) / CHUNK_J, &L->h_shared, &L->d_sgg);
+    if (rc == SI_OK) {
+      L->s_gg = s_gg; L->s_cg = s_cg; L->s_cc = s_cc;
+      L->sch_gg = s_gg / CHUNK_J; L->sch_cg = s_cg / CHUNK_J; L->sch_cc = s_cc / CHUNK_J;
+      L->desc.r_gg = r_gg; L->desc.r_cg = r_cg; L->desc.r_cc = r_cc;
+    }
+  }
+  L->pre_n = 0;
+  L->pre_slot.clear();
+  if (L->ch_cc + L->ch_cg + L->sch_cc + L->sch_cg > 0) {
+    const int rc2 = setup_staging(L);
+    if (rc2) return rc2;
+  }
+  const int rc3 = setup_pool(L);
+  return rc ? rc : rc3;
 }
 
 int si_layer_split_info(const si_layer_t* L, int32_t* n_gg, int32_t* n_cg, int32_t* n_cc, int32_t* s_gg, int32_t* s_cg, int32_t* s_cc) {
