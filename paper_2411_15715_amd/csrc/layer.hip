@@ -744,7 +744,7 @@ int si_route(const float* logits_dev, int32_t T, int32_t E, int32_t k, const si_
   }
   p.idx = out->idx ? out->idx : tmp;
   p.w = out->w ? out->w : reinterpret_cast<float*>(tmp + n);
-  hipError_t e = launch_route(logits_dev, T, E, k, 0, 0, PREFILL_BM_MAX, p, u, s);
+  hipError_t e = launch_route(logits_dev, T, E, k, 0, 0, p, u, s);
   if (tmp) (void)hipFreeAsync(tmp, s);
   if (e != hipSuccess) return fail(SI_EHIP, "route launch failed: %s", hipGetErrorString(e));
   return SI_OK;
@@ -820,9 +820,6 @@ int si_layer_forward(si_layer_t* L, const void* x_dev, const float* logits_dev, 
   const bool need_sync = need_cc || need_counts;
   const auto wall0 = std::chrono::steady_clock::now();
 
-  // rows per GEMM tile: 256 when experts have many rows (MFMA bound), smaller when the GEMM only streams weights
-  auto pick_bm = [](int rows) { return rows >= 192 ? 256 : (rows >= 96 ? 128 : 64); };
-  const int bm_call = pick_bm(ceil_div(T * k, E));
   if (!L->segs_preloaded) { L->ev_used = 0; L->segs.clear(); }
   L->segs_preloaded = false;
   L->in_staged = 0;
@@ -837,7 +834,7 @@ int si_layer_forward(si_layer_t* L, const void* x_dev, const float* logits_dev, 
   if (rout) u = RouteOut{rout->idx, rout->w, rout->count, rout->off, rout->perm, rout->inv};
   {
     SegScope sc(L, stream, 0);
-    hipError_t e = launch_route(E > 1 ? logits_dev : nullptr, T, E, k, L->has_shared, n_g, bm_call, L->plan, u, stream);
+    hipError_t e = launch_route(E > 1 ? logits_dev : nullptr, T, E, k, L->has_shared, n_g, L->plan, u, stream);
     if (e != hipSuccess) return fail(SI_EHIP, "route launch failed: %s", hipGetErrorString(e));
   }
   // ---- hand-off to the host: X1 and the assignment (Section III-B: "X1 will be additionally
@@ -881,7 +878,7 @@ int si_layer_forward(si_layer_t* L, const void* x_dev, const float* logits_dev, 
   auto rows_all = [&](int e) { return need_sync ? L->hcount[e] : T; };
   auto rows_x2 = [&](int e) { return need_sync ? L->hcount[e] - L->hcount[EX + e] : n_g; };
   const int max_touched = std::min(EX, T * k + L->has_shared);
-  const int tiles_upper = (T * k) / bm_call + E;  // bound on the routed row tiles
+  const int tiles_upper = (T * k) / TILE_ROWS + std::min(E, T * k);  // bound on the routed row tiles
   // (whole-expert placement: every routed expert has H/64 chunks wherever it lives)
   const int cps_gg = cps_of(L->placed ? L->H / CHUNK_J : L->ch_gg), cps_cg = cps_of(L->placed ? L->H / CHUNK_J : L->ch_cg),
             cps_cc = cps_of(L->placed ? L->H / CHUNK_J : L->ch_cc);
@@ -889,7 +886,8 @@ int si_layer_forward(si_layer_t* L, const void* x_dev, const float* logits_dev, 
   const size_t slot_stride = (size_t)L->rows_dec * M;
   // k-splits of the prefill down projection: enough blocks to fill 256 CUs when there are few row tiles
   const int n_ntiles = ceil_div(M, 256);
-  const int split_call = std::min(MAX_KSPLIT, std::max(1, 256 / (std::max(1, ceil_div(T * k, bm_call)) * n_ntiles)));
+  const int rt_guess = std::max(ceil_div(T * k, TILE_ROWS), std::min(E, T * k));  // row tiles if the rows spread evenly
+  const int split_call = std::min(MAX_KSPLIT, std::max(1, 256 / (std::max(1, rt_guess) * n_ntiles)));
   hipError_t ke = hipSuccess;
 #define K_TRY(expr) do { ke = (expr); if (ke != hipSuccess) return fail(SI_EHIP, "%s failed: %s", #expr, hipGetErrorString(ke)); } while (0)
 
@@ -919,15 +917,7 @@ int si_layer_forward(si_layer_t* L, const void* x_dev, const float* logits_dev, 
       K_TRY(launch_decode_down(L->d_h, L->ldh_dec, M, L->plan, T, esel, x2_only, max_touched, wv,
                                part * DOWN_SLOTS + part_chunk0 / cps, cps, L->d_part, slot_stride, stream));
     } else {
-      int n_rt, bm;
-      if (esel >= 0) {
-        const int rows = x2_only ? rows_x2(esel) : rows_all(esel);
-        bm = pick_bm(rows);
-        n_rt = ceil_div(rows, bm);
-      } else {
-        bm = bm_call;
-        n_rt = tiles_upper;
-      }
+      const int n_rt = esel >= 0 ? n_row_tiles(x2_only ? rows_x2(esel) : rows_all(esel)) : tiles_upper;
       // bf16 layers: one pass over the chunk range.  4-bit layers: the range goes through the bf16 scratch in
       // sub-pieces (dequantise, FC1, FC2 accumulating), as many chunks per expert as the scratch holds.
       const int cap = !L->q4 ? n : std::max(1, esel >= 0 ? L->deq_chunks : L->deq_chunks / E);
@@ -947,11 +937,11 @@ int si_layer_forward(si_layer_t* L, const void* x_dev, const float* logits_dev, 
         const int ldh = ns * CHUNK_J;
         {
           SegScope sc(L, stream, SI_K_PREFILL_GATEUP);
-          K_TRY(launch_prefill_gateup(x, M, L->plan, bm, esel, x2_only, n_rt, wg, L->d_hact, ldh, stream));
+          K_TRY(launch_prefill_gateup(x, M, L->plan, esel, x2_only, n_rt, wg, L->d_hact, ldh, stream));
         }
         SegScope sc(L, stream, SI_K_PREFILL_DOWN);
         const int split = first ? split_call : std::min(split_call, std::max(1, ns / 8));
-        K_TRY(launch_prefill_down(L->d_hact, ldh, M, L->plan, bm, esel, x2_only, n_rt, wg, L->d_yp, L->yp_slab, split,
+        K_TRY(launch_prefill_down(L->d_hact, ldh, M, L->plan, esel, x2_only, n_rt, wg, L->d_yp, L->yp_slab, split,
                                   first ? 0 : 1, stream));
       }
     }

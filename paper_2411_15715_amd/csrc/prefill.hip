@@ -5,9 +5,10 @@
 // Rows are the expert-sorted (token, slot) pairs of the token assignment; a row tile never
 // crosses an expert.  The gather of x rows is fused into the A-operand load of the first GEMM.
 //
-// Both GEMMs: one 512-thread block (8 waves, 2 per SIMD) per BM x 256 output tile (BM = 256, 128 or
-// 64 rows), BK = 64, a ring of LDS stages filled by direct global->LDS loads (global_load_lds_dwordx4,
-// no VGPR staging), wave tile (BM/2) x 64.
+// Both GEMMs: one 512-thread block (8 waves, 2 per SIMD) per BM x 256 output tile, BK = 64, a ring of LDS
+// stages filled by direct global->LDS loads (global_load_lds_dwordx4, no VGPR staging), wave tile
+// (BM/2) x 64.  A row tile holds up to 256 rows (si_internal.h: n_row_tiles); the block runs the body
+// instantiated for BM = 64, 128, 192 or 256, the smallest that covers the rows the tile really has.
 // LDS rows hold 64 contraction elements (128 bytes); the 16-byte piece c of row r sits at piece
 // c ^ ((r >> 1) & 7): gfx950's LDS has 64 banks, so 16 consecutive rows x 16 bytes must cover 256
 // distinct bytes of bank space for the 128-bit MFMA operand reads to be conflict free (measured:
@@ -28,14 +29,14 @@ constexpr int THREADS = 512;
 constexpr int BN = 256;  // B rows per tile: 128 hidden columns (gate+up) or 256 output columns
 constexpr int BK = 64;
 constexpr int B_BYTES = BN * BK * 2;  // 32 KB
+constexpr int KERNEL_LDS = 144 * 1024;  // the largest body
 
-// Tile shapes.  BM rows per tile: 256 for the MFMA-bound regime (many rows per expert), 128 / 64 when an
-// expert has few rows and the GEMM is bound by streaming its weights: smaller A tiles leave LDS for a
+// Body shapes.  With few rows the GEMM only streams its weights: the smaller A tiles then leave LDS for a
 // deeper ring of stages, i.e. more weight bytes in flight per CU.
 template <int BM> struct Shape {
-  static constexpr int NST = BM == 256 ? 2 : 3;          // LDS stages
+  static constexpr int NST = BM >= 192 ? 2 : 3;           // LDS stages
   static constexpr int STAGE = BM * 128 + B_BYTES;        // bytes per stage
-  static constexpr int LDS = NST * STAGE;                 // 128 KB, 144 KB, 120 KB
+  static constexpr int LDS = NST * STAGE;                 // 120, 144, 112, 128 KB for BM = 64, 128, 192, 256
   static constexpr int FA = BM / 64;                      // A fragments (32 rows each) per wave
   static constexpr int ALD = BM / 64;                     // A load instructions per wave per stage
   static constexpr int LPW = ALD + 4;                     // load instructions per wave per stage
@@ -78,12 +79,11 @@ __device__ inline void block_barrier() {
 //    ranges are cut from the number of ids that really have work (known on the device only), so that no
 //    XCD is handed a range of empty ids (with ranges cut from the grid's upper bound the remap cost more than
 //    it saved on small tiles: the last XCD idled while the others carried its share).
-//  * Tail split (256-row launches): N tiles on n_cu compute units run in ceil(N / n_cu) rounds; when the
-//    last round is at most half full its tiles are cut into two 128-row halves, each a block of its own,
-//    so that the round costs about half a round (LLaMA-shaped gate/up GEMM: 896 tiles = 3.5 rounds).
-template <int BM>
+//  * Tail split: N tiles on n_cu compute units run in ceil(N / n_cu) rounds; when the last round is at most
+//    half full each of its tiles gets two blocks, which share its rows if it has more than 128 (LLaMA-shaped
+//    gate/up GEMM: 896 tiles = 3.5 rounds; the last round then costs about half a round).
 __device__ inline bool map_block(int b, int N, int n_cu, int& L, int& half, int& halves) {
-  int r = BM == 256 ? N % n_cu : 0;
+  int r = N % n_cu;
   if (2 * r > n_cu) r = 0;
   const int main_n = N - r;
   const int per = (main_n + 7) / 8;
@@ -103,19 +103,17 @@ __device__ inline bool map_block(int b, int N, int n_cu, int& L, int& half, int&
 
 struct TileInfo { int e, row0, row_end, se; };  // se: index of the expert inside the launch's weight storage
 
-// Number of logical tile ids with work in this launch (row tiles of BM rows x inner tiles).
-template <int BM>
+// Number of logical tile ids with work in this launch (row tiles x inner tiles).
 __device__ inline int launch_extent(const Plan& p, int expert_sel, int x2_only, int n_inner) {
   if (expert_sel >= 0) {
     const int start = p.off[expert_sel] + (x2_only ? p.count1[expert_sel] : 0);
-    return (p.off[expert_sel + 1] - start + BM - 1) / BM * n_inner;
+    return n_row_tiles(p.off[expert_sel + 1] - start) * n_inner;
   }
   return (x2_only ? *p.n_tiles_x2 : *p.n_tiles) * n_inner;  // row tiles of the routed experts
 }
 
 // logical id L -> (expert, inner index, row tile) with the row tile varying fastest inside an
-// expert: L / n_inner indexes the row-tile table (built for the same BM), which yields the expert.
-template <int BM>
+// expert: L / n_inner indexes the row-tile table, which yields the expert.
 __device__ inline bool decode_tile(const Plan& p, int expert_sel, int x2_only, int L, int n_inner, int& inner,
                                    TileInfo& ti) {
   int e, first, nrt, start, end;
@@ -123,7 +121,7 @@ __device__ inline bool decode_tile(const Plan& p, int expert_sel, int x2_only, i
     e = expert_sel;
     start = p.off[e] + (x2_only ? p.count1[e] : 0);
     end = p.off[e + 1];
-    nrt = (end - start + BM - 1) / BM;
+    nrt = n_row_tiles(end - start);
     if (L >= nrt * n_inner) return false;
     first = 0;
   } else {
@@ -135,28 +133,29 @@ __device__ inline bool decode_tile(const Plan& p, int expert_sel, int x2_only, i
     first = t - (x2_only ? p.tile_r_x2[t] : p.tile_r[t]);
     start = p.off[e] + (x2_only ? p.count1[e] : 0);
     end = p.off[e + 1];
-    nrt = (end - start + BM - 1) / BM;
+    nrt = n_row_tiles(end - start);
   }
   const int Le = L - first * n_inner;
   inner = Le / nrt;
   const int r = Le % nrt;
   ti.e = e;
-  ti.row0 = start + r * BM;
-  ti.row_end = end;
+  ti.row0 = start + r * TILE_ROWS;
+  ti.row_end = r == nrt - 1 ? end : ti.row0 + TILE_ROWS;
   return true;
 }
 
 // block id -> tile of this block (false: nothing to do)
-template <int BM>
 __device__ inline bool block_tile(const Plan& p, int expert_sel, int x2_only, int n_inner, int n_cu, int& inner,
                                   TileInfo& ti) {
   int L, half, halves;
-  if (!map_block<BM>(blockIdx.x, launch_extent<BM>(p, expert_sel, x2_only, n_inner), n_cu, L, half, halves))
-    return false;
-  if (!decode_tile<BM>(p, expert_sel, x2_only, L, n_inner, inner, ti)) return false;
+  if (!map_block(blockIdx.x, launch_extent(p, expert_sel, x2_only, n_inner), n_cu, L, half, halves)) return false;
+  if (!decode_tile(p, expert_sel, x2_only, L, n_inner, inner, ti)) return false;
   if (halves == 2) {
-    ti.row0 += half * (BM / 2);
-    ti.row_end = min(ti.row_end, ti.row0 + BM / 2);
+    const int rows = ti.row_end - ti.row0;
+    if (rows <= 128) return half == 0;  // too few rows to share: the first block takes them all
+    const int hs = ((rows + 1) / 2 + 31) / 32 * 32;
+    ti.row0 += half * hs;
+    ti.row_end = min(ti.row_end, ti.row0 + hs);
     if (ti.row0 >= ti.row_end) return false;
   }
   return true;
@@ -282,10 +281,14 @@ __device__ __forceinline__ void gateup_body(const uint16_t* __restrict__ x, int 
   }
 }
 
-// Row tiles are laid out with 256 rows when experts have many rows; the last tile of an expert then
-// usually holds fewer: a block picks the body for the rows it really has (whole-block branch), so a
-// 40-row tail costs a 64-row tile, not a 256-row one.
-template <int BM>
+// A block picks the body for the rows its tile really has (whole-block branch), so a 40-row tile costs a 64-row
+// body and a 140-row tile a 192-row one.
+#define SI_PICK_BODY(rows, CALL)                 \
+  if ((rows) <= 64) CALL(64);                    \
+  else if ((rows) <= 128) CALL(128);             \
+  else if ((rows) <= 192) CALL(192);             \
+  else CALL(256)
+
 __global__ __launch_bounds__(THREADS, 1) void k_prefill_gateup(const uint16_t* __restrict__ x, int M, Plan p,
                                                                int expert_sel, int x2_only, int n_cu,
                                                                int n_ctiles, WeightView wv,
@@ -293,16 +296,11 @@ __global__ __launch_bounds__(THREADS, 1) void k_prefill_gateup(const uint16_t* _
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
   int tc;
   TileInfo ti;
-  if (!block_tile<BM>(p, expert_sel, x2_only, n_ctiles, n_cu, tc, ti)) return;
+  if (!block_tile(p, expert_sel, x2_only, n_ctiles, n_cu, tc, ti)) return;
   if (!storage_index(wv, ti.e, ti.se)) return;
-  if (BM == 256) {
-    const int rows = ti.row_end - ti.row0;
-    if (rows <= 64) gateup_body<64>(x, M, p, tc, ti, wv, hact, ldh, lds);
-    else if (rows <= 128) gateup_body<128>(x, M, p, tc, ti, wv, hact, ldh, lds);
-    else gateup_body<256>(x, M, p, tc, ti, wv, hact, ldh, lds);
-  } else {
-    gateup_body<BM>(x, M, p, tc, ti, wv, hact, ldh, lds);
-  }
+#define SI_CALL_GU(BMV) gateup_body<BMV>(x, M, p, tc, ti, wv, hact, ldh, lds)
+  SI_PICK_BODY(ti.row_end - ti.row0, SI_CALL_GU);
+#undef SI_CALL_GU
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -381,7 +379,6 @@ __device__ __forceinline__ void down_body(const uint16_t* __restrict__ hact, int
   }
 }
 
-template <int BM>
 __global__ __launch_bounds__(THREADS, 1) void k_prefill_down(const uint16_t* __restrict__ hact, int ldh, int M, Plan p,
                                                              int expert_sel, int x2_only, int n_cu,
                                                              int n_ntiles, int n_split, WeightView wv,
@@ -391,16 +388,11 @@ __global__ __launch_bounds__(THREADS, 1) void k_prefill_down(const uint16_t* __r
   int inner;
   TileInfo ti;
   // (XCD ranges: one expert's Hact rows, the A operand, stay in one L2)
-  if (!block_tile<BM>(p, expert_sel, x2_only, n_ntiles * n_split, n_cu, inner, ti)) return;
+  if (!block_tile(p, expert_sel, x2_only, n_ntiles * n_split, n_cu, inner, ti)) return;
   if (!storage_index(wv, ti.e, ti.se)) return;
-  if (BM == 256) {
-    const int rows = ti.row_end - ti.row0;
-    if (rows <= 64) down_body<64>(hact, ldh, M, inner, ti, n_ntiles, n_split, wv, yp, slab_stride, accumulate, lds);
-    else if (rows <= 128) down_body<128>(hact, ldh, M, inner, ti, n_ntiles, n_split, wv, yp, slab_stride, accumulate, lds);
-    else down_body<256>(hact, ldh, M, inner, ti, n_ntiles, n_split, wv, yp, slab_stride, accumulate, lds);
-  } else {
-    down_body<BM>(hact, ldh, M, inner, ti, n_ntiles, n_split, wv, yp, slab_stride, accumulate, lds);
-  }
+#define SI_CALL_DN(BMV) down_body<BMV>(hact, ldh, M, inner, ti, n_ntiles, n_split, wv, yp, slab_stride, accumulate, lds)
+  SI_PICK_BODY(ti.row_end - ti.row0, SI_CALL_DN);
+#undef SI_CALL_DN
 }
 
 __global__ __launch_bounds__(256) void k_prefill_combine(const float* __restrict__ yp, size_t slab_stride, int n_split,
@@ -443,16 +435,8 @@ __global__ void k_fill_zero(float* __restrict__ p, size_t n) {
 
 }  // namespace
 
-// dynamic LDS of a launch: the 256-row kernels may run the smaller bodies on tail tiles
-template <int BM> constexpr int kernel_lds() {
-  return BM == 256 ? (Shape<128>::LDS > Shape<256>::LDS ? Shape<128>::LDS : Shape<256>::LDS) : Shape<BM>::LDS;
-}
-
-template <int BM> static hipError_t set_lds_attr() {
-  hipError_t e = hipFuncSetAttribute((const void*)k_prefill_gateup<BM>, hipFuncAttributeMaxDynamicSharedMemorySize, kernel_lds<BM>());
-  if (e != hipSuccess) return e;
-  return hipFuncSetAttribute((const void*)k_prefill_down<BM>, hipFuncAttributeMaxDynamicSharedMemorySize, kernel_lds<BM>());
-}
+static_assert(Shape<64>::LDS <= KERNEL_LDS && Shape<128>::LDS <= KERNEL_LDS && Shape<192>::LDS <= KERNEL_LDS &&
+              Shape<256>::LDS <= KERNEL_LDS, "a body does not fit the launch's LDS");
 
 // compute units of the current device (a round of the tail split)
 static int cu_count() {
@@ -466,54 +450,41 @@ static int cu_count() {
 }
 
 // grid of a launch over at most n_tiles logical ids: room for the XCD ranges (rounded up to 8) and for the
-// second halves of a split tail (at most half a round)
-static int grid_blocks(int n_tiles, int bm) { return (n_tiles + 7) / 8 * 8 + 8 + (bm == 256 ? cu_count() / 2 + 8 : 0); }
+// second blocks of a split tail (at most half a round)
+static int grid_blocks(int n_tiles) { return (n_tiles + 7) / 8 * 8 + 8 + cu_count() / 2 + 8; }
 
 static hipError_t ensure_lds_attr() {
   static hipError_t st = [] {
-    hipError_t e = set_lds_attr<256>();
-    if (e == hipSuccess) e = set_lds_attr<128>();
-    if (e == hipSuccess) e = set_lds_attr<64>();
-    return e;
+    hipError_t e = hipFuncSetAttribute((const void*)k_prefill_gateup, hipFuncAttributeMaxDynamicSharedMemorySize, KERNEL_LDS);
+    if (e != hipSuccess) return e;
+    return hipFuncSetAttribute((const void*)k_prefill_down, hipFuncAttributeMaxDynamicSharedMemorySize, KERNEL_LDS);
   }();
   return st;
 }
 
-hipError_t launch_prefill_gateup(const uint16_t* x, int M, const Plan& plan, int bm, int expert_sel, int x2_only,
+hipError_t launch_prefill_gateup(const uint16_t* x, int M, const Plan& plan, int expert_sel, int x2_only,
                                  int n_row_tiles, const WeightView& wv, uint16_t* hact, int ldh,
                                  hipStream_t stream) {
   if (wv.n_chunks <= 0 || n_row_tiles <= 0) return hipSuccess;
   hipError_t e = ensure_lds_attr();
   if (e != hipSuccess) return e;
   const int n_ctiles = (wv.n_chunks + 1) / 2;
-  const int total = grid_blocks(n_row_tiles * n_ctiles, bm);
-#define SI_LAUNCH_GU(BMV)                                                                                          \
-  hipLaunchKernelGGL(k_prefill_gateup<BMV>, dim3(total), dim3(THREADS), kernel_lds<BMV>(), stream, x, M, plan,        \
-                     expert_sel, x2_only, cu_count(), n_ctiles, wv, hact, ldh)
-  if (bm == 256) SI_LAUNCH_GU(256);
-  else if (bm == 128) SI_LAUNCH_GU(128);
-  else if (bm == 64) SI_LAUNCH_GU(64);
-  else return hipErrorInvalidValue;
-#undef SI_LAUNCH_GU
+  const int total = grid_blocks(n_row_tiles * n_ctiles);
+  hipLaunchKernelGGL(k_prefill_gateup, dim3(total), dim3(THREADS), KERNEL_LDS, stream, x, M, plan, expert_sel, x2_only,
+                     cu_count(), n_ctiles, wv, hact, ldh);
   return hipGetLastError();
 }
 
-hipError_t launch_prefill_down(const uint16_t* hact, int ldh, int M, const Plan& plan, int bm, int expert_sel,
+hipError_t launch_prefill_down(const uint16_t* hact, int ldh, int M, const Plan& plan, int expert_sel,
                                int x2_only, int n_row_tiles, const WeightView& wv, float* yp, size_t slab_stride,
                                int n_split, int accumulate, hipStream_t stream) {
   if (wv.n_chunks <= 0 || n_row_tiles <= 0) return hipSuccess;
   hipError_t e = ensure_lds_attr();
   if (e != hipSuccess) return e;
   const int n_ntiles = (M + BN - 1) / BN;
-  const int total = grid_blocks(n_row_tiles * n_ntiles * n_split, bm);
-#define SI_LAUNCH_DN(BMV)                                                                                          \
-  hipLaunchKernelGGL(k_prefill_down<BMV>, dim3(total), dim3(THREADS), kernel_lds<BMV>(), stream, hact, ldh, M, plan,  \
-                     expert_sel, x2_only, cu_count(), n_ntiles, n_split, wv, yp, slab_stride, accumulate)
-  if (bm == 256) SI_LAUNCH_DN(256);
-  else if (bm == 128) SI_LAUNCH_DN(128);
-  else if (bm == 64) SI_LAUNCH_DN(64);
-  else return hipErrorInvalidValue;
-#undef SI_LAUNCH_DN
+  const int total = grid_blocks(n_row_tiles * n_ntiles * n_split);
+  hipLaunchKernelGGL(k_prefill_down, dim3(total), dim3(THREADS), KERNEL_LDS, stream, hact, ldh, M, plan, expert_sel,
+                     x2_only, cu_count(), n_ntiles, n_split, wv, yp, slab_stride, accumulate);
   return hipGetLastError();
 }
 

@@ -72,7 +72,7 @@ __global__ void k_dense_assign(int T, int32_t* __restrict__ idx, float* __restri
 }
 
 // Single block.  Builds count/off/perm/inv and the launch tables from idx.
-__device__ __forceinline__ void assign_body(int T, int E, int k, int has_shared, int n_x1, int bm, const Plan& p,
+__device__ __forceinline__ void assign_body(int T, int E, int k, int has_shared, int n_x1, const Plan& p,
                                             const RouteOut& u) {
   __shared__ int s_count[MAX_EXPERTS + 2];
   __shared__ int s_count1[MAX_EXPERTS + 2];
@@ -105,8 +105,8 @@ __device__ __forceinline__ void assign_body(int T, int E, int k, int has_shared,
       if (s_count[e] > 0) ++nt;
       s_tiles[0][e] = a;
       s_tiles[1][e] = b;
-      a += (s_count[e] + bm - 1) / bm;
-      b += (s_count[e] - s_count1[e] + bm - 1) / bm;
+      a += n_row_tiles(s_count[e]);
+      b += n_row_tiles(s_count[e] - s_count1[e]);
     }
     s_tiles[0][EX] = a;
     s_tiles[1][EX] = b;
@@ -180,15 +180,15 @@ __device__ __forceinline__ void assign_body(int T, int E, int k, int has_shared,
     for (int t = tid; t < T; t += ROUTE_THREADS) p.row_token[n_pairs + t] = t;
 }
 
-__global__ __launch_bounds__(ROUTE_THREADS) void k_assign(int T, int E, int k, int has_shared, int n_x1, int bm,
+__global__ __launch_bounds__(ROUTE_THREADS) void k_assign(int T, int E, int k, int has_shared, int n_x1,
                                                           Plan p, RouteOut u) {
-  assign_body(T, E, k, has_shared, n_x1, bm, p, u);
+  assign_body(T, E, k, has_shared, n_x1, p, u);
 }
 
 // Few tokens (generation phase): selection and assignment in one launch.  Wave v of the block takes
 // tokens v, v + 16, ...; the assignment then runs on the whole block.
 __global__ __launch_bounds__(ROUTE_THREADS) void k_route_small(const float* __restrict__ logits, int T, int E, int k,
-                                                               int has_shared, int n_x1, int bm, Plan p, RouteOut u) {
+                                                               int has_shared, int n_x1, Plan p, RouteOut u) {
   __shared__ float sel[ROUTE_THREADS / WAVE][MAX_EXPERTS];
   const int wv = threadIdx.x / WAVE, lane = threadIdx.x % WAVE;
   if (logits) {
@@ -203,7 +203,7 @@ __global__ __launch_bounds__(ROUTE_THREADS) void k_route_small(const float* __re
       if (u.idx) u.idx[i] = p.idx[i];
       if (u.w) u.w[i] = p.w[i];
     }
-  assign_body(T, E, k, has_shared, n_x1, bm, p, u);
+  assign_body(T, E, k, has_shared, n_x1, p, u);
 }
 
 __global__ void k_copy_user(int n, const int32_t* __restrict__ idx, const float* __restrict__ w, int32_t* uidx,
@@ -217,11 +217,11 @@ __global__ void k_copy_user(int n, const int32_t* __restrict__ idx, const float*
 
 }  // namespace
 
-hipError_t launch_route(const float* logits, int T, int E, int k, int has_shared, int n_g, int bm,
+hipError_t launch_route(const float* logits, int T, int E, int k, int has_shared, int n_g,
                         const Plan& plan, const RouteOut& user, hipStream_t stream) {
   if (T <= 0) return hipSuccess;
   if (T <= 64) {
-    hipLaunchKernelGGL(k_route_small, dim3(1), dim3(ROUTE_THREADS), 0, stream, logits, T, E, k, has_shared, T - n_g, bm,
+    hipLaunchKernelGGL(k_route_small, dim3(1), dim3(ROUTE_THREADS), 0, stream, logits, T, E, k, has_shared, T - n_g,
                        plan, user);
     return hipGetLastError();
   }
@@ -235,7 +235,7 @@ hipError_t launch_route(const float* logits, int T, int E, int k, int has_shared
     hipLaunchKernelGGL(k_copy_user, dim3((n + 255) / 256), dim3(256), 0, stream, n, plan.idx, plan.w, user.idx,
                        user.w);
   }
-  hipLaunchKernelGGL(k_assign, dim3(1), dim3(ROUTE_THREADS), 0, stream, T, E, k, has_shared, T - n_g, bm, plan,
+  hipLaunchKernelGGL(k_assign, dim3(1), dim3(ROUTE_THREADS), 0, stream, T, E, k, has_shared, T - n_g, plan,
                      user);
   return hipGetLastError();
 }

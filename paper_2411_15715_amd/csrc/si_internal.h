@@ -17,10 +17,21 @@ inline size_t chunk_bytes(int M) { return chunk_elems(M) * 2; }
 
 constexpr int MAX_EXPERTS = 256;      // routed experts (a shared expert adds one more table entry)
 constexpr int ROUTE_THREADS = 1024;   // block size of the assignment kernel
-constexpr int PREFILL_BM_MAX = 256;   // largest row tile of the prefill GEMMs (also 128 and 64)
+constexpr int TILE_ROWS = 256;        // rows per row tile of the prefill GEMMs ...
+constexpr int TILE_MERGE = 0;         // ... except that a remainder of up to this many rows rides in the expert's last tile
 constexpr int MAX_KSPLIT = 4;         // k-splits (output slabs) of the prefill down projection
 constexpr int DECODE_TB = 4;          // most tokens handled per weight pass in the GEMV kernels
 constexpr int DOWN_SLOTS = 16;        // j-splits of the decode down projection per part
+
+// Row tiles of an expert (or of its X2 rows) with `rows` rows: tiles of TILE_ROWS rows; the last one holds what is
+// left, up to TILE_ROWS + TILE_MERGE rows, so that a few rows beyond a multiple of the tile never cost a block of
+// their own (a block streams its weight tile whatever the number of rows).  The GEMM kernels run, per tile, the
+// body instantiated for the rows the tile really has (64, 128, 192, 256 or 320).
+inline SI_HD int n_row_tiles(int rows) {
+  if (rows <= 0) return 0;
+  const int n = (rows - TILE_MERGE + TILE_ROWS - 1) / TILE_ROWS;
+  return n < 1 ? 1 : n;
+}
 
 // Device-side result of the token assignment plus the launch tables derived from it.
 // Expert tables have EX = E + (shared ? 1 : 0) entries; the shared expert is entry E and owns the
@@ -52,7 +63,7 @@ struct RouteOut {
 };
 
 // route.hip
-hipError_t launch_route(const float* logits, int T, int E, int k, int has_shared, int n_g, int bm,
+hipError_t launch_route(const float* logits, int T, int E, int k, int has_shared, int n_g,
                         const Plan& plan, const RouteOut& user, hipStream_t stream);
 
 // Description of the weights one kernel launch works on.
@@ -98,13 +109,13 @@ hipError_t launch_decode_combine(const DecodeCombineArgs& a, const Plan& plan, f
 
 // prefill.hip --------------------------------------------------------------------------------
 // Hact[row][c] (bf16) for c in [0, 64*n_chunks): SwiGLU of the gate/up products (MFMA, fp32 acc).
-// bm: rows per tile (256, 128 or 64); launches over all experts need the row-tile tables built for the same bm.
-hipError_t launch_prefill_gateup(const uint16_t* x, int M, const Plan& plan, int bm, int expert_sel, int x2_only,
+// n_row_tiles: (an upper bound on) the row tiles of the launch, for the grid; the kernels find the real ones
+hipError_t launch_prefill_gateup(const uint16_t* x, int M, const Plan& plan, int expert_sel, int x2_only,
                                  int n_row_tiles, const WeightView& wv, uint16_t* hact, int ldh,
                                  hipStream_t stream);
 // Yp[split][row][m] (fp32) (+)= Hact[row][chunks of the split] . Wd[chunks][m]; the chunk range of the launch is
 // cut into n_split equal parts, each with its own output slab (summed by the combine kernel)
-hipError_t launch_prefill_down(const uint16_t* hact, int ldh, int M, const Plan& plan, int bm, int expert_sel,
+hipError_t launch_prefill_down(const uint16_t* hact, int ldh, int M, const Plan& plan, int expert_sel,
                                int x2_only, int n_row_tiles, const WeightView& wv, float* yp, size_t slab_stride,
                                int n_split, int accumulate, hipStream_t stream);
 // y[t][m] = sum_s w[t][s]*Yp[inv[t*k+s]][m] + Yp[T*k+t][m] (shared) + ycc[t][m] (X1 rows)
