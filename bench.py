@@ -35,8 +35,8 @@ PMC_TRAFFIC = {
     ("mixtral_8x7b", (0.5, 0.5, 0.0), "decode_gateup"): 153040.2 * 1024 + 56.3 * 1024,
     ("mixtral_8x7b", (1.0, 0.0, 0.0), "decode_gateup"): 458877.0 * 1024 + 112.5 * 1024,
     ("mixtral_8x7b", (1.0, 0.0, 0.0), "decode_down"): 230330.2 * 1024 + 512.0 * 1024,
-    ("mixtral_8x7b", (1.0, 0.0, 0.0), "prefill_gateup"): 2602236.6 * 1024 + 28672.0 * 1024,
-    ("mixtral_8x7b", (1.0, 0.0, 0.0), "prefill_down"): 993128.4 * 1024 + 32768.0 * 1024,
+    ("mixtral_8x7b", (1.0, 0.0, 0.0), "prefill_gateup"): 2103590.4 * 1024 + 28672.0 * 1024,
+    ("mixtral_8x7b", (1.0, 0.0, 0.0), "prefill_down"): 946501.6 * 1024 + 32768.0 * 1024,
 }
 
 

@@ -17,21 +17,15 @@ inline size_t chunk_bytes(int M) { return chunk_elems(M) * 2; }
 
 constexpr int MAX_EXPERTS = 256;      // routed experts (a shared expert adds one more table entry)
 constexpr int ROUTE_THREADS = 1024;   // block size of the assignment kernel
-constexpr int TILE_ROWS = 256;        // rows per row tile of the prefill GEMMs ...
-constexpr int TILE_MERGE = 0;         // ... except that a remainder of up to this many rows rides in the expert's last tile
+constexpr int TILE_ROWS = 256;        // rows per row tile of the prefill GEMMs (the last tile of an expert holds what is left)
 constexpr int MAX_KSPLIT = 4;         // k-splits (output slabs) of the prefill down projection
 constexpr int DECODE_TB = 4;          // most tokens handled per weight pass in the GEMV kernels
 constexpr int DOWN_SLOTS = 16;        // j-splits of the decode down projection per part
 
-// Row tiles of an expert (or of its X2 rows) with `rows` rows: tiles of TILE_ROWS rows; the last one holds what is
-// left, up to TILE_ROWS + TILE_MERGE rows, so that a few rows beyond a multiple of the tile never cost a block of
-// their own (a block streams its weight tile whatever the number of rows).  The GEMM kernels run, per tile, the
-// body instantiated for the rows the tile really has (64, 128, 192, 256 or 320).
-inline SI_HD int n_row_tiles(int rows) {
-  if (rows <= 0) return 0;
-  const int n = (rows - TILE_MERGE + TILE_ROWS - 1) / TILE_ROWS;
-  return n < 1 ? 1 : n;
-}
+// Row tiles of an expert (or of its X2 rows) with `rows` rows.  The GEMM kernels run, per tile, the body
+// instantiated for the rows the tile really has (64, 128, 192 or 256): a block streams its weight tile whatever
+// the number of rows, so an expert with 140 rows gets one 192-row block, not two blocks of 128.
+inline SI_HD int n_row_tiles(int rows) { return rows <= 0 ? 0 : (rows + TILE_ROWS - 1) / TILE_ROWS; }
 
 // Device-side result of the token assignment plus the launch tables derived from it.
 // Expert tables have EX = E + (shared ? 1 : 0) entries; the shared expert is entry E and owns the
