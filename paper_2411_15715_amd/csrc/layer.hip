@@ -647,7 +647,8 @@ int si_layer_resplit(si_layer_t* L, float r_gg, float r_cg, float r_cc) {
   int n_gg, n_cg, n_cc, s_gg = 0, s_cg = 0, s_cc = 0;
   split_counts(L->H, g, r_gg, r_cg, &n_gg, &n_cg, &n_cc);
   if (L->has_shared) split_counts(L->Hs, g, r_gg, r_cg, &s_gg, &s_cg, &s_cc);
-  // nothing may be in flight on the old buffers
+  // nothing may be in flight on the old buffers (a forward call that failed half-way may have left the host workers running)
+  if (L->pool) cc_pool_wait(L->pool);
   HIP_TRY(hipStreamSynchronize(L->copy_stream));
   HIP_TRY(hipDeviceSynchronize());
   const size_t ce = L->ce;
