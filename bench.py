@@ -616,7 +616,7 @@ def main():
                                                          (" + shared H=%d" % cfg.d_ff_shared) if cfg.d_ff_shared else "",
                                                          cfg.t_prefill, args.decode_calls, cfg.t_decode),
                    "split_gg_cg_cc": list(split), "columns": info, "n_g": n_g, "tokens_per_step": tokens_per_step},
-        "roofline": roofline_of(dominant, ktab[dominant], cfg.name, split),
+        "roofline": roofline_of(dominant, ktab[dominant], None if args.q4 else cfg.name, split),
         "phases": {k: round(v, 4) for k, v in phase.items()},
         "kernels": {k: {kk: (round(vv, 4) if isinstance(vv, float) else vv) for kk, vv in v.items()} for k, v in ktab.items()},
         "host_link": link,
@@ -634,7 +634,7 @@ def main():
             "decode_call_us": round(calls2["decode_call_us"], 2), "prefill_call_us": round(calls2["prefill_call_us"], 2),
             "prefill_ms": round(float(np.mean([s["total_ms"] for s in pre2])), 4),
             "decode_ms": round(float(np.mean([s["total_ms"] for s in dec2])), 4),
-            "rooflines": [roofline_of(k, k2[k], cfg.name, (1.0, 0.0, 0.0)) for k in k2 if "bound" in k2[k]],
+            "rooflines": [roofline_of(k, k2[k], None if args.q4 else cfg.name, (1.0, 0.0, 0.0)) for k in k2 if "bound" in k2[k]],
         }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, w, wl, args.cpu_seconds)
