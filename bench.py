@@ -66,6 +66,10 @@ def parse_args():
                     help="instead of the throughput line: a stack of this many layers of the config's shape under GPU-memory "
                          "budgets of 25/50/75 %% of its weights; greedy per-layer r_GG (Section IV-A.4) against the same "
                          "r_GG for every layer, decode step measured with and without cross-layer prefetch")
+    ap.add_argument("--sweep", action="store_true",
+                    help="instead of the throughput line: the config's layer moved through the GG/CG/CC sweep of the "
+                         "PhiMoE / Mixtral-8x22B workloads (100/0/0 ... 20/60/20) with si_layer_resplit; per split the "
+                         "prompt-phase and generation-phase call times, link rate and overlap")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="first run a plain elementwise copy of 1 GiB (reads 1 GiB, writes 1 GiB) three times: "
                          "the reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE counters")
@@ -530,6 +534,67 @@ def placement_study(args, si, torch, cfg, w):
                       "decode_calls": len(wl.dec), "rows": rows}))
 
 
+def sweep_study(args, si, torch, cfg, w):
+    """One layer, re-sliced through the split sweep: call times per phase, streamed bytes, link rate, overlap."""
+    import synth
+    wl = Workload(cfg, args.decode_calls)
+    stream = torch.cuda.current_stream().cuda_stream
+    first = synth.SPLIT_SWEEP[0]
+    shared = tuple(w[k] for k in ("s_gate", "s_up", "s_down")) if cfg.d_ff_shared else None
+    layer = si.si_layer_create(cfg.d_model, cfg.d_ff, cfg.n_experts, cfg.top_k, w["w_gate"], w["w_up"], w["w_down"],
+                               first[0], first[1], first[2], max(cfg.t_prefill, cfg.t_decode),
+                               d_ff_shared=cfg.d_ff_shared, shared=shared)
+    rows = []
+    try:
+        for split in synth.SPLIT_SWEEP:
+            t0 = time.perf_counter()
+            si.si_layer_resplit(layer, *split)
+            t_resplit = time.perf_counter() - t0
+            n_g = cfg.t_prefill if split[2] > 0 else 0
+            run_steps(si, layer, wl, max(1, args.warmup), n_g, stream)
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+            for _ in range(args.steps):
+                for xd, ld, _lg in wl.dec:
+                    si.si_layer_forward(layer, xd.data_ptr(), ld.data_ptr() if ld is not None else None, cfg.t_decode, 0,
+                                        si.SI_DECODE, wl.yd.data_ptr(), stream=stream)
+            torch.cuda.synchronize()
+            t_dec = (time.perf_counter() - t1) / (args.steps * len(wl.dec))
+            t1 = time.perf_counter()
+            for _ in range(args.steps):
+                si.si_layer_forward(layer, wl.xp.data_ptr(), wl.lp_dev.data_ptr() if wl.lp_dev is not None else None,
+                                    cfg.t_prefill, n_g, si.SI_PREFILL, wl.yp.data_ptr(), stream=stream)
+            torch.cuda.synchronize()
+            t_pre = (time.perf_counter() - t1) / args.steps
+            si.si_layer_set_profiling(layer, 1)
+            stats = []
+            run_steps(si, layer, wl, 1, n_g, stream, collect=stats)
+            torch.cuda.synchronize()
+            si.si_layer_set_profiling(layer, 0)
+            pre = [st for kind, st in stats if kind == "prefill"]
+            dec = [st for kind, st in stats if kind == "decode"]
+            copied = sum(st["bytes_streamed"] for _, st in stats)
+            copy_ms = sum(st["copy_ms"] for _, st in stats)
+            rows.append({"split": list(split), "columns": si.si_layer_split_info(layer), "n_g": n_g,
+                         "resplit_s": round(t_resplit, 3),
+                         "prefill_call_ms": round(1e3 * t_pre, 3), "decode_call_ms": round(1e3 * t_dec, 4),
+                         "prefill_tokens_per_s": round(cfg.t_prefill / t_pre, 1),
+                         "decode_tokens_per_s": round(cfg.t_decode / t_dec, 1),
+                         "streamed_MB_prefill": round(sum(st["bytes_streamed"] for st in pre) / 1e6, 1),
+                         "streamed_MB_decode_call": round(float(np.mean([st["bytes_streamed"] for st in dec])) / 1e6, 1),
+                         "link_GBps": round(copied / (copy_ms / 1e3) / 1e9, 2) if copy_ms > 0 else None,
+                         "overlap_prefill": round(float(np.mean([st["overlap"] for st in pre])), 3),
+                         "overlap_decode": round(float(np.mean([st["overlap"] for st in dec])), 3),
+                         "cc_ms_decode_call": round(float(np.mean([st["cc_ms"] for st in dec])), 3)})
+            print("sweep %s done" % (split,), file=sys.stderr, flush=True)
+    finally:
+        si.si_layer_destroy(layer)
+    print(json.dumps({"study": "split sweep", "config": {"workload": "%s-shaped layer: E=%d top-%d M=%d H=%d, prefill %d tokens, "
+                      "decode %d token(s) per call" % (cfg.name, cfg.n_experts, cfg.top_k, cfg.d_model, cfg.d_ff,
+                                                        cfg.t_prefill, cfg.t_decode)},
+                      "dtype": "bf16", "data": "synthetic", "rows": rows}))
+
+
 def synth_tokens(cfg, T):
     import synth
     return synth.make_tokens(cfg, T, stream=7)
@@ -572,6 +637,9 @@ def main():
         return
     if args.place:
         placement_study(args, si, torch, cfg, w)
+        return
+    if args.sweep:
+        sweep_study(args, si, torch, cfg, w)
         return
     wl = Workload(cfg, args.decode_calls)
     t_gen = time.perf_counter() - t0
