@@ -55,6 +55,9 @@ def parse_args():
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     ap.add_argument("--q4", action="store_true",
                     help="4-bit weights (codes + bf16 group scales) instead of bf16: same step, same metric")
+    ap.add_argument("--deq-mib", type=int, default=0,
+                    help="with --q4: 0 = prompt-phase GEMMs convert the codes themselves; > 0 = two passes through a "
+                         "bf16 scratch of this many MiB")
     ap.add_argument("--solve", action="store_true",
                     help="instead of the throughput line: profile this machine (Eq. 3), solve r_CG* for the config's "
                          "r_GG and n_g* for its prompt length (Section IV), and measure the layer over a sweep of "
@@ -124,7 +127,7 @@ def measure(si, torch, cfg, w, split, wl, steps, warmup, n_g):
     """Time `steps` steps (profiling off), then repeat them with per-launch events for kernel times."""
     if "q_gate" in w:
         layer = si.si_layer_create_q4(cfg.d_model, cfg.d_ff, cfg.n_experts, cfg.top_k, w, split[0], split[1], split[2],
-                                      max(cfg.t_prefill, cfg.t_decode), d_ff_shared=cfg.d_ff_shared)
+                                      max(cfg.t_prefill, cfg.t_decode), d_ff_shared=cfg.d_ff_shared, deq_mib=DEQ_MIB)
     else:
         shared = tuple(w[k] for k in ("s_gate", "s_up", "s_down")) if cfg.d_ff_shared else None
         layer = si.si_layer_create(cfg.d_model, cfg.d_ff, cfg.n_experts, cfg.top_k, w["w_gate"], w["w_up"], w["w_down"],
@@ -250,6 +253,7 @@ def eq6_prediction(st):
     return max(tau_g + merge, tau_c)
 
 
+DEQ_MIB = 0  # set by main() from --deq-mib
 MEASURED_PEAKS = None  # filled by main() from si_measure_peaks(): what the simplest kernels reach on this machine
 
 
@@ -618,7 +622,8 @@ def main():
             torch.add(src, 0.0, out=dst)
         torch.cuda.synchronize()
         del src, dst
-    global MEASURED_PEAKS
+    global MEASURED_PEAKS, DEQ_MIB
+    DEQ_MIB = args.deq_mib
     if not args.no_peaks:
         MEASURED_PEAKS = si.si_measure_peaks(0)
     cfg = synth.CONFIGS[args.config]

@@ -69,8 +69,10 @@ typedef struct {
   int32_t device;      /* HIP device ordinal */
   int32_t stage_mib;   /* size of one staging buffer for CG copies in MiB; 0 -> 256 */
   int32_t n_stage;     /* number of staging buffers (>= 2); 0 -> 2 (double buffering) */
-  int32_t deq_mib;     /* 4-bit layers only: device scratch in MiB for the bf16 copies the prompt-phase GEMMs read
-                          (never more than the largest part needs); 0 -> 2048 */
+  int32_t deq_mib;     /* 4-bit layers only.  0: the prompt-phase GEMMs read the 4-bit chunks and convert them on
+                          their way into LDS (no scratch).  > 0: two passes instead, a dequantisation kernel writing
+                          bf16 copies into a device scratch of this many MiB (never more than the largest part
+                          needs) that the bf16 GEMMs then read, piece by piece */
 } si_layer_desc_t;
 
 /* Optional device outputs of the token-assignment step; any pointer may be NULL.

@@ -572,16 +572,15 @@ int create_impl(const si_layer_desc_t* desc, const WeightSource& src, const uint
   {
     // widest launch whatever the slicing rates: a part never has more columns than its expert
     int cols = std::max(L->H, L->Hs);
-    if (L->q4) {
-      // bf16 scratch for the prompt-phase GEMMs (default 2 GiB: the fewer sub-pieces, the fewer short launches;
-      // measured 1.88 / 1.59 / 1.47 ms per Mixtral-shaped prompt call with 0.5 / 2 / 4 GiB), at least one chunk per
-      // routed expert, never more than the largest part needs
+    if (L->q4 && desc->deq_mib > 0) {
+      // two-pass prompt phase on request: bf16 scratch that a dequantisation kernel fills and the bf16 GEMMs read
+      // (the fewer sub-pieces, the fewer short launches), at least one chunk per routed expert, never more than
+      // the largest part needs.  By default (deq_mib = 0) the GEMMs convert the codes on their way into LDS.
       const size_t cb16 = chunk_elems(M) * 2;
-      const size_t deq_mib = desc->deq_mib == 0 ? 2048 : (size_t)desc->deq_mib;
-      L->deq_chunks = (int)std::max<size_t>((size_t)E, (deq_mib << 20) / cb16);
+      L->deq_chunks = (int)std::max<size_t>((size_t)E, ((size_t)desc->deq_mib << 20) / cb16);
       L->deq_chunks = std::min(L->deq_chunks, std::max(E, E * std::max({L->H / CHUNK_J, L->Hs / CHUNK_J, 1})));
       TRY_OR_DESTROY(dev_alloc(&L->d_deq, (size_t)L->deq_chunks * chunk_elems(M)));
-      cols = L->deq_chunks * CHUNK_J;
+      cols = std::max(cols, L->deq_chunks * CHUNK_J);
     }
     L->hact_elems = n_rows * (size_t)cols;
     TRY_OR_DESTROY(dev_alloc(&L->d_hact, L->hact_elems));
@@ -921,12 +920,13 @@ int si_layer_forward(si_layer_t* L, const void* x_dev, const float* logits_dev, 
       const int n_rt = esel >= 0 ? n_row_tiles(x2_only ? rows_x2(esel) : rows_all(esel)) : tiles_upper;
       // bf16 layers: one pass over the chunk range.  4-bit layers: the range goes through the bf16 scratch in
       // sub-pieces (dequantise, FC1, FC2 accumulating), as many chunks per expert as the scratch holds.
-      const int cap = !L->q4 ? n : std::max(1, esel >= 0 ? L->deq_chunks : L->deq_chunks / E);
+      const bool two_pass = L->q4 && L->d_deq;
+      const int cap = !two_pass ? n : std::max(1, esel >= 0 ? L->deq_chunks : L->deq_chunks / E);
       for (int s0 = 0; s0 < n; s0 += cap) {
         const int ns = std::min(cap, n - s0);
         const bool first = first_for_rows && s0 == 0;
         WeightView wg = wv;
-        if (L->q4) {
+        if (two_pass) {
           WeightView src{base, estride, c0 + s0, ns, 0, 1, wv.e_map};
           const size_t dst_stride = esel >= 0 ? 0 : (size_t)ns * chunk_elems(M);
           {

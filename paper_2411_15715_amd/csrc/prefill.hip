@@ -214,6 +214,118 @@ __device__ inline bool block_tile(const Plan& p, int expert_sel, int x2_only, in
     }                                                                                                            \
   }
 
+// register loads and the dependency tie used by the 4-bit loop below
+__device__ inline void gload_b128(u32x4& q, const void* p) {
+  asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(q) : "v"(p) : "memory");
+}
+__device__ inline void gload_u16(uint32_t& z, const void* p) {
+  asm volatile("global_load_ushort %0, %1, off" : "=v"(z) : "v"(p) : "memory");
+}
+#define SI_BREADY(q, z) asm volatile("" : "+v"(q), "+v"(z)::"memory")
+
+// The same loop for weights in the 4-bit storage form.  The A operand still arrives by direct global->LDS loads;
+// the B operand cannot (it has to be turned into bf16 on the way), so every lane fetches 16 bytes of codes (32
+// weights) and their group scale into registers one iteration ahead (BLOAD), and turns them into four 16-byte
+// pieces of bf16((code - 8) * scale) that it writes into the stage freed by the previous iteration's barrier,
+// one piece after each k-step's matrix instructions (BCONV), so that the conversion arithmetic runs under the
+// matrix core's work.  A k-tile of 64 is one scale group of either projection.
+// Order of the vector-memory operations of a wave, which the wait counts rely on: iteration j issues the
+// register loads of tile j+NST (GL instructions, at the top of the iteration) and, after its barrier, the A loads
+// of tile j+NST (ALD instructions).  The register loads are inline assembly and their waits explicit: with
+// direct-to-LDS loads in flight the compiler's own wait before the first use of a loaded register is vmcnt(0),
+// which would drain the ring every iteration; BREADY ties the registers to the explicit wait so that no use is
+// scheduled above it.
+#define SI_GEMM_MAIN_LOOP_Q4(NK, ISSUE_A, BLOAD, BCONV, BFRAG_OFF)                                               \
+  f32x16 acc[S::FA][2];                                                                                          \
+  _Pragma("unroll") for (int i = 0; i < S::FA; ++i) _Pragma("unroll") for (int j = 0; j < 2; ++j)                \
+      _Pragma("unroll") for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;                                         \
+  bf16x8 fa[2][S::FA], fb[2][2];                                                                                 \
+  auto ldfrag = [&](int stage, int ks, int buf) {                                                                \
+    const unsigned char* sa = lds + stage * S::STAGE;                                                            \
+    const unsigned char* sb = sa + BM * 128;                                                                     \
+    const int pc = ks * 2 + (lane >> 5);                                                                         \
+    _Pragma("unroll") for (int i = 0; i < S::FA; ++i) fa[buf][i] = as_bf16x8(                                    \
+        *reinterpret_cast<const u32x4*>(sa + swz(wr * (BM / 2) + i * 32 + (lane & 31), pc)));                    \
+    _Pragma("unroll") for (int j = 0; j < 2; ++j) fb[buf][j] = as_bf16x8(                                        \
+        *reinterpret_cast<const u32x4*>(sb + BFRAG_OFF(wc * 64 + j * 32 + (lane & 31), pc)));                    \
+  };                                                                                                             \
+  auto mma = [&](int buf) {                                                                                      \
+    _Pragma("unroll") for (int i = 0; i < S::FA; ++i) _Pragma("unroll") for (int j = 0; j < 2; ++j)              \
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[buf][i], fb[buf][j], acc[i][j], 0, 0, 0);         \
+  };                                                                                                             \
+  {                                                                                                              \
+    constexpr int GL = 2; /* register loads per B tile and lane: codes, scale */                                 \
+    const int nk_ = (NK);                                                                                        \
+    u32x4 qa, qb;                                                                                                \
+    uint32_t za, zb;                                                                                             \
+    _Pragma("unroll") for (int s0 = 0; s0 < S::NST; ++s0) if (s0 < nk_) ISSUE_A(s0, s0);                         \
+    _Pragma("unroll") for (int s0 = 0; s0 < S::NST - 1; ++s0) if (s0 < nk_) {                                    \
+      BLOAD(s0, qa, za);                                                                                         \
+      wait_vmcnt<0>();                                                                                           \
+      SI_BREADY(qa, za);                                                                                         \
+      _Pragma("unroll") for (int i = 0; i < 4; ++i) BCONV(s0, qa, za, i);                                        \
+    }                                                                                                            \
+    BLOAD(min(S::NST - 1, nk_ - 1), qa, za);                                                                     \
+    wait_vmcnt<0>();                                                                                             \
+    SI_BREADY(qa, za);                                                                                           \
+    wait_lgkmcnt0();                                                                                             \
+    block_barrier();                                                                                             \
+    ldfrag(0, 0, 0);                                                                                             \
+    int st = 0;                                                                                                  \
+    /* one iteration; the codes it converts sit in (qc, zc), those it fetches go to (qn, zn): the loop below  */ \
+    /* alternates two register sets, so that no fetched register is copied while its load is in flight        */ \
+    auto step = [&](int it, u32x4& qc, uint32_t& zc, u32x4& qn, uint32_t& zn) {                                  \
+      const int nx = st + 1 == S::NST ? 0 : st + 1;                                                              \
+      const int pv = st == 0 ? S::NST - 1 : st - 1;                                                              \
+      const bool fill = it + S::NST - 1 < nk_; /* B of tile it+NST-1 goes into stage pv during this iteration */ \
+      /* always issued (index clamped), so that the wait below sees the same number of younger operations */     \
+      BLOAD(min(it + S::NST, nk_ - 1), qn, zn);                                                                  \
+      ldfrag(st, 1, 1); mma(0);                                                                                  \
+      /* (qc, zc) were fetched at the top of the previous iteration; younger: that iteration's A loads, the   */ \
+      /* fetch above                                                                                           */ \
+      if (fill) { wait_vmcnt<S::ALD + GL>(); SI_BREADY(qc, zc); BCONV(pv, qc, zc, 0); }                          \
+      ldfrag(st, 2, 0); mma(1); if (fill) BCONV(pv, qc, zc, 1);                                                  \
+      ldfrag(st, 3, 1); mma(0); if (fill) { BCONV(pv, qc, zc, 2); BCONV(pv, qc, zc, 3); }                        \
+      /* the A loads of tile it+1 must have landed, the B pieces written above and every read of stage st  */    \
+      /* must be complete before the barrier; younger than those A loads are the operations of NST-2 whole  */    \
+      /* iterations and this iteration's register loads                                                     */    \
+      if (fill) wait_vmcnt<(S::NST - 2) * (S::ALD + GL) + GL>(); else wait_vmcnt<0>();                           \
+      wait_lgkmcnt0();                                                                                           \
+      block_barrier();                                                                                           \
+      if (it + 1 < nk_) ldfrag(nx, 0, 0);                                                                        \
+      if (it + S::NST < nk_) ISSUE_A(st, it + S::NST);                                                           \
+      __builtin_amdgcn_s_setprio(1);                                                                             \
+      mma(1);                                                                                                    \
+      __builtin_amdgcn_s_setprio(0);                                                                             \
+      st = nx;                                                                                                   \
+    };                                                                                                           \
+    for (int it = 0; it < nk_; it += 2) {                                                                        \
+      step(it, qa, za, qb, zb);                                                                                  \
+      if (it + 1 < nk_) step(it + 1, qb, zb, qa, za);                                                            \
+    }                                                                                                            \
+  }
+
+// 16-byte LDS store the compiler does not see as one: with a direct-to-LDS load in flight it would otherwise wait
+// for ALL vector-memory operations (vmcnt(0)) before any LDS store it cannot prove disjoint from the load's
+// target, which would drain the ring every iteration.  Disjointness is by construction here (the stage written is
+// not the target of any load in flight), and completion is covered by the loop's own lgkmcnt(0) before each barrier.
+__device__ inline void lds_store_b128(unsigned char* p, const u32x4& v) {
+  const uint32_t a = (uint32_t)(uintptr_t)SI_LPTR(p);
+  asm volatile("ds_write_b128 %0, %1" ::"v"(a), "v"(v) : "memory");
+}
+
+// Eight 4-bit codes (as two words of four byte-sized codes each: `lo` holds elements a0 a1 a2 a3 in its bytes
+// 0..3 for the byte order given by the caller) -> bf16((code - 8) * scale), exact product, one rounding.
+// s8 = -8 * scale.
+__device__ inline uint32_t q4_pair(uint32_t bytes, int b0, int b1, float sc, float s8) {
+  // (the compiler turns byte extraction + conversion into one v_cvt_f32_ubyteN)
+  const float c0 = (float)((bytes >> (8 * b0)) & 0xffu), c1 = (float)((bytes >> (8 * b1)) & 0xffu);
+  typedef float f32x2 __attribute__((ext_vector_type(2)));
+  typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+  const f32x2 v = {__builtin_fmaf(c0, sc, s8), __builtin_fmaf(c1, sc, s8)};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));  // round to nearest even
+}
+
 #define SI_BOFF_SWZ(row, pc) swz((row), (pc))
 #define SI_BOFF_K8(col, pc) (((pc) * BN + (col)) * 16)
 
@@ -395,6 +507,180 @@ __global__ __launch_bounds__(THREADS, 1) void k_prefill_down(const uint16_t* __r
 #undef SI_CALL_DN
 }
 
+// ---------------------------------------------------------------------------------------------
+// The same two GEMMs on weights in the 4-bit storage form (chunk layout in cc_worker.h), converted on the way
+// into the B stage.  Tiles, LDS layouts, fragment reads, matrix instructions and epilogues are those above.
+// ---------------------------------------------------------------------------------------------
+template <int BM>
+__device__ __forceinline__ void gateup_body_q4(const uint16_t* __restrict__ x, int M, const Plan& p, int tc, const TileInfo& ti,
+                                               const WeightView& wv, uint16_t* __restrict__ hact, int ldh,
+                                               unsigned char* lds) {
+  using S = Shape<BM>;
+  const int tid = threadIdx.x, lane = tid % WAVE, w = tid / WAVE;
+  const int wr = w >> 2, wc = w & 3;
+  const unsigned char* ebase = reinterpret_cast<const unsigned char*>(wv.base + (size_t)ti.se * wv.expert_stride);
+
+  const int lrow = lane >> 3, lpp = lane & 7;
+  const uint16_t* a_src[S::ALD];
+#pragma unroll
+  for (int i = 0; i < S::ALD; ++i) {
+    const int lr = w * (BM / 8) + i * 8 + lrow;
+    int row = ti.row0 + lr;
+    row = row < ti.row_end ? row : ti.row_end - 1;
+    a_src[i] = x + (size_t)p.row_token[row] * M + ((lpp ^ ((lr >> 1) & 7)) * 8);
+  }
+  auto issue_a = [&](int stage, int kt) {
+    unsigned char* sa = lds + stage * S::STAGE + w * (BM / 8) * 128;
+#pragma unroll
+    for (int i = 0; i < S::ALD; ++i)
+      __builtin_amdgcn_global_load_lds(SI_GPTR(a_src[i] + kt * BK), SI_LPTR(sa + i * 1024), 16, 0, 0);
+  };
+  // B: wave w fills LDS rows [32 w, 32 w + 32) = (chunk 2*tc + w/4, gate (w even) or up block, columns
+  // ((w/2)%2)*32 .. +31 of the chunk); lane = (row lane/2, k-half lane%2): the 32 weights of its half row are
+  // 16 bytes of codes, i.e. the pieces 4*(lane%2) .. +3 of the LDS row
+  const int chunk_rel = min(2 * tc + (w >> 2), wv.n_chunks - 1);
+  const unsigned char* cb = ebase + (size_t)(wv.chunk0 + chunk_rel) * q4_chunk_u16(M) * 2;
+  const int jc = ((w >> 1) & 1) * 32 + (lane >> 1), kh = lane & 1;
+  const unsigned char* qrow = cb + q4_off_codes(w & 1, M) + (size_t)jc * (M / 2) + kh * 16;
+  const uint16_t* zrow = reinterpret_cast<const uint16_t*>(cb + q4_off_scales(w & 1, M)) + (size_t)jc * (M / 64);
+  const int brow = w * 32 + (lane >> 1);
+  const int bsw = (brow >> 1) & 7;
+  auto bload = [&](int kt, u32x4& q, uint32_t& z) {
+    gload_b128(q, qrow + (size_t)kt * 32);
+    gload_u16(z, zrow + kt);
+  };
+  // word i of the lane's codes = elements 8i .. 8i+7 of its half row; even nibbles hold elements 0 4 1 5, odd
+  // nibbles 2 6 3 7 (cc_worker.h)
+  auto bconv = [&](int stage, const u32x4& q, uint32_t z, int i) {
+    const float sc = __uint_as_float(z << 16), s8 = -8.f * sc;
+    const uint32_t wd = q[i], ev = wd & 0x0f0f0f0fu, od = (wd >> 4) & 0x0f0f0f0fu;
+    u32x4 o;
+    o.x = q4_pair(ev, 0, 2, sc, s8);
+    o.y = q4_pair(od, 0, 2, sc, s8);
+    o.z = q4_pair(ev, 1, 3, sc, s8);
+    o.w = q4_pair(od, 1, 3, sc, s8);
+    lds_store_b128(lds + stage * S::STAGE + BM * 128 + brow * 128 + (((kh * 4 + i) ^ bsw) << 4), o);
+  };
+  SI_GEMM_MAIN_LOOP_Q4(M / BK, issue_a, bload, bconv, SI_BOFF_SWZ)
+  const int jl = wc * 32 + (lane & 31);
+  if (2 * tc + (jl >> 6) < wv.n_chunks) {
+    const int col = wv.col0 + tc * 128 + jl;
+#pragma unroll
+    for (int i = 0; i < S::FA; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int row = ti.row0 + wr * (BM / 2) + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+        if (row < ti.row_end) hact[(size_t)row * ldh + col] = f32_to_bf16(silu_f(acc[i][0][r]) * acc[i][1][r]);
+      }
+  }
+}
+
+__global__ __launch_bounds__(THREADS, 1) void k_prefill_gateup_q4(const uint16_t* __restrict__ x, int M, Plan p,
+                                                                  int expert_sel, int x2_only, int n_cu,
+                                                                  int n_ctiles, WeightView wv,
+                                                                  uint16_t* __restrict__ hact, int ldh) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+  int tc;
+  TileInfo ti;
+  if (!block_tile(p, expert_sel, x2_only, n_ctiles, n_cu, tc, ti)) return;
+  if (!storage_index(wv, ti.e, ti.se)) return;
+#define SI_CALL_GU(BMV) gateup_body_q4<BMV>(x, M, p, tc, ti, wv, hact, ldh, lds)
+  SI_PICK_BODY(ti.row_end - ti.row0, SI_CALL_GU);
+#undef SI_CALL_GU
+}
+
+template <int BM>
+__device__ __forceinline__ void down_body_q4(const uint16_t* __restrict__ hact, int ldh, int M, int inner, const TileInfo& ti,
+                                             int n_ntiles, int n_split, const WeightView& wv, float* __restrict__ yp,
+                                             size_t slab_stride, int accumulate, unsigned char* lds) {
+  using S = Shape<BM>;
+  const int nt = inner % n_ntiles, split = inner / n_ntiles;
+  const int c_begin = (int)((long)wv.n_chunks * split / n_split), c_end = (int)((long)wv.n_chunks * (split + 1) / n_split);
+  if (c_begin >= c_end && accumulate) return;
+  const int tid = threadIdx.x, lane = tid % WAVE, w = tid / WAVE;
+  const int wr = w >> 2, wc = w & 3;
+  const int n0 = nt * BN;
+  const unsigned char* ebase = reinterpret_cast<const unsigned char*>(wv.base + (size_t)ti.se * wv.expert_stride);
+  float* out = yp + (size_t)split * slab_stride;
+
+  const int lrow = lane >> 3, lpp = lane & 7;
+  const uint16_t* a_src[S::ALD];
+#pragma unroll
+  for (int i = 0; i < S::ALD; ++i) {
+    const int lr = w * (BM / 8) + i * 8 + lrow;
+    int row = ti.row0 + lr;
+    row = row < ti.row_end ? row : ti.row_end - 1;
+    a_src[i] = hact + (size_t)row * ldh + wv.col0 + ((lpp ^ ((lr >> 1) & 7)) * 8);
+  }
+  auto issue_a = [&](int stage, int kt) {
+    unsigned char* sa = lds + stage * S::STAGE + w * (BM / 8) * 128;
+#pragma unroll
+    for (int i = 0; i < S::ALD; ++i)
+      __builtin_amdgcn_global_load_lds(SI_GPTR(a_src[i] + (c_begin + kt) * CHUNK_J), SI_LPTR(sa + i * 1024), 16, 0, 0);
+  };
+  // B: thread = (output column n0 + (w%4)*64 + lane, j-half w/4): its 16 bytes of codes are the 32 hidden columns
+  // of the half for that output column, i.e. the pieces 4*half .. +3 of the column in the [piece][column] B stage
+  const int NW = ntile_width(M);
+  const int half = w >> 2, col = (w & 3) * 64 + lane;
+  const int n = min(n0 + col, M - 1);
+  const size_t qoff = q4_off_codes(2, M) + (((size_t)(n / NW) * 2 + half) * NW + (n % NW)) * 16;
+  const size_t zoff = q4_off_scales(2, M) + (size_t)n * 2;
+  const size_t cbytes = q4_chunk_u16(M) * 2;
+  auto bload = [&](int kt, u32x4& q, uint32_t& z) {
+    const unsigned char* cb = ebase + (size_t)(wv.chunk0 + c_begin + kt) * cbytes;
+    gload_b128(q, cb + qoff);
+    gload_u16(z, cb + zoff);
+  };
+  // word i = hidden columns 8i .. 8i+7 of the half; even nibbles hold elements 0 1 2 3, odd nibbles 4 5 6 7
+  auto bconv = [&](int stage, const u32x4& q, uint32_t z, int i) {
+    const float sc = __uint_as_float(z << 16), s8 = -8.f * sc;
+    const uint32_t wd = q[i], ev = wd & 0x0f0f0f0fu, od = (wd >> 4) & 0x0f0f0f0fu;
+    u32x4 o;
+    o.x = q4_pair(ev, 0, 1, sc, s8);
+    o.y = q4_pair(ev, 2, 3, sc, s8);
+    o.z = q4_pair(od, 0, 1, sc, s8);
+    o.w = q4_pair(od, 2, 3, sc, s8);
+    lds_store_b128(lds + stage * S::STAGE + BM * 128 + ((half * 4 + i) * BN + col) * 16, o);
+  };
+  if (c_begin < c_end) {
+    SI_GEMM_MAIN_LOOP_Q4(c_end - c_begin, issue_a, bload, bconv, SI_BOFF_K8)
+#pragma unroll
+    for (int i = 0; i < S::FA; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const int m = n0 + wc * 64 + j * 32 + (lane & 31);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int row = ti.row0 + wr * (BM / 2) + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+          if (row < ti.row_end && m < M) {
+            float* dst = out + (size_t)row * M + m;
+            *dst = accumulate ? *dst + acc[i][j][r] : acc[i][j][r];
+          }
+        }
+      }
+  } else {
+    for (int i = tid; i < BM * BN; i += THREADS) {
+      const int row = ti.row0 + i / BN, m = n0 + i % BN;
+      if (row < ti.row_end && m < M) out[(size_t)row * M + m] = 0.f;
+    }
+  }
+}
+
+__global__ __launch_bounds__(THREADS, 1) void k_prefill_down_q4(const uint16_t* __restrict__ hact, int ldh, int M, Plan p,
+                                                                int expert_sel, int x2_only, int n_cu,
+                                                                int n_ntiles, int n_split, WeightView wv,
+                                                                float* __restrict__ yp, size_t slab_stride,
+                                                                int accumulate) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+  int inner;
+  TileInfo ti;
+  if (!block_tile(p, expert_sel, x2_only, n_ntiles * n_split, n_cu, inner, ti)) return;
+  if (!storage_index(wv, ti.e, ti.se)) return;
+#define SI_CALL_DN(BMV) down_body_q4<BMV>(hact, ldh, M, inner, ti, n_ntiles, n_split, wv, yp, slab_stride, accumulate, lds)
+  SI_PICK_BODY(ti.row_end - ti.row0, SI_CALL_DN);
+#undef SI_CALL_DN
+}
+
 __global__ __launch_bounds__(256) void k_prefill_combine(const float* __restrict__ yp, size_t slab_stride, int n_split,
                                                          const float* __restrict__ ycc, int T, int k, int M, int n_x1,
                                                          int has_shared, Plan p, float* __restrict__ y) {
@@ -455,9 +741,13 @@ static int grid_blocks(int n_tiles) { return (n_tiles + 7) / 8 * 8 + 8 + cu_coun
 
 static hipError_t ensure_lds_attr() {
   static hipError_t st = [] {
-    hipError_t e = hipFuncSetAttribute((const void*)k_prefill_gateup, hipFuncAttributeMaxDynamicSharedMemorySize, KERNEL_LDS);
-    if (e != hipSuccess) return e;
-    return hipFuncSetAttribute((const void*)k_prefill_down, hipFuncAttributeMaxDynamicSharedMemorySize, KERNEL_LDS);
+    const void* kernels[] = {(const void*)k_prefill_gateup, (const void*)k_prefill_down, (const void*)k_prefill_gateup_q4,
+                             (const void*)k_prefill_down_q4};
+    for (const void* k : kernels) {
+      hipError_t e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, KERNEL_LDS);
+      if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
   }();
   return st;
 }
@@ -470,8 +760,12 @@ hipError_t launch_prefill_gateup(const uint16_t* x, int M, const Plan& plan, int
   if (e != hipSuccess) return e;
   const int n_ctiles = (wv.n_chunks + 1) / 2;
   const int total = grid_blocks(n_row_tiles * n_ctiles);
-  hipLaunchKernelGGL(k_prefill_gateup, dim3(total), dim3(THREADS), KERNEL_LDS, stream, x, M, plan, expert_sel, x2_only,
-                     cu_count(), n_ctiles, wv, hact, ldh);
+  if (wv.q4)
+    hipLaunchKernelGGL(k_prefill_gateup_q4, dim3(total), dim3(THREADS), KERNEL_LDS, stream, x, M, plan, expert_sel, x2_only,
+                       cu_count(), n_ctiles, wv, hact, ldh);
+  else
+    hipLaunchKernelGGL(k_prefill_gateup, dim3(total), dim3(THREADS), KERNEL_LDS, stream, x, M, plan, expert_sel, x2_only,
+                       cu_count(), n_ctiles, wv, hact, ldh);
   return hipGetLastError();
 }
 
@@ -483,8 +777,12 @@ hipError_t launch_prefill_down(const uint16_t* hact, int ldh, int M, const Plan&
   if (e != hipSuccess) return e;
   const int n_ntiles = (M + BN - 1) / BN;
   const int total = grid_blocks(n_row_tiles * n_ntiles * n_split);
-  hipLaunchKernelGGL(k_prefill_down, dim3(total), dim3(THREADS), KERNEL_LDS, stream, hact, ldh, M, plan, expert_sel,
-                     x2_only, cu_count(), n_ntiles, n_split, wv, yp, slab_stride, accumulate);
+  if (wv.q4)
+    hipLaunchKernelGGL(k_prefill_down_q4, dim3(total), dim3(THREADS), KERNEL_LDS, stream, hact, ldh, M, plan, expert_sel,
+                       x2_only, cu_count(), n_ntiles, n_split, wv, yp, slab_stride, accumulate);
+  else
+    hipLaunchKernelGGL(k_prefill_down, dim3(total), dim3(THREADS), KERNEL_LDS, stream, hact, ldh, M, plan, expert_sel,
+                       x2_only, cu_count(), n_ntiles, n_split, wv, yp, slab_stride, accumulate);
   return hipGetLastError();
 }
 

@@ -94,6 +94,31 @@ def test_shared_expert_and_odd_width_q4(oracle, split):
         L.close()
 
 
+@pytest.mark.parametrize("split", [(1.0, 0.0, 0.0), (0.4, 0.3, 0.3)])
+def test_two_pass_prompt_phase_q4(oracle, split):
+    """deq_mib > 0: the prompt phase goes through a dequantisation kernel and the bf16 GEMMs instead of the GEMMs
+    that read the codes; a 1 MiB scratch forces several sub-pieces per part.  Same bar, and close to the default."""
+    for name, kw in (("llama2_70b", dict(d_model=512, d_ff=1792)), ("mixtral_8x7b", dict(d_model=512, d_ff=1024))):
+        cfg = synth.scaled(synth.CONFIGS[name], **kw)
+        wq = synth.make_weights_q4(cfg)
+        xp = synth.make_tokens(cfg, 300)
+        lg = synth.make_router_logits(cfg, xp)
+        yo = oracle.layer_forward_q4(xp, wq, logits=lg, top_k=cfg.top_k)
+        outs = []
+        for deq_mib in (1, 0):
+            L = Q4Layer(cfg, wq, split, max_tokens=300, stage_mib=1, deq_mib=deq_mib)
+            try:
+                for n_g in (0, 120):
+                    y = L.forward(xp, lg, n_g=n_g)
+                    assert_parity(y, yo)
+                outs.append(y)
+            finally:
+                L.close()
+        # both paths multiply by the same bf16((code - 8) * scale): they differ only in the order of fp32 sums
+        rms = float(np.sqrt(np.mean(yo ** 2)))
+        assert np.max(np.abs(outs[0] - outs[1])) <= 1e-3 * rms
+
+
 def test_full_size_mixtral_q4(oracle):
     """Mixtral-8x7B-shaped layer at full size, 50/50/0: decode on all tokens, prefill on sampled tokens."""
     cfg = synth.CONFIGS["mixtral_8x7b"]
