@@ -177,9 +177,10 @@ def kernel_table(si, cfg, info, wl, stats, steps, n_g, q4=False):
       prefill gateup: (token, expert) pairs x part columns x M x 4 flop ; weight bytes as above
       prefill down  : pairs x part columns x M x 2 flop
     Columns of the CC part count only when they run on the GPU (CG', the n_g tokens of X2).
-    4-bit weights: the decode kernels read 0.5 B of codes + 2/64 B of scales per weight; the prefill GEMMs read the
-    bf16 copies made by the dequantisation kernel (whose time is in the "fill" class)."""
+    4-bit weights: every kernel reads 0.5 B of codes + 2/64 B of scales per weight; with --deq-mib > 0 the prefill
+    GEMMs read the bf16 copies made by the dequantisation kernel instead (whose time is in the "fill" class)."""
     wb_dec = 0.5 + 2.0 / 64 if q4 else 2.0
+    wb_pre = wb_dec if (q4 and DEQ_MIB == 0) else 2.0
     M, H, Hs, k = cfg.d_model, cfg.d_ff, cfg.d_ff_shared, cfg.top_k
     gpu_cols = info["n_gg"] + info["n_cg"]
     gpu_cols_s = info["s_gg"] + info["s_cg"]
@@ -193,7 +194,7 @@ def kernel_table(si, cfg, info, wl, stats, steps, n_g, q4=False):
     ntp = Workload.touched(cfg, wl.lp)
     cc_cols_gpu = info["n_cc"] if n_g > 0 else 0
     cc_cols_gpu_s = info["s_cc"] if n_g > 0 else 0
-    pre_w_gu = (ntp * (gpu_cols + cc_cols_gpu) + gpu_cols_s + cc_cols_gpu_s) * M * 2 * 2
+    pre_w_gu = (ntp * (gpu_cols + cc_cols_gpu) + gpu_cols_s + cc_cols_gpu_s) * M * 2 * wb_pre
     pre_w_dn = pre_w_gu / 2
     pairs = T * k
     flop_gu = (pairs * gpu_cols + T * gpu_cols_s + n_g * k * info["n_cc"] + n_g * info["s_cc"]) * M * 4.0

@@ -170,7 +170,8 @@ __device__ inline bool block_tile(const Plan& p, int expert_sel, int x2_only, in
 // last 8 MFMAs of this iteration run; the wait before the barrier leaves the NST-2 youngest tiles in
 // flight.
 // ---------------------------------------------------------------------------------------------
-#define SI_GEMM_MAIN_LOOP(NK, ISSUE, BFRAG_OFF)                                                                  \
+// accumulators, operand fragments and the two lambdas every variant of the main loop uses
+#define SI_GEMM_DECLS(BFRAG_OFF)                                                                                 \
   f32x16 acc[S::FA][2];                                                                                          \
   _Pragma("unroll") for (int i = 0; i < S::FA; ++i) _Pragma("unroll") for (int j = 0; j < 2; ++j)                \
       _Pragma("unroll") for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;                                         \
@@ -187,7 +188,9 @@ __device__ inline bool block_tile(const Plan& p, int expert_sel, int x2_only, in
   auto mma = [&](int buf) {                                                                                      \
     _Pragma("unroll") for (int i = 0; i < S::FA; ++i) _Pragma("unroll") for (int j = 0; j < 2; ++j)              \
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[buf][i], fb[buf][j], acc[i][j], 0, 0, 0);         \
-  };                                                                                                             \
+  };
+
+#define SI_GEMM_MAIN_LOOP(NK, ISSUE)                                                                  \
   {                                                                                                              \
     const int nk_ = (NK);                                                                                        \
     _Pragma("unroll") for (int s0 = 0; s0 < S::NST; ++s0) if (s0 < nk_) ISSUE(s0, s0);                           \
@@ -221,7 +224,7 @@ __device__ inline void gload_b128(u32x4& q, const void* p) {
 __device__ inline void gload_u16(uint32_t& z, const void* p) {
   asm volatile("global_load_ushort %0, %1, off" : "=v"(z) : "v"(p) : "memory");
 }
-#define SI_BREADY(q, z) asm volatile("" : "+v"(q), "+v"(z)::"memory")
+struct Q4Regs { u32x4 q; uint32_t z; };  // codes and scale of one lane's share of a B tile
 
 // The same loop for weights in the 4-bit storage form.  The A operand still arrives by direct global->LDS loads;
 // the B operand cannot (it has to be turned into bf16 on the way), so every lane fetches 16 bytes of codes (32
@@ -235,57 +238,41 @@ __device__ inline void gload_u16(uint32_t& z, const void* p) {
 // direct-to-LDS loads in flight the compiler's own wait before the first use of a loaded register is vmcnt(0),
 // which would drain the ring every iteration; BREADY ties the registers to the explicit wait so that no use is
 // scheduled above it.
-#define SI_GEMM_MAIN_LOOP_Q4(NK, ISSUE_A, BLOAD, BCONV, BFRAG_OFF)                                               \
-  f32x16 acc[S::FA][2];                                                                                          \
-  _Pragma("unroll") for (int i = 0; i < S::FA; ++i) _Pragma("unroll") for (int j = 0; j < 2; ++j)                \
-      _Pragma("unroll") for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;                                         \
-  bf16x8 fa[2][S::FA], fb[2][2];                                                                                 \
-  auto ldfrag = [&](int stage, int ks, int buf) {                                                                \
-    const unsigned char* sa = lds + stage * S::STAGE;                                                            \
-    const unsigned char* sb = sa + BM * 128;                                                                     \
-    const int pc = ks * 2 + (lane >> 5);                                                                         \
-    _Pragma("unroll") for (int i = 0; i < S::FA; ++i) fa[buf][i] = as_bf16x8(                                    \
-        *reinterpret_cast<const u32x4*>(sa + swz(wr * (BM / 2) + i * 32 + (lane & 31), pc)));                    \
-    _Pragma("unroll") for (int j = 0; j < 2; ++j) fb[buf][j] = as_bf16x8(                                        \
-        *reinterpret_cast<const u32x4*>(sb + BFRAG_OFF(wc * 64 + j * 32 + (lane & 31), pc)));                    \
-  };                                                                                                             \
-  auto mma = [&](int buf) {                                                                                      \
-    _Pragma("unroll") for (int i = 0; i < S::FA; ++i) _Pragma("unroll") for (int j = 0; j < 2; ++j)              \
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[buf][i], fb[buf][j], acc[i][j], 0, 0, 0);         \
-  };                                                                                                             \
+#define SI_GEMM_MAIN_LOOP_REGB(NK, GLN, BREGS, ISSUE_A, BLOAD, BREADY, BCONV)                                    \
   {                                                                                                              \
-    constexpr int GL = 2; /* register loads per B tile and lane: codes, scale */                                 \
+    constexpr int GL = (GLN); /* register loads per B tile and lane */                                           \
     const int nk_ = (NK);                                                                                        \
-    u32x4 qa, qb;                                                                                                \
-    uint32_t za, zb;                                                                                             \
+    BREGS ra, rb;                                                                                                \
     _Pragma("unroll") for (int s0 = 0; s0 < S::NST; ++s0) if (s0 < nk_) ISSUE_A(s0, s0);                         \
     _Pragma("unroll") for (int s0 = 0; s0 < S::NST - 1; ++s0) if (s0 < nk_) {                                    \
-      BLOAD(s0, qa, za);                                                                                         \
+      BLOAD(s0, ra);                                                                                             \
       wait_vmcnt<0>();                                                                                           \
-      SI_BREADY(qa, za);                                                                                         \
-      _Pragma("unroll") for (int i = 0; i < 4; ++i) BCONV(s0, qa, za, i);                                        \
+      BREADY(ra);                                                                                                \
+      _Pragma("unroll") for (int i = 0; i < 4; ++i) BCONV(s0, ra, i);                                            \
     }                                                                                                            \
-    BLOAD(min(S::NST - 1, nk_ - 1), qa, za);                                                                     \
+    BLOAD(min(S::NST - 1, nk_ - 1), ra);                                                                         \
     wait_vmcnt<0>();                                                                                             \
-    SI_BREADY(qa, za);                                                                                           \
+    BREADY(ra);                                                                                                  \
     wait_lgkmcnt0();                                                                                             \
     block_barrier();                                                                                             \
     ldfrag(0, 0, 0);                                                                                             \
     int st = 0;                                                                                                  \
-    /* one iteration; the codes it converts sit in (qc, zc), those it fetches go to (qn, zn): the loop below  */ \
+    /* one iteration; the registers it converts are rc, those it fetches go to rn: the loop below            */ \
     /* alternates two register sets, so that no fetched register is copied while its load is in flight        */ \
-    auto step = [&](int it, u32x4& qc, uint32_t& zc, u32x4& qn, uint32_t& zn) {                                  \
+    auto step = [&](int it, BREGS& rc, BREGS& rn) {                                                              \
       const int nx = st + 1 == S::NST ? 0 : st + 1;                                                              \
       const int pv = st == 0 ? S::NST - 1 : st - 1;                                                              \
       const bool fill = it + S::NST - 1 < nk_; /* B of tile it+NST-1 goes into stage pv during this iteration */ \
       /* always issued (index clamped), so that the wait below sees the same number of younger operations */     \
-      BLOAD(min(it + S::NST, nk_ - 1), qn, zn);                                                                  \
+      BLOAD(min(it + S::NST, nk_ - 1), rn);                                                                      \
       ldfrag(st, 1, 1); mma(0);                                                                                  \
-      /* (qc, zc) were fetched at the top of the previous iteration; younger: that iteration's A loads, the   */ \
-      /* fetch above                                                                                           */ \
-      if (fill) { wait_vmcnt<S::ALD + GL>(); SI_BREADY(qc, zc); BCONV(pv, qc, zc, 0); }                          \
-      ldfrag(st, 2, 0); mma(1); if (fill) BCONV(pv, qc, zc, 1);                                                  \
-      ldfrag(st, 3, 1); mma(0); if (fill) { BCONV(pv, qc, zc, 2); BCONV(pv, qc, zc, 3); }                        \
+      /* rc was fetched at the top of the previous iteration; younger: that iteration's A loads, the          */ \
+      /* fetch above.  Past the last tile the conversion runs on whatever the clamped fetch brought and      */ \
+      /* writes a stage nobody reads again: straight-line code, so that the scheduler can place the          */ \
+      /* conversion arithmetic between the matrix instructions                                               */ \
+      wait_vmcnt<S::ALD + GL>(); BREADY(rc); BCONV(pv, rc, 0);                                                   \
+      ldfrag(st, 2, 0); mma(1); BCONV(pv, rc, 1);                                                                \
+      ldfrag(st, 3, 1); mma(0); BCONV(pv, rc, 2); BCONV(pv, rc, 3);                                              \
       /* the A loads of tile it+1 must have landed, the B pieces written above and every read of stage st  */    \
       /* must be complete before the barrier; younger than those A loads are the operations of NST-2 whole  */    \
       /* iterations and this iteration's register loads                                                     */    \
@@ -300,8 +287,8 @@ __device__ inline void gload_u16(uint32_t& z, const void* p) {
       st = nx;                                                                                                   \
     };                                                                                                           \
     for (int it = 0; it < nk_; it += 2) {                                                                        \
-      step(it, qa, za, qb, zb);                                                                                  \
-      if (it + 1 < nk_) step(it + 1, qb, zb, qa, za);                                                            \
+      step(it, ra, rb);                                                                                          \
+      if (it + 1 < nk_) step(it + 1, rb, ra);                                                                    \
     }                                                                                                            \
   }
 
@@ -377,7 +364,8 @@ __device__ __forceinline__ void gateup_body(const uint16_t* __restrict__ x, int 
                                        SI_LPTR(sb + i * 1024), 16, 0, 0);
     }
   };
-  SI_GEMM_MAIN_LOOP(M / BK, issue, SI_BOFF_SWZ)
+  SI_GEMM_DECLS(SI_BOFF_SWZ)
+  SI_GEMM_MAIN_LOOP(M / BK, issue)
   // epilogue: element (row 8*(r/4) + 4*(lane/32) + r%4, column lane%32) of each 32x32 tile;
   // acc[i][0] is the gate tile and acc[i][1] the up tile of the same 32 hidden columns
   const int jl = wc * 32 + (lane & 31);  // hidden column inside the 128-column tile
@@ -467,7 +455,8 @@ __device__ __forceinline__ void down_body(const uint16_t* __restrict__ hact, int
       __builtin_amdgcn_global_load_lds(SI_GPTR(dblk + b_off[i]), SI_LPTR(sb + i * 1024), 16, 0, 0);
   };
   if (c_begin < c_end) {
-    SI_GEMM_MAIN_LOOP(c_end - c_begin, issue, SI_BOFF_K8)
+    SI_GEMM_DECLS(SI_BOFF_K8)
+    SI_GEMM_MAIN_LOOP(c_end - c_begin, issue)
 #pragma unroll
     for (int i = 0; i < S::FA; ++i)
 #pragma unroll
@@ -545,15 +534,16 @@ __device__ __forceinline__ void gateup_body_q4(const uint16_t* __restrict__ x, i
   const uint16_t* zrow = reinterpret_cast<const uint16_t*>(cb + q4_off_scales(w & 1, M)) + (size_t)jc * (M / 64);
   const int brow = w * 32 + (lane >> 1);
   const int bsw = (brow >> 1) & 7;
-  auto bload = [&](int kt, u32x4& q, uint32_t& z) {
-    gload_b128(q, qrow + (size_t)kt * 32);
-    gload_u16(z, zrow + kt);
+  auto bload = [&](int kt, Q4Regs& r) {
+    gload_b128(r.q, qrow + (size_t)kt * 32);
+    gload_u16(r.z, zrow + kt);
   };
+  auto bready = [&](Q4Regs& r) { asm volatile("" : "+v"(r.q), "+v"(r.z)::"memory"); };
   // word i of the lane's codes = elements 8i .. 8i+7 of its half row; even nibbles hold elements 0 4 1 5, odd
   // nibbles 2 6 3 7 (cc_worker.h)
-  auto bconv = [&](int stage, const u32x4& q, uint32_t z, int i) {
-    const float sc = __uint_as_float(z << 16), s8 = -8.f * sc;
-    const uint32_t wd = q[i], ev = wd & 0x0f0f0f0fu, od = (wd >> 4) & 0x0f0f0f0fu;
+  auto bconv = [&](int stage, const Q4Regs& r, int i) {
+    const float sc = __uint_as_float(r.z << 16), s8 = -8.f * sc;
+    const uint32_t wd = r.q[i], ev = wd & 0x0f0f0f0fu, od = (wd >> 4) & 0x0f0f0f0fu;
     u32x4 o;
     o.x = q4_pair(ev, 0, 2, sc, s8);
     o.y = q4_pair(od, 0, 2, sc, s8);
@@ -561,7 +551,8 @@ __device__ __forceinline__ void gateup_body_q4(const uint16_t* __restrict__ x, i
     o.w = q4_pair(od, 1, 3, sc, s8);
     lds_store_b128(lds + stage * S::STAGE + BM * 128 + brow * 128 + (((kh * 4 + i) ^ bsw) << 4), o);
   };
-  SI_GEMM_MAIN_LOOP_Q4(M / BK, issue_a, bload, bconv, SI_BOFF_SWZ)
+  SI_GEMM_DECLS(SI_BOFF_SWZ)
+  SI_GEMM_MAIN_LOOP_REGB(M / BK, 2, Q4Regs, issue_a, bload, bready, bconv)
   const int jl = wc * 32 + (lane & 31);
   if (2 * tc + (jl >> 6) < wv.n_chunks) {
     const int col = wv.col0 + tc * 128 + jl;
@@ -626,15 +617,16 @@ __device__ __forceinline__ void down_body_q4(const uint16_t* __restrict__ hact, 
   const size_t qoff = q4_off_codes(2, M) + (((size_t)(n / NW) * 2 + half) * NW + (n % NW)) * 16;
   const size_t zoff = q4_off_scales(2, M) + (size_t)n * 2;
   const size_t cbytes = q4_chunk_u16(M) * 2;
-  auto bload = [&](int kt, u32x4& q, uint32_t& z) {
+  auto bload = [&](int kt, Q4Regs& r) {
     const unsigned char* cb = ebase + (size_t)(wv.chunk0 + c_begin + kt) * cbytes;
-    gload_b128(q, cb + qoff);
-    gload_u16(z, cb + zoff);
+    gload_b128(r.q, cb + qoff);
+    gload_u16(r.z, cb + zoff);
   };
+  auto bready = [&](Q4Regs& r) { asm volatile("" : "+v"(r.q), "+v"(r.z)::"memory"); };
   // word i = hidden columns 8i .. 8i+7 of the half; even nibbles hold elements 0 1 2 3, odd nibbles 4 5 6 7
-  auto bconv = [&](int stage, const u32x4& q, uint32_t z, int i) {
-    const float sc = __uint_as_float(z << 16), s8 = -8.f * sc;
-    const uint32_t wd = q[i], ev = wd & 0x0f0f0f0fu, od = (wd >> 4) & 0x0f0f0f0fu;
+  auto bconv = [&](int stage, const Q4Regs& r, int i) {
+    const float sc = __uint_as_float(r.z << 16), s8 = -8.f * sc;
+    const uint32_t wd = r.q[i], ev = wd & 0x0f0f0f0fu, od = (wd >> 4) & 0x0f0f0f0fu;
     u32x4 o;
     o.x = q4_pair(ev, 0, 1, sc, s8);
     o.y = q4_pair(ev, 2, 3, sc, s8);
@@ -643,7 +635,8 @@ __device__ __forceinline__ void down_body_q4(const uint16_t* __restrict__ hact, 
     lds_store_b128(lds + stage * S::STAGE + BM * 128 + ((half * 4 + i) * BN + col) * 16, o);
   };
   if (c_begin < c_end) {
-    SI_GEMM_MAIN_LOOP_Q4(c_end - c_begin, issue_a, bload, bconv, SI_BOFF_K8)
+    SI_GEMM_DECLS(SI_BOFF_K8)
+    SI_GEMM_MAIN_LOOP_REGB(c_end - c_begin, 2, Q4Regs, issue_a, bload, bready, bconv)
 #pragma unroll
     for (int i = 0; i < S::FA; ++i)
 #pragma unroll
