@@ -174,8 +174,8 @@ int si_place_experts(const double* freq, int32_t n_experts, int32_t n_gg, double
  * Everything else (slicing, placement, forward, stats) is as for si_layer_create; the parts keep the 4-bit
  * form in HBM, in pinned memory and on the host link (102*d_model bytes per 64 hidden columns instead of
  * 384*d_model).  Generation-phase kernels and the host workers multiply codes and scales in fp32 (exact); the
- * prompt-phase GEMMs run on bf16 copies of the weights made piece by piece on the GPU, (c - 8) * scale
- * rounded to bf16.
+ * prompt-phase GEMMs read the same chunks and feed the matrix cores (c - 8) * scale rounded to bf16, converted
+ * on the way into LDS (or, with desc->deq_mib > 0, by a separate pass into a bf16 scratch).
  */
 typedef struct {
   const uint8_t* q_gate;
