@@ -240,6 +240,21 @@ int si_layer_forward(si_layer_t* layer, const void* x_dev, const float* logits_d
 int si_route(const float* logits_dev, int32_t T, int32_t E, int32_t k, const si_routing_out_t* out,
              void* stream);
 
+/*
+ * si_route for callers that cannot allocate device memory: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments, same results.  Where si_route takes a stream-ordered
+ * temporary for the idx / w tables that the caller does not ask for, this call uses a fixed array that lives in
+ * the library's device image (2 * 4 * SI_ROUTE_NOALLOC_MAX_PAIRS bytes = 1 MiB on every GPU the library runs on,
+ * held until the process ends) and calls no allocating routine.
+ * Limits: T * k <= SI_ROUTE_NOALLOC_MAX_PAIRS, else SI_EINVAL.  Runs on the current HIP device.
+ * All calls on one GPU share that GPU's array: two calls that overlap on one GPU (different streams, or threads)
+ * race unless both pass idx and w themselves; calls ordered on one stream are safe.  The array keeps the previous
+ * call's contents; every entry a call reads was written by that call first.
+ */
+#define SI_ROUTE_NOALLOC_MAX_PAIRS 131072
+int si_route_noalloc(const float* logits_dev, int32_t T, int32_t E, int32_t k, const si_routing_out_t* out,
+                     void* stream);
+
 /* Timings and byte counts of the last forward call; synchronises the layer's events. */
 int si_layer_stats(si_layer_t* layer, si_stats_t* out);
 

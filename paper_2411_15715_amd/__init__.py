@@ -16,8 +16,9 @@ LIB_PATH = os.path.join(_HERE, "libscheinfer.so")
 SI_OK, SI_EINVAL, SI_ENOMEM, SI_EHIP, SI_ESTATE = 0, -1, -2, -3, -4
 SI_AUTO, SI_DECODE, SI_PREFILL = 0, 1, 2
 SI_DECODE_AUTO_T, SI_DECODE_AUTO_ROWS, SI_DECODE_MAX_T = 8, 4, 16
+SI_ROUTE_NOALLOC_MAX_PAIRS = 131072
 
-EXPORTS = ["si_layer_create", "si_layer_split_info", "si_split_counts", "si_layer_forward", "si_route",
+EXPORTS = ["si_layer_create", "si_layer_split_info", "si_split_counts", "si_layer_forward", "si_route", "si_route_noalloc",
            "si_layer_stats", "si_layer_set_profiling", "si_repack_chunks", "si_cc_compute", "si_layer_destroy", "si_last_error", "si_version",
            "si_stack_create", "si_stack_forward", "si_stack_destroy",
            "si_layer_create_q4", "si_repack_chunks_q4", "si_cc_compute_q4", "si_layer_create_placed", "si_place_experts", "si_layer_resplit",
@@ -127,6 +128,8 @@ def lib():
         L.si_layer_forward.argtypes = [vp, vp, vp, i32, i32, i32, vp, ctypes.POINTER(si_routing_out_t), vp]
         L.si_route.restype = ctypes.c_int
         L.si_route.argtypes = [vp, i32, i32, i32, ctypes.POINTER(si_routing_out_t), vp]
+        L.si_route_noalloc.restype = ctypes.c_int
+        L.si_route_noalloc.argtypes = [vp, i32, i32, i32, ctypes.POINTER(si_routing_out_t), vp]
         L.si_layer_stats.restype = ctypes.c_int
         L.si_layer_stats.argtypes = [vp, ctypes.POINTER(si_stats_t)]
         L.si_layer_set_profiling.restype = ctypes.c_int
@@ -305,6 +308,11 @@ def si_layer_forward(layer, x_ptr, logits_ptr, T, n_g, mode, y_ptr, routing_out=
 
 def si_route(logits_ptr, T, E, k, routing_out, stream=0):
     _check(lib().si_route(logits_ptr, T, E, k, _routing(routing_out), stream))
+
+
+def si_route_noalloc(logits_ptr, T, E, k, routing_out, stream=0):
+    """si_route without any device allocation (fixed scratch; T * k <= SI_ROUTE_NOALLOC_MAX_PAIRS)."""
+    _check(lib().si_route_noalloc(logits_ptr, T, E, k, _routing(routing_out), stream))
 
 
 def si_layer_set_profiling(layer, on):

@@ -12,7 +12,7 @@ OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libscheinfer.so")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
-HIP_SOURCES = ["route.hip", "decode.hip", "prefill.hip", "layer.hip", "profiler.hip", "q4.hip", "peaks.hip"]
+HIP_SOURCES = ["route.hip", "route_static.hip", "decode.hip", "prefill.hip", "layer.hip", "profiler.hip", "q4.hip", "peaks.hip"]
 CPP_SOURCES = ["cc_worker.cpp", "solver.cpp"]
 HIP_FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang",
              "-packed-fp32-ops", "-Wno-unused-command-line-argument", "-I", os.path.join(ROOT, "include"), "-I", CSRC]
