@@ -1,22 +1,34 @@
 #!/usr/bin/env python3
 """Benchmark of the partitioned FFN/MoE layer on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config mixtral_8x7b] [--split r_gg,r_cg,r_cc]
+    python bench.py [--gpus 1] [--steps K] [--warmup W]                      all five workload shapes, one JSON line
+    python bench.py --config mixtral_8x7b [--split r_gg,r_cg,r_cc] ...       one shape at one split (profiling runs)
 
 A *step* is one pass of the whole hot path over one batch of synthetic input: one prompt-phase
 call (T = the config's prefill length) followed by ``--decode-calls`` generation-phase calls of
 the config's decode batch, each on different tokens (so that decode calls touch different experts
 and no weight byte is served from the 256 MB Infinity Cache).  Inputs are resident in HBM before
-the timed region.  The printed JSON line carries
-  value / ms_per_step   whole-step throughput at the config's own GG/CG/CC split
-  roofline              the dominant kernel (most GPU time in the step) against its roofline,
-                        kernel time from HIP events recorded by the library around every launch
-  gg_only               the same step with all weights resident (100/0/0), per-kernel rooflines
+the timed region.
+
+Without --config the run covers every workload shape at full size in one process.  The headline
+(``value``, ``ms_per_step``, ``roofline``, ``cpu_baseline``) is the largest one, the Mixtral-8x22B-shaped
+layer with all weights resident, timed over exactly K steps after W warm-up steps; ``configs`` holds one
+entry per shape and quoted split (the PhiMoE- and Mixtral-8x22B-shaped layers: all seven splits of the
+sweep 100/0/0 ... 20/60/20) with the step time, tokens/s per phase, every weight kernel against its
+roofline, host-link rate, overlap and the Eq. 6 prediction next to the measured call time; those
+entries are timed over min(K, 3) steps of min(decode calls, 4) decode calls each.
+
+The printed JSON line carries
+  value / ms_per_step   whole-step throughput of the headline workload
+  roofline              its dominant kernel (most GPU time in the step) against its roofline; kernel
+                        time from HIP events recorded by the library around every launch
+  configs               see above
   cpu_baseline          the CPU oracle timed on this machine's host cores on a bounded token sample
 """
 import argparse
 import json
 import os
+import re
 import sys
 import time
 
@@ -27,17 +39,29 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0      # MI355X HBM3E
 MFMA_BF16_PEAK_TF = 2500.0  # dense bf16
+HEADLINE = "mixtral_8x22b"
+TIMER_NOTE = ("kernel time = HIP events recorded by the library on the launch stream around each launch, in a repeat of "
+              "the timed region (an event pair adds about 3 us of launch gap to a kernel's rocprofv3 duration)")
 
-# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE (x2.000, the factor a plain 1 GiB copy gives) plus
-# WRITE_SIZE (x1.000), averaged over the launches of the kernel class in one bench step; the runs and the raw
-# counters are in profiles/mixtral_8x7b_gg_only_hbm_traffic.md.  Keyed by (config, split, kernel class).
-PMC_TRAFFIC = {
-    ("mixtral_8x7b", (0.5, 0.5, 0.0), "decode_gateup"): 153040.2 * 1024 + 56.3 * 1024,
-    ("mixtral_8x7b", (1.0, 0.0, 0.0), "decode_gateup"): 458877.0 * 1024 + 112.5 * 1024,
-    ("mixtral_8x7b", (1.0, 0.0, 0.0), "decode_down"): 230330.2 * 1024 + 512.0 * 1024,
-    ("mixtral_8x7b", (1.0, 0.0, 0.0), "prefill_gateup"): 2103590.4 * 1024 + 28672.0 * 1024,
-    ("mixtral_8x7b", (1.0, 0.0, 0.0), "prefill_down"): 946501.6 * 1024 + 32768.0 * 1024,
-}
+
+def load_pmc_traffic():
+    """HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE and WRITE_SIZE, each scaled by what the same
+    counter reads for a plain copy of known size): the table rows of profiles/hbm_traffic_table.md, keyed by
+    (config, split, kernel class).  Kernels that were not profiled report traffic = null."""
+    out = {}
+    path = os.path.join(ROOT, "profiles", "hbm_traffic_table.md")
+    if not os.path.exists(path):
+        return out
+    for ln in open(path):
+        m = re.match(r"\|\s*(\w+)\s*\|\s*([\d.]+)/([\d.]+)/([\d.]+)\s*\|\s*(\w+)\s*\|\s*([\d.]+)\s*\|\s*([\d.]+)\s*\|", ln)
+        if m:
+            split = tuple(round(float(m.group(i)) / 100.0, 4) for i in (2, 3, 4))
+            # FETCH_SIZE counts half the bytes of a plain copy (factor 2.0), WRITE_SIZE all of them (factor 1.0)
+            out[(m.group(1), split, m.group(5))] = (2.0 * float(m.group(6)) + float(m.group(7))) * 1024.0
+    return out
+
+
+PMC_TRAFFIC = load_pmc_traffic()
 
 
 def parse_args():
@@ -45,7 +69,9 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--config", default="mixtral_8x7b")
+    ap.add_argument("--config", default=None,
+                    help="one workload shape only (tiny_dense, mixtral_8x7b, llama2_70b, qwen_moe, phimoe, mixtral_8x22b); "
+                         "default: all five full-size shapes, headline on the Mixtral-8x22B-shaped layer")
     ap.add_argument("--split", default=None, help="r_gg,r_cg,r_cc (default: the config's)")
     ap.add_argument("--decode-calls", type=int, default=16)
     ap.add_argument("--n-g", type=int, default=-1, help="prefill tokens on CG' (default: all when r_cc > 0)")
@@ -123,49 +149,57 @@ def run_steps(si, layer, wl, n_steps, n_g, stream, collect=None):
                 collect.append(("decode", si.si_layer_stats(layer)))
 
 
-def measure(si, torch, cfg, w, split, wl, steps, warmup, n_g):
-    """Time `steps` steps (profiling off), then repeat them with per-launch events for kernel times."""
+def create_layer(si, cfg, w, split):
     if "q_gate" in w:
-        layer = si.si_layer_create_q4(cfg.d_model, cfg.d_ff, cfg.n_experts, cfg.top_k, w, split[0], split[1], split[2],
-                                      max(cfg.t_prefill, cfg.t_decode), d_ff_shared=cfg.d_ff_shared, deq_mib=DEQ_MIB)
-    else:
-        shared = tuple(w[k] for k in ("s_gate", "s_up", "s_down")) if cfg.d_ff_shared else None
-        layer = si.si_layer_create(cfg.d_model, cfg.d_ff, cfg.n_experts, cfg.top_k, w["w_gate"], w["w_up"], w["w_down"],
-                                   split[0], split[1], split[2], max(cfg.t_prefill, cfg.t_decode),
-                                   d_ff_shared=cfg.d_ff_shared, shared=shared)
+        return si.si_layer_create_q4(cfg.d_model, cfg.d_ff, cfg.n_experts, cfg.top_k, w, split[0], split[1], split[2],
+                                     max(cfg.t_prefill, cfg.t_decode), d_ff_shared=cfg.d_ff_shared, deq_mib=DEQ_MIB)
+    shared = tuple(w[k] for k in ("s_gate", "s_up", "s_down")) if cfg.d_ff_shared else None
+    return si.si_layer_create(cfg.d_model, cfg.d_ff, cfg.n_experts, cfg.top_k, w["w_gate"], w["w_up"], w["w_down"],
+                              split[0], split[1], split[2], max(cfg.t_prefill, cfg.t_decode),
+                              d_ff_shared=cfg.d_ff_shared, shared=shared)
+
+
+def measure_layer(si, torch, layer, wl, steps, warmup, n_g):
+    """Time `steps` steps (profiling off), then repeat them with per-launch events for kernel times."""
+    cfg = wl.cfg
+    info = si.si_layer_split_info(layer)
+    stream = torch.cuda.current_stream().cuda_stream
+    run_steps(si, layer, wl, warmup, n_g, stream)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run_steps(si, layer, wl, steps, n_g, stream)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    # per-phase call time without any event inside the library (back-to-back calls, one sync)
+    reps = max(2, steps)
+    t1 = time.perf_counter()
+    for _ in range(reps):
+        for xd, ld, _lg in wl.dec:
+            si.si_layer_forward(layer, xd.data_ptr(), ld.data_ptr() if ld is not None else None, cfg.t_decode, 0,
+                                si.SI_DECODE, wl.yd.data_ptr(), stream=stream)
+    torch.cuda.synchronize()
+    t_dec = (time.perf_counter() - t1) / (reps * len(wl.dec))
+    t1 = time.perf_counter()
+    for _ in range(reps):
+        si.si_layer_forward(layer, wl.xp.data_ptr(), wl.lp_dev.data_ptr() if wl.lp_dev is not None else None,
+                            cfg.t_prefill, n_g, si.SI_PREFILL, wl.yp.data_ptr(), stream=stream)
+    torch.cuda.synchronize()
+    t_pre = (time.perf_counter() - t1) / reps
+    # same region again with HIP events around every launch (stream-ordered, on the launch stream)
+    si.si_layer_set_profiling(layer, 1)
+    stats = []
+    run_steps(si, layer, wl, steps, n_g, stream, collect=stats)
+    torch.cuda.synchronize()
+    si.si_layer_set_profiling(layer, 0)
+    return elapsed, stats, info, {"decode_call_us": 1e6 * t_dec, "prefill_call_us": 1e6 * t_pre}
+
+
+def measure(si, torch, cfg, w, split, wl, steps, warmup, n_g):
+    layer = create_layer(si, cfg, w, split)
     try:
-        info = si.si_layer_split_info(layer)
-        stream = torch.cuda.current_stream().cuda_stream
-        run_steps(si, layer, wl, warmup, n_g, stream)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        run_steps(si, layer, wl, steps, n_g, stream)
-        torch.cuda.synchronize()
-        elapsed = time.perf_counter() - t0
-        # per-phase call time without any event inside the library (back-to-back calls, one sync)
-        reps = max(2, steps)
-        t1 = time.perf_counter()
-        for _ in range(reps):
-            for xd, ld, _lg in wl.dec:
-                si.si_layer_forward(layer, xd.data_ptr(), ld.data_ptr() if ld is not None else None, cfg.t_decode, 0,
-                                    si.SI_DECODE, wl.yd.data_ptr(), stream=stream)
-        torch.cuda.synchronize()
-        t_dec = (time.perf_counter() - t1) / (reps * len(wl.dec))
-        t1 = time.perf_counter()
-        for _ in range(reps):
-            si.si_layer_forward(layer, wl.xp.data_ptr(), wl.lp_dev.data_ptr() if wl.lp_dev is not None else None,
-                                cfg.t_prefill, n_g, si.SI_PREFILL, wl.yp.data_ptr(), stream=stream)
-        torch.cuda.synchronize()
-        t_pre = (time.perf_counter() - t1) / reps
-        # same region again with HIP events around every launch (stream-ordered, on the launch stream)
-        si.si_layer_set_profiling(layer, 1)
-        stats = []
-        run_steps(si, layer, wl, steps, n_g, stream, collect=stats)
-        torch.cuda.synchronize()
-        si.si_layer_set_profiling(layer, 0)
+        return measure_layer(si, torch, layer, wl, steps, warmup, n_g)
     finally:
         si.si_layer_destroy(layer)
-    return elapsed, stats, info, {"decode_call_us": 1e6 * t_dec, "prefill_call_us": 1e6 * t_pre}
 
 
 def kernel_table(si, cfg, info, wl, stats, steps, n_g, q4=False):
@@ -269,6 +303,10 @@ def roofline_of(name, ent, cfg_name=None, split=None):
     out = {"kernel": name, "bound": ent["bound"], "achieved": round(a, 2), "peak": p, "unit": unit,
            "frac": round(a / p, 4), "traffic": traffic, "avg_launch_us": round(ent["avg_launch_us"], 2),
            "launches_per_step": ent["launches_per_step"]}
+    if traffic:
+        algo = ent["bytes_per_step"] / ent["launches_per_step"]
+        out["algorithmic_bytes_per_launch"] = round(algo, 1)
+        out["traffic_over_algorithmic"] = round(traffic / algo, 4)
     if measured:
         out["measured_peak"] = round(measured, 1)
         out["frac_of_measured_peak"] = round(a / measured, 4)
@@ -605,6 +643,119 @@ def synth_tokens(cfg, T):
     return synth.make_tokens(cfg, T, stream=7)
 
 
+def workload_text(cfg, decode_calls):
+    return ("%s-shaped layer: E=%d top-%d M=%d H=%d%s, step = 1 prefill call of %d tokens + %d decode calls of %d token(s)"
+            % (cfg.name, cfg.n_experts, cfg.top_k, cfg.d_model, cfg.d_ff,
+               (" + shared H=%d" % cfg.d_ff_shared) if cfg.d_ff_shared else "", cfg.t_prefill, decode_calls, cfg.t_decode))
+
+
+def link_of(stats, steps):
+    pre = [st for kind, st in stats if kind == "prefill"]
+    dec = [st for kind, st in stats if kind == "decode"]
+    copied = sum(s["bytes_streamed"] for _, s in stats)
+    copy_ms = sum(s["copy_ms"] for _, s in stats)
+    if copied <= 0:
+        return None
+    return {"GBps": round(copied / (copy_ms / 1e3) / 1e9, 2), "bytes_per_step": copied / steps,
+            "copy_ms_per_step": copy_ms / steps,
+            "overlap_prefill": float(np.mean([s["overlap"] for s in pre])),
+            "overlap_decode": float(np.mean([s["overlap"] for s in dec])),
+            "gg_kernel_time_under_copies_prefill": float(np.mean([s["gg_in_copy"] for s in pre])),
+            "gg_kernel_time_under_copies_decode": float(np.mean([s["gg_in_copy"] for s in dec])),
+            "cc_ms_per_step": sum(s["cc_ms"] for _, s in stats) / steps,
+            "eq6_predicted_prefill_ms": float(np.mean([eq6_prediction(s) for s in pre])),
+            "eq6_predicted_decode_ms": float(np.mean([eq6_prediction(s) for s in dec])),
+            "measured_prefill_ms": float(np.mean([s["total_ms"] for s in pre])),
+            "measured_decode_ms": float(np.mean([s["total_ms"] for s in dec]))}
+
+
+def split_entry(si, cfg, split, n_g, wl, steps, elapsed, stats, info, calls, q4=False):
+    """One row of the `configs` array: a workload shape at one GG/CG/CC split."""
+    ktab = kernel_table(si, cfg, info, wl, stats, steps, n_g, q4=q4)
+    tokens_per_step = cfg.t_prefill + len(wl.dec) * cfg.t_decode
+    ms_per_step = 1e3 * elapsed / steps
+    ent = {"config": cfg.name, "split_gg_cg_cc": [round(v, 4) for v in split], "columns": info, "n_g": n_g,
+           "steps": steps, "decode_calls": len(wl.dec), "ms_per_step": round(ms_per_step, 4),
+           "tokens_per_s": round(tokens_per_step / (ms_per_step / 1e3), 1),
+           "prefill_call_ms": round(calls["prefill_call_us"] / 1e3, 4), "decode_call_us": round(calls["decode_call_us"], 2),
+           "prefill_tokens_per_s": round(cfg.t_prefill / (calls["prefill_call_us"] / 1e6), 1),
+           "decode_tokens_per_s": round(cfg.t_decode / (calls["decode_call_us"] / 1e6), 1)}
+    # the generation-phase call as a whole against the HBM bound of the weight bytes its kernels read
+    if "decode_gateup" in ktab and tuple(split)[0] == 1.0:
+        call_bytes = (ktab["decode_gateup"]["bytes_per_step"] + ktab["decode_down"]["bytes_per_step"]) / len(wl.dec)
+        ent["decode_call_frac_of_hbm_bound"] = round(call_bytes / (calls["decode_call_us"] / 1e6) / (HBM_PEAK_GBS * 1e9), 4)
+    ent["rooflines"] = [roofline_of(k, ktab[k], None if q4 else cfg.name, split) for k in ktab if "bound" in ktab[k]]
+    ent["other_kernels_us"] = {k: round(v["avg_launch_us"], 2) for k, v in ktab.items() if "bound" not in v}
+    link = link_of(stats, steps)
+    if link:
+        ent["host_link"] = {k: (round(v, 4) if isinstance(v, float) else v) for k, v in link.items()}
+    return ent, ktab
+
+
+def all_configs_line(args, si, torch, synth):
+    """Default run: every workload shape at full size; headline on the Mixtral-8x22B-shaped layer."""
+    plan = [("mixtral_8x7b", [(1.0, 0.0, 0.0), (0.5, 0.5, 0.0)]),
+            ("llama2_70b", [(1.0, 0.0, 0.0), (0.3, 0.5, 0.2)]),
+            ("qwen_moe", [(1.0, 0.0, 0.0), (0.5, 0.5, 0.0)]),
+            ("phimoe", list(synth.SPLIT_SWEEP)),
+            (HEADLINE, list(synth.SPLIT_SWEEP))]
+    entries = []
+    head = None
+    t_all = time.perf_counter()
+    for name, splits in plan:
+        cfg = synth.CONFIGS[name]
+        t0 = time.perf_counter()
+        w = synth.make_weights(cfg, threads=min(16, os.cpu_count() or 8))
+        wl_full = Workload(cfg, args.decode_calls)
+        wl_short = Workload(cfg, min(args.decode_calls, 4))
+        t_gen = time.perf_counter() - t0
+        layer = create_layer(si, cfg, w, splits[0])
+        try:
+            for split in splits:
+                if split != splits[0]:
+                    si.si_layer_resplit(layer, *split)
+                n_g = cfg.t_prefill if split[2] > 0 else 0
+                is_head = name == HEADLINE and split == (1.0, 0.0, 0.0)
+                # resident-only splits take microseconds to milliseconds per step: full step count; the link-bound
+                # ones take up to 0.3 s per step and are timed over a few steps of fewer decode calls
+                full = is_head or split == (1.0, 0.0, 0.0)
+                steps = args.steps if full else max(1, min(args.steps, 3))
+                warmup = args.warmup if full else 1
+                wl = wl_full if full else wl_short
+                elapsed, stats, info, calls = measure_layer(si, torch, layer, wl, steps, warmup, n_g)
+                ent, ktab = split_entry(si, cfg, split, n_g, wl, steps, elapsed, stats, info, calls)
+                entries.append(ent)
+                print("bench: %s %s done (%.1f s since start)" % (name, split, time.perf_counter() - t_all), file=sys.stderr, flush=True)
+                if is_head:
+                    weight_kernels = [k for k in ktab if "bound" in ktab[k]]
+                    dominant = max(weight_kernels, key=lambda k: ktab[k]["ms_per_step"])
+                    roof = roofline_of(dominant, ktab[dominant], cfg.name, split)
+                    roof["timer"] = TIMER_NOTE
+                    head = {"ent": ent, "roofline": roof, "elapsed": elapsed, "t_gen": t_gen, "info": info}
+        finally:
+            si.si_layer_destroy(layer)
+        if name == HEADLINE and not args.no_cpu_baseline:
+            head["cpu_baseline"] = cpu_baseline(cfg, w, wl_full, args.cpu_seconds)
+        del w, wl_full, wl_short
+    cfg = synth.CONFIGS[HEADLINE]
+    ms_per_step = 1e3 * head["elapsed"] / args.steps
+    tokens_per_step = cfg.t_prefill + args.decode_calls * cfg.t_decode
+    out = {
+        "metric": "FFN/MoE layer tokens/s (decode+prefill)", "value": round(tokens_per_step / (ms_per_step / 1e3), 2),
+        "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": workload_text(cfg, args.decode_calls), "split_gg_cg_cc": [1.0, 0.0, 0.0],
+                   "columns": head["info"], "n_g": 0, "tokens_per_step": tokens_per_step},
+        "roofline": head["roofline"],
+        "configs": entries,
+        "measured_peaks": {k: (round(v, 1) if isinstance(v, float) else v) for k, v in MEASURED_PEAKS.items()} if MEASURED_PEAKS else None,
+        "bench_wall_s": round(time.perf_counter() - t_all, 1),
+    }
+    if "cpu_baseline" in head:
+        out["cpu_baseline"] = head["cpu_baseline"]
+    print(json.dumps(out))
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -627,6 +778,12 @@ def main():
     DEQ_MIB = args.deq_mib
     if not args.no_peaks:
         MEASURED_PEAKS = si.si_measure_peaks(0)
+    if args.config is None:
+        if args.q4 or args.solve or args.stack or args.place or args.sweep or args.split:
+            print("bench.py: --q4 / --split / --solve / --stack / --place / --sweep need --config", file=sys.stderr)
+            sys.exit(2)
+        all_configs_line(args, si, torch, synth)
+        return
     cfg = synth.CONFIGS[args.config]
     split = tuple(float(v) for v in args.split.split(",")) if args.split else cfg.split
     n_g = args.n_g if args.n_g >= 0 else (cfg.t_prefill if split[2] > 0 else 0)
@@ -664,33 +821,17 @@ def main():
         "prefill_tokens_per_s": cfg.t_prefill / (np.mean([s["total_ms"] for s in pre]) / 1e3),
         "decode_tokens_per_s": cfg.t_decode / (np.mean([s["total_ms"] for s in dec]) / 1e3),
     }
-    link = None
-    copied = sum(s["bytes_streamed"] for _, s in stats)
-    copy_ms = sum(s["copy_ms"] for _, s in stats)
-    if copied > 0:
-        link = {"GBps": round(copied / (copy_ms / 1e3) / 1e9, 2), "bytes_per_step": copied / args.steps,
-                "copy_ms_per_step": copy_ms / args.steps,
-                "overlap_prefill": float(np.mean([s["overlap"] for s in pre])),
-                "overlap_decode": float(np.mean([s["overlap"] for s in dec])),
-                "gg_kernel_time_under_copies_prefill": float(np.mean([s["gg_in_copy"] for s in pre])),
-                "gg_kernel_time_under_copies_decode": float(np.mean([s["gg_in_copy"] for s in dec])),
-                "cc_ms_per_step": sum(s["cc_ms"] for _, s in stats) / args.steps,
-                "eq6_predicted_prefill_ms": float(np.mean([eq6_prediction(s) for s in pre])),
-                "eq6_predicted_decode_ms": float(np.mean([eq6_prediction(s) for s in dec])),
-                "measured_prefill_ms": float(np.mean([s["total_ms"] for s in pre])),
-                "measured_decode_ms": float(np.mean([s["total_ms"] for s in dec]))}
-
+    link = link_of(stats, args.steps)
+    roof = roofline_of(dominant, ktab[dominant], None if args.q4 else cfg.name, split)
+    roof["timer"] = TIMER_NOTE
     out = {
         "metric": "FFN/MoE layer tokens/s (decode+prefill)", "value": round(tokens_per_step / (ms_per_step / 1e3), 2),
         "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int4 weights x bf16 activations, f32 accumulate" if args.q4 else "bf16", "data": "synthetic",
-        "config": {"workload": "%s-shaped layer: E=%d top-%d M=%d H=%d%s, step = 1 prefill call of %d tokens + %d decode "
-                               "calls of %d token(s)" % (cfg.name, cfg.n_experts, cfg.top_k, cfg.d_model, cfg.d_ff,
-                                                         (" + shared H=%d" % cfg.d_ff_shared) if cfg.d_ff_shared else "",
-                                                         cfg.t_prefill, args.decode_calls, cfg.t_decode),
+        "config": {"workload": workload_text(cfg, args.decode_calls),
                    "split_gg_cg_cc": list(split), "columns": info, "n_g": n_g, "tokens_per_step": tokens_per_step},
-        "roofline": roofline_of(dominant, ktab[dominant], None if args.q4 else cfg.name, split),
+        "roofline": roof,
         "phases": {k: round(v, 4) for k, v in phase.items()},
         "kernels": {k: {kk: (round(vv, 4) if isinstance(vv, float) else vv) for kk, vv in v.items()} for k, v in ktab.items()},
         "host_link": link,

@@ -22,7 +22,9 @@
  * Weight layout is [expert][hidden index j][model index m] for gate, up and down alike.
  *
  * Parallelism: "omp parallel for" over independent hidden indices j (step 1) and over blocks of
- * output columns m (step 2).  No blocking, fusion or reordering beyond that.
+ * 256 output columns m (step 2: the m loop is cut into blocks only to hand them to threads; every
+ * y[m] is still the sum over j in ascending j, so the result does not depend on the block size or
+ * the thread count).  No fusion or reordering beyond that.
  */
 #include <math.h>
 #include <stdint.h>

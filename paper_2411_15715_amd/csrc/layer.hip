@@ -193,7 +193,15 @@ struct si_layer {
   // the first pre_n pieces of the CG part, cut for path pre_path, sit in slots pre_slot[0..pre_n)
   int pre_n = 0, pre_path = 0;
   std::vector<int> pre_slot;
-  bool segs_preloaded = false;   // this call's event list already holds the prefetch copies
+  // timing events of the copies issued ahead of a call live in two pools of their own, used alternately: the call
+  // that consumes the pieces merges pre_segs into its own list and flips the pool, so the events its statistics
+  // refer to stay untouched until the prefetch after the next one (the layer's own list and pool are never
+  // touched from another layer's call)
+  std::vector<hipEvent_t> pre_ev_pool[2];
+  size_t pre_ev_used = 0;
+  int pre_cur = 0;
+  std::vector<Seg> pre_segs;
+  bool cc_inflight = false;      // the host workers were started and not yet waited for
   si_layer* chain_next = nullptr;  // layer whose CG copies are issued once this call's own are (set by the stack)
   hipStream_t copy_stream = nullptr;      // Stream-C in use: the layer's own, or its stack's
   hipStream_t own_copy_stream = nullptr;  // the one this layer created and destroys
@@ -381,6 +389,7 @@ void si_layer_destroy(si_layer_t* L) {
   for (auto e : L->ev_ready) if (e) (void)hipEventDestroy(e);
   for (auto e : L->ev_free) if (e) (void)hipEventDestroy(e);
   for (auto e : L->ev_pool) if (e) (void)hipEventDestroy(e);
+  for (auto& pool : L->pre_ev_pool) for (auto e : pool) if (e) (void)hipEventDestroy(e);
   if (L->ev_host) (void)hipEventDestroy(L->ev_host);
   if (L->ev_t0) (void)hipEventDestroy(L->ev_t0);
   if (L->ev_t1) (void)hipEventDestroy(L->ev_t1);
@@ -771,16 +780,26 @@ int prefetch_cg(si_layer* N, int path) {
   HIP_TRY(hipSetDevice(N->device));
   const int piece_max = piece_chunks(N, path, cps_of(N->ch_cg));
   const uint16_t* hbase = N->h_routed;
-  if (N->profiling) { N->ev_used = 0; N->segs.clear(); N->segs_preloaded = true; }
+  N->pre_segs.clear();
+  N->pre_ev_used = 0;
+  auto pre_event = [&]() -> hipEvent_t {
+    auto& pool = N->pre_ev_pool[N->pre_cur];
+    if (N->pre_ev_used == pool.size()) {
+      hipEvent_t e = nullptr;
+      if (hipEventCreate(&e) != hipSuccess) return nullptr;
+      pool.push_back(e);
+    }
+    return pool[N->pre_ev_used++];
+  };
   N->pre_slot.clear();
   for (int c = 0; c < N->ch_cg && (int)N->pre_slot.size() < N->n_stage; c += piece_max) {
     const int n = std::min(piece_max, N->ch_cg - c);
     const int slot = (int)(N->piece_counter++ % N->n_stage);
     if (N->slot_used[slot]) HIP_TRY(hipStreamWaitEvent(N->copy_stream, N->ev_free[slot], 0));
-    {
-      SegScope sc(N, N->copy_stream, SEG_COPY);
-      HIP_TRY(hipMemcpyAsync(N->d_stage[slot], hbase + (size_t)(N->ch_cc + c) * N->ce, (size_t)n * N->ce * 2, hipMemcpyHostToDevice, N->copy_stream));
-    }
+    hipEvent_t ea = N->profiling ? pre_event() : nullptr, eb = ea ? pre_event() : nullptr;
+    if (eb) HIP_TRY(hipEventRecord(ea, N->copy_stream));
+    HIP_TRY(hipMemcpyAsync(N->d_stage[slot], hbase + (size_t)(N->ch_cc + c) * N->ce, (size_t)n * N->ce * 2, hipMemcpyHostToDevice, N->copy_stream));
+    if (eb) { HIP_TRY(hipEventRecord(eb, N->copy_stream)); N->pre_segs.push_back({ea, eb, SEG_COPY, 0}); }
     HIP_TRY(hipEventRecord(N->ev_ready[slot], N->copy_stream));
     N->pre_slot.push_back(slot);
   }
@@ -820,10 +839,28 @@ int si_layer_forward(si_layer_t* L, const void* x_dev, const float* logits_dev, 
   const bool need_sync = need_cc || need_counts;
   const auto wall0 = std::chrono::steady_clock::now();
 
-  if (!L->segs_preloaded) { L->ev_used = 0; L->segs.clear(); }
-  L->segs_preloaded = false;
+  // Whatever way the call ends, nothing of it may outlive it on the host: on an error return the host workers are
+  // waited for (they read hx / hidx / hw, which the next call overwrites) and the prefetch state is dropped.
+  struct ExitGuard {
+    si_layer* L; bool ok = false;
+    ~ExitGuard() {
+      if (ok) return;
+      if (L->cc_inflight) { cc_pool_wait(L->pool); L->cc_inflight = false; }
+      L->pre_n = 0;
+      L->in_staged = 0;
+    }
+  } guard{L};
+  L->ev_used = 0;
+  L->segs.clear();
   L->in_staged = 0;
   if (L->pre_n > 0 && L->pre_path != path) L->pre_n = 0;  // cut for the other path: copy again
+  if (L->pre_n > 0 && !L->pre_segs.empty()) {
+    // the copies issued ahead of this call belong to its statistics; their events stay valid until the prefetch
+    // after the next one (prefetch_cg records into the other pool from now on)
+    L->segs.insert(L->segs.end(), L->pre_segs.begin(), L->pre_segs.end());
+    L->pre_cur ^= 1;
+  }
+  L->pre_segs.clear();
   si_stats_t st{};
   st.path = path;
   st.n_touched = -1;
@@ -837,8 +874,8 @@ int si_layer_forward(si_layer_t* L, const void* x_dev, const float* logits_dev, 
     hipError_t e = launch_route(E > 1 ? logits_dev : nullptr, T, E, k, L->has_shared, n_g, L->plan, u, stream);
     if (e != hipSuccess) return fail(SI_EHIP, "route launch failed: %s", hipGetErrorString(e));
   }
-  // ---- hand-off to the host: X1 and the assignment (Section III-B: "X1 will be additionally
-  //      transferred into CPU"), and the per-expert counts the copy scheduler needs
+  // ---- hand-off to the host: the rows of X1 and the assignment go to the CPU for the CC part (Section III-B),
+  //      and with them the per-expert counts the copy scheduler needs
   if (need_sync) {
     if (need_cc) {
       HIP_TRY(hipMemcpyAsync(L->hx, x, (size_t)n_x1 * M * 2, hipMemcpyDeviceToHost, stream));
@@ -871,6 +908,7 @@ int si_layer_forward(si_layer_t* L, const void* x_dev, const float* logits_dev, 
     } else {
       cc0 = std::chrono::steady_clock::now();
       cc_pool_start(L->pool, job);
+      L->cc_inflight = true;
     }
   }
 
@@ -1039,6 +1077,7 @@ int si_layer_forward(si_layer_t* L, const void* x_dev, const float* logits_dev, 
   if (need_cc) {
     if (L->ch_cc > 0 || (L->has_shared && L->sch_cc > 0)) {
       cc_pool_wait(L->pool);
+      L->cc_inflight = false;
       st.cc_ms = std::chrono::duration<float, std::milli>(std::chrono::steady_clock::now() - cc0).count();
       double b = 0;
       for (int e = 0; e < EX; ++e) if (L->hcount[EX + e] > 0) b += (double)L->e_chunks(e, 2) * ce * 2;
@@ -1070,6 +1109,7 @@ int si_layer_forward(si_layer_t* L, const void* x_dev, const float* logits_dev, 
   st.enqueue_ms = std::chrono::duration<float, std::milli>(std::chrono::steady_clock::now() - wall0).count();
   st.total_ms = st.enqueue_ms;  // replaced by event time in si_layer_stats when profiling is on
   L->last = st;
+  guard.ok = true;
   return SI_OK;
 }
 

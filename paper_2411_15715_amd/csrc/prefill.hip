@@ -40,6 +40,11 @@ template <int BM> struct Shape {
   static constexpr int FA = BM / 64;                      // A fragments (32 rows each) per wave
   static constexpr int ALD = BM / 64;                     // A load instructions per wave per stage
   static constexpr int LPW = ALD + 4;                     // load instructions per wave per stage
+  // Invariant behind every wait_vmcnt<N> of the main loops: between two barriers a wave issues exactly these
+  // vector-memory instructions, in program order, and no others (no spill, no hoisted table load: everything a
+  // loop needs from global memory besides the tiles is fetched before it starts).  ensure_lds_attr() refuses a
+  // build whose kernels use scratch memory, and the GPU tests run every body with fewer, as many and more k-tiles
+  // than stages.
 };
 
 __device__ inline uint16_t f32_to_bf16(float f) {
@@ -739,6 +744,13 @@ static hipError_t ensure_lds_attr() {
     for (const void* k : kernels) {
       hipError_t e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, KERNEL_LDS);
       if (e != hipSuccess) return e;
+      // The main loops count their own vector-memory operations (wait_vmcnt<N> against Shape<>::LPW / ALD): a
+      // register spill would add scratch loads and stores to that count and let a barrier pass before a tile has
+      // landed.  A build whose GEMM kernels use scratch memory is refused here instead of computing wrong results.
+      hipFuncAttributes fa{};
+      e = hipFuncGetAttributes(&fa, k);
+      if (e != hipSuccess) return e;
+      if (fa.localSizeBytes != 0) return hipErrorInvalidDeviceFunction;
     }
     return hipSuccess;
   }();

@@ -90,11 +90,14 @@ def test_qwen_moe_full(oracle):
 
 
 def test_phimoe_full_sweep(oracle):
-    check_config(oracle, "phimoe", [(1.0, 0.0, 0.0), (0.6, 0.3, 0.1), (0.2, 0.6, 0.2)], decode_reps=1, prefill_ng=[-512])
+    # every split of the sweep 100/0/0 ... 20/60/20 at full size: one decode call and one prefill call whose last
+    # T - 512 tokens take the CC share to the GPU (CG') while the host computes the first 512; the oracle
+    # references are computed once and shared by the seven splits
+    check_config(oracle, "phimoe", synth.SPLIT_SWEEP, decode_reps=1, prefill_ng=[-512])
 
 
 def test_mixtral_8x22b_full_sweep(oracle):
-    check_config(oracle, "mixtral_8x22b", [(1.0, 0.0, 0.0), (0.4, 0.4, 0.2)], decode_reps=1, prefill_ng=[-256])
+    check_config(oracle, "mixtral_8x22b", synth.SPLIT_SWEEP, decode_reps=1, prefill_ng=[-256])
 
 
 def test_qwen_moe_full_whole_expert_placement(oracle):

@@ -1,0 +1,53 @@
+"""The LDS ring of the prompt-phase GEMMs synchronises with hand-counted waits on outstanding loads, so every
+body (64, 128, 192, 256 rows; 3 or 2 stages) is run here with fewer k-tiles than stages, as many, and more, in the
+bf16 loop and in the 4-bit loop, against the oracle.  FC1 contracts over d_model (k-tiles = d_model / 64); FC2
+over the hidden columns of one k-split (the layer cuts the chunk range of a 1-tile launch into 4 splits, so
+d_ff = 64 gives splits of 1, 0, 0, 0 k-tiles and d_ff = 512 / 768 / 1024 gives 2 / 3 / 4 each)."""
+import numpy as np
+import pytest
+
+import paper_2411_15715_amd as si
+import synth
+from gpu_helpers import GpuLayer, assert_parity
+from test_gpu_q4 import Q4Layer
+
+pytestmark = pytest.mark.gpu
+
+ROWS = (40, 100, 150, 250)  # one row tile each: the 64-, 128-, 192- and 256-row body
+
+
+@pytest.mark.parametrize("d_model", [64, 128, 192, 256])
+@pytest.mark.parametrize("d_ff", [64, 512, 768, 1024])
+def test_ring_depth_bf16(oracle, d_model, d_ff):
+    cfg = synth.scaled(synth.CONFIGS["llama2_70b"], d_model=d_model, d_ff=d_ff, seed=100 + d_model + d_ff)
+    w = synth.make_weights(cfg)
+    L = GpuLayer(cfg, w, (1.0, 0.0, 0.0), max_tokens=max(ROWS))
+    try:
+        xp = synth.make_tokens(cfg, max(ROWS))
+        yo = oracle.layer_forward(xp, w["w_gate"], w["w_up"], w["w_down"])
+        for T in ROWS:
+            print("ring depth bf16 M=%d H=%d T=%d" % (d_model, d_ff, T), flush=True)
+            assert_parity(L.forward(xp[:T], None, mode=si.SI_PREFILL), yo[:T])
+    finally:
+        L.close()
+
+
+@pytest.mark.parametrize("d_model", [64, 128, 192, 256])
+@pytest.mark.parametrize("d_ff", [64, 512, 768, 1024])
+def test_ring_depth_q4(oracle, d_model, d_ff):
+    cfg = synth.scaled(synth.CONFIGS["llama2_70b"], d_model=d_model, d_ff=d_ff, seed=200 + d_model + d_ff)
+    wq = synth.make_weights_q4(cfg)
+    # Power-of-two scales (2^-7, about the synthetic mean): (code - 8) * scale is then a bfloat16 exactly, so the one
+    # rounding per weight of the 4-bit GEMMs costs nothing and the test measures the ring, not that rounding (which
+    # alone reaches 2e-2 x RMS on layers this small: 64 x 64 weights leave nothing to average over)
+    for key in ("z_gate", "z_up", "z_down"):
+        wq[key] = np.full_like(wq[key], 0x3C00)
+    L = Q4Layer(cfg, wq, (1.0, 0.0, 0.0), max_tokens=max(ROWS))
+    try:
+        xp = synth.make_tokens(cfg, max(ROWS))
+        yo = oracle.layer_forward_q4(xp, wq)
+        for T in ROWS:
+            print("ring depth 4-bit M=%d H=%d T=%d" % (d_model, d_ff, T), flush=True)
+            assert_parity(L.forward(xp[:T], None, mode=si.SI_PREFILL), yo[:T])
+    finally:
+        L.close()

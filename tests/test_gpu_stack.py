@@ -23,8 +23,13 @@ def assert_parity(h_gpu, h_or):
     step = 2.0 ** (np.floor(np.log2(np.max(np.abs(h_or)))) - 7)
     d = np.abs(h_gpu.astype(np.float64) - h_or)
     assert float(d.max()) <= TOL * rms + step, "max-abs error %.3e > %.3e" % (d.max(), TOL * rms + step)
-    # straddles are rare: nearly all elements stay within the single-layer bound
-    assert np.mean(d > TOL * rms) < 1e-3
+    # straddles are rare: nearly all elements stay within the single-layer bound.  The measured share is printed
+    # (run pytest with -s) so that the allowance of 0.1 % is evidence, not an assumption.
+    frac = float(np.mean(d > TOL * rms))
+    print("stack parity: max-abs %.3e (single-layer bound %.3e, one bf16 step %.3e), elements above the single-layer "
+          "bound: %d of %d (%.4f %%)" % (d.max(), TOL * rms, step, int(np.sum(d > TOL * rms)), d.size, 100 * frac), flush=True)
+    assert frac < 1e-3
+    return frac
 
 
 class GpuStack:
@@ -105,6 +110,36 @@ def test_moe_stack(oracle):
             assert_parity(S.forward(xb, logits, n_g=n_g, prefetch=3), ho)
     finally:
         S.close()
+
+
+def test_stack_statistics_survive_prefetch(oracle):
+    """Per-layer statistics with cross-layer prefetch on: the copies issued ahead of a layer's call are counted in
+    that call, and a prefetch for the next call (wrap-around, or a one-layer stack prefetching itself) leaves the
+    statistics of the call just finished readable."""
+    base = synth.scaled(synth.CONFIGS["llama2_70b"], d_model=256, d_ff=1024)
+    cfgs = [dataclasses.replace(base, seed=400 + i) for i in range(2)]
+    weights = [synth.make_weights(c) for c in cfgs]
+    x2 = synth.make_tokens(base, 2, stream=9)
+    for n_layers in (2, 1):
+        S = GpuStack(cfgs[:n_layers], weights[:n_layers], [(0.25, 0.75, 0.0)] * n_layers, max_tokens=8, stage_mib=1)
+        try:
+            ho = oracle.stack_forward(x2, _oracle_layers(cfgs[:n_layers], weights[:n_layers], None))
+            ref = S.forward(x2, None, prefetch=0)
+            assert_parity(ref, ho)
+            for l in S.layers:
+                si.si_layer_set_profiling(l, 1)
+            for rep in range(3):
+                out = S.forward(x2, None, prefetch=3)
+                assert np.array_equal(out, ref)
+                for l in S.layers:
+                    st = si.si_layer_stats(l)
+                    # 768 of 1024 columns = 12 chunks of 96 KiB streamed per call, whoever issued the copies
+                    assert st["bytes_streamed"] == 12 * 3 * 64 * 256 * 2
+                    assert st["n_copies"] >= 1 and st["copy_ms"] > 0.0
+                    assert st["kernel_launches"][si.SI_K_NAMES.index("decode_gateup")] == 1 + st["n_copies"]
+                    assert 0.0 < st["total_ms"] < 1e3 and 0.0 < st["gpu_ms"] < 1e3
+        finally:
+            S.close()
 
 
 def test_stack_argument_checks():

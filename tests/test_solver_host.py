@@ -179,6 +179,20 @@ def test_profile_rejects_bad_arguments_before_any_gpu_call():
         assert ei.value.code == si.SI_EINVAL
 
 
+def test_place_experts_hand_worked_examples():
+    """Oracle and library against placements worked by hand (ties, the share hit exactly, the share missed by one
+    expert, the extremes): a wrong tie order or a wrong acceptance rule fails here."""
+    import os
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "place_experts.txt")
+    rows = [ln.split() for ln in open(path) if ln.strip() and ln[0] != "#"]
+    assert len(rows) >= 6
+    for freq, n_gg, share, want in rows:
+        freq = [float(v) for v in freq.split(",")]
+        want = [int(v) for v in want.split(",")]
+        assert so.place_experts(freq, int(n_gg), float(share)) == want, freq
+        assert si.si_place_experts(np.array(freq), int(n_gg), float(share)) == want, freq
+
+
 def test_place_experts_matches_oracle_and_its_contract():
     rng = np.random.default_rng(12)
     for _ in range(200):
