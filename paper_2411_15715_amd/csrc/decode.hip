@@ -6,6 +6,9 @@
 // Every weight byte is read once per pass of up to DECODE_TB tokens, with 128-bit loads that are
 // contiguous across the lanes of a wave.
 #include "si_internal.h"
+#include "route_device.h"
+
+#include <type_traits>
 
 namespace si {
 namespace {
@@ -42,13 +45,125 @@ __device__ inline bool block_rows(const Plan& p, int expert_sel, int x2_only, in
   return r1 > r0;
 }
 
-template <int TB>
+// Token assignment of a few tokens inside a block (FusedRoute): the same result as route.hip's kernels, derived
+// by every block for itself.  Pairs q = t*k + s in ascending order; the expert-sorted row of pair q is the number of
+// pairs with a smaller expert plus the number of earlier pairs with the same expert (stable), which for at most
+// FUSED_ROUTE_MAX_PAIRS pairs is a loop over all pairs per thread.
+struct BlockRoute {
+  int32_t idx[FUSED_ROUTE_MAX_PAIRS];
+  float w[FUSED_ROUTE_MAX_PAIRS];
+  int32_t row[FUSED_ROUTE_MAX_PAIRS];        // expert-sorted row of pair q
+  int32_t row_token[FUSED_ROUTE_MAX_PAIRS + FUSED_ROUTE_MAX_T];  // token of each row (shared expert rows follow)
+  int32_t t_expert[FUSED_ROUTE_MAX_PAIRS];   // touched experts, ascending
+  int32_t t_off[FUSED_ROUTE_MAX_PAIRS];      // first row of each touched expert
+  int32_t t_cnt[FUSED_ROUTE_MAX_PAIRS];
+  int32_t n_touched;
+  float sel[FUSED_ROUTE_MAX_T][MAX_EXPERTS];
+};
+
+__device__ inline void block_route(const FusedRoute& fr, BlockRoute& br, const Plan& p, bool write_tables) {
+  const int tid = threadIdx.x, lane = tid % WAVE, wid = tid / WAVE;
+  const int T = fr.T, E = fr.E, k = fr.k, n_pairs = T * k;
+  if (fr.logits) {
+    if (wid < T) topk_token(fr.logits + (size_t)wid * E, E, k, lane, br.idx + wid * k, br.w + wid * k, br.sel[wid]);
+  } else if (tid < n_pairs) {
+    br.idx[tid] = 0;
+    br.w[tid] = 1.f;
+  }
+  if (tid == 0) br.n_touched = 0;
+  __syncthreads();
+  int e = -1, row = 0, cnt = 0, first = 0;
+  if (tid < n_pairs) {
+    e = br.idx[tid];
+    first = 1;
+    for (int q = 0; q < n_pairs; ++q) {
+      const int eq = br.idx[q];
+      row += (eq < e) || (eq == e && q < tid);
+      cnt += eq == e;
+      if (eq == e && q < tid) first = 0;
+    }
+    br.row[tid] = first;  // (reused as the flag "first pair of its expert" for the next step)
+    br.row_token[row] = tid / k;
+  }
+  if (fr.has_shared && tid < T) br.row_token[n_pairs + tid] = tid;
+  __syncthreads();
+  if (first) {
+    // slot of this expert in the ascending list of touched experts = distinct smaller experts
+    int slot = 0;
+    for (int q = 0; q < n_pairs; ++q) slot += br.row[q] && br.idx[q] < e;
+    br.t_expert[slot] = e;
+    br.t_off[slot] = row;
+    br.t_cnt[slot] = cnt;
+    atomicAdd(&br.n_touched, 1);
+  }
+  __syncthreads();
+  if (!write_tables) return;
+  // the tables later launches of this call and the caller read (block (0, 0) only)
+  const RouteOut& u = fr.user;
+  const int EX = E + (fr.has_shared ? 1 : 0);
+  if (tid < n_pairs) {
+    const int q = tid;
+    p.idx[q] = e; p.w[q] = br.w[q];
+    p.perm[row] = q; p.inv[q] = row;
+    if (u.idx) u.idx[q] = e;
+    if (u.w) u.w[q] = br.w[q];
+    if (u.perm) u.perm[row] = q;
+    if (u.inv) u.inv[q] = row;
+  }
+  for (int r = tid; r < n_pairs + (fr.has_shared ? T : 0); r += GU_THREADS) p.row_token[r] = br.row_token[r];
+  for (int ex = tid; ex <= EX; ex += GU_THREADS) {
+    int c = 0, c1 = 0, o = 0;
+    if (ex < E) {
+      for (int q = 0; q < n_pairs; ++q) {
+        const int eq = br.idx[q];
+        c += eq == ex;
+        c1 += eq == ex && q / k < fr.n_x1;
+        o += eq < ex;
+      }
+    } else if (ex == E && fr.has_shared) {
+      c = T; c1 = fr.n_x1; o = n_pairs;
+    } else {
+      o = n_pairs + (fr.has_shared ? T : 0);  // the end of the prefix sum
+    }
+    if (ex < EX) { p.count[ex] = c; p.count1[ex] = c1; }
+    p.off[ex] = o;
+    if (ex < E) { if (u.count) u.count[ex] = c; }
+    if (ex <= E) { if (u.off) u.off[ex] = ex < E ? o : n_pairs; }
+  }
+  if (tid < br.n_touched) p.touched[tid] = br.t_expert[tid];
+  if (tid == 0) {
+    int nt = br.n_touched;
+    if (fr.has_shared) p.touched[nt++] = E;  // the shared expert always has rows
+    *p.n_touched = nt;
+  }
+}
+
+template <int TB, int FUSED>
 __global__ __launch_bounds__(GU_THREADS) void k_decode_gateup(const uint16_t* __restrict__ x, int M, Plan p,
                                                               int expert_sel, int x2_only, WeightView wv,
-                                                              float* __restrict__ h, int ldh) {
+                                                              float* __restrict__ h, int ldh, FusedRoute fr) {
   extern __shared__ u32x4 s_x[];  // [TB][M/8] bf16 x 8
+  __shared__ typename std::conditional<FUSED != 0, BlockRoute, int>::type s_br;  // (4 bytes when the tables are given)
   int e, r0, r1;
-  if (!block_rows(p, expert_sel, x2_only, blockIdx.y, e, r0, r1)) return;
+  const int* row_token = p.row_token;
+  if constexpr (FUSED != 0) {
+    BlockRoute& br = s_br;
+    block_route(fr, br, p, blockIdx.x == 0 && blockIdx.y == 0);
+    if (expert_sel >= 0) {
+      // one given expert: the routed expert of a dense layer (every pair is its row)
+      e = expert_sel;
+      r0 = 0;
+      r1 = fr.T * fr.k;
+    } else {
+      if ((int)blockIdx.y >= br.n_touched) return;
+      e = br.t_expert[blockIdx.y];
+      r0 = br.t_off[blockIdx.y];
+      r1 = r0 + br.t_cnt[blockIdx.y];
+    }
+    row_token = br.row_token;
+  } else {
+    if (!block_rows(p, expert_sel, x2_only, blockIdx.y, e, r0, r1)) return;
+  }
   const int tid = threadIdx.x, lane = tid % WAVE, wid = tid / WAVE;
   const int M8 = M / 8;
   const int blocks_per_chunk = CHUNK_J / GU_JPB;
@@ -68,7 +183,7 @@ __global__ __launch_bounds__(GU_THREADS) void k_decode_gateup(const uint16_t* __
     __syncthreads();
     for (int i = tid; i < nt * M8; i += GU_THREADS) {
       int tb = i / M8, c = i % M8;
-      int tok = p.row_token[rb + tb];
+      int tok = row_token[rb + tb];
       s_x[tb * M8 + c] = reinterpret_cast<const u32x4*>(x + (size_t)tok * M)[c];
     }
     __syncthreads();
@@ -229,15 +344,28 @@ __global__ __launch_bounds__(64) void k_decode_combine(DecodeCombineArgs a, Plan
 static int pick_tb(int tb_hint) { return tb_hint <= 1 ? 1 : (tb_hint <= 2 ? 2 : 4); }
 
 hipError_t launch_decode_gateup(const uint16_t* x, int M, const Plan& plan, int tb_hint, int expert_sel, int x2_only,
-                                int max_touched, const WeightView& wv, float* h, int ldh, hipStream_t stream) {
+                                int max_touched, const WeightView& wv, float* h, int ldh, hipStream_t stream,
+                                const FusedRoute* fused_route) {
   if (wv.n_chunks <= 0) return hipSuccess;
-  if (wv.q4) return launch_decode_gateup_q4(x, M, plan, tb_hint, expert_sel, x2_only, max_touched, wv, h, ldh, stream);
+  if (wv.q4) {
+    if (fused_route) return hipErrorInvalidValue;  // the 4-bit kernels take the assignment from the tables
+    return launch_decode_gateup_q4(x, M, plan, tb_hint, expert_sel, x2_only, max_touched, wv, h, ldh, stream);
+  }
   dim3 grid(wv.n_chunks * (CHUNK_J / GU_JPB), expert_sel >= 0 ? 1 : max_touched);
   const int tb = pick_tb(tb_hint);
   size_t lds = (size_t)tb * M * 2;
-  if (tb == 1) hipLaunchKernelGGL(k_decode_gateup<1>, grid, dim3(GU_THREADS), lds, stream, x, M, plan, expert_sel, x2_only, wv, h, ldh);
-  else if (tb == 2) hipLaunchKernelGGL(k_decode_gateup<2>, grid, dim3(GU_THREADS), lds, stream, x, M, plan, expert_sel, x2_only, wv, h, ldh);
-  else hipLaunchKernelGGL(k_decode_gateup<4>, grid, dim3(GU_THREADS), lds, stream, x, M, plan, expert_sel, x2_only, wv, h, ldh);
+  if (fused_route) {
+    const FusedRoute& fr = *fused_route;
+    if (fr.T < 1 || fr.T > FUSED_ROUTE_MAX_T || fr.T * fr.k > FUSED_ROUTE_MAX_PAIRS || fr.E > MAX_EXPERTS || x2_only) return hipErrorInvalidValue;
+    if (tb == 1) hipLaunchKernelGGL((k_decode_gateup<1, 1>), grid, dim3(GU_THREADS), lds, stream, x, M, plan, expert_sel, x2_only, wv, h, ldh, fr);
+    else if (tb == 2) hipLaunchKernelGGL((k_decode_gateup<2, 1>), grid, dim3(GU_THREADS), lds, stream, x, M, plan, expert_sel, x2_only, wv, h, ldh, fr);
+    else hipLaunchKernelGGL((k_decode_gateup<4, 1>), grid, dim3(GU_THREADS), lds, stream, x, M, plan, expert_sel, x2_only, wv, h, ldh, fr);
+    return hipGetLastError();
+  }
+  const FusedRoute none{};
+  if (tb == 1) hipLaunchKernelGGL((k_decode_gateup<1, 0>), grid, dim3(GU_THREADS), lds, stream, x, M, plan, expert_sel, x2_only, wv, h, ldh, none);
+  else if (tb == 2) hipLaunchKernelGGL((k_decode_gateup<2, 0>), grid, dim3(GU_THREADS), lds, stream, x, M, plan, expert_sel, x2_only, wv, h, ldh, none);
+  else hipLaunchKernelGGL((k_decode_gateup<4, 0>), grid, dim3(GU_THREADS), lds, stream, x, M, plan, expert_sel, x2_only, wv, h, ldh, none);
   return hipGetLastError();
 }
 

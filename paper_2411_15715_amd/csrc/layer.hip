@@ -869,7 +869,13 @@ int si_layer_forward(si_layer_t* L, const void* x_dev, const float* logits_dev, 
   // ---- token assignment (Section II-A)
   RouteOut u{};
   if (rout) u = RouteOut{rout->idx, rout->w, rout->count, rout->off, rout->perm, rout->inv};
-  {
+  // Generation phase of a fully resident bf16 layer with very few (token, expert) pairs: a launch costs as much as
+  // reading tens of megabytes of weights (Section III-C: with few tokens the launch time rivals the compute time),
+  // so the assignment is derived inside the first gate/up launch instead of by a kernel of its own.
+  const bool resident_only = !any_cg && !need_cgp && !need_cc && !L->placed && !L->q4 && L->ch_gg > 0;
+  bool fuse_route = path == SI_DECODE && resident_only && T <= FUSED_ROUTE_MAX_T && T * k <= FUSED_ROUTE_MAX_PAIRS;
+  FusedRoute fr{E > 1 ? logits_dev : nullptr, T, E, k, L->has_shared, n_x1, u};
+  if (!fuse_route) {
     SegScope sc(L, stream, 0);
     hipError_t e = launch_route(E > 1 ? logits_dev : nullptr, T, E, k, L->has_shared, n_g, L->plan, u, stream);
     if (e != hipSuccess) return fail(SI_EHIP, "route launch failed: %s", hipGetErrorString(e));
@@ -949,7 +955,9 @@ int si_layer_forward(si_layer_t* L, const void* x_dev, const float* logits_dev, 
       const int cps = is_shared ? (part == 0 ? scps_gg : part == 1 ? scps_cg : scps_cc) : (part == 0 ? cps_gg : part == 1 ? cps_cg : cps_cc);
       {
         SegScope sc(L, stream, SI_K_DECODE_GATEUP);
-        K_TRY(launch_decode_gateup(x, M, L->plan, T, esel, x2_only, max_touched, wv, L->d_h, L->ldh_dec, stream));
+        K_TRY(launch_decode_gateup(x, M, L->plan, T, esel, x2_only, max_touched, wv, L->d_h, L->ldh_dec, stream,
+                                   fuse_route ? &fr : nullptr));
+        fuse_route = false;  // the tables exist from here on
       }
       SegScope sc(L, stream, SI_K_DECODE_DOWN);
       K_TRY(launch_decode_down(L->d_h, L->ldh_dec, M, L->plan, T, esel, x2_only, max_touched, wv,

@@ -85,12 +85,21 @@ __device__ inline bool storage_index(const WeightView& wv, int e, int& se) {
 //  expert_sel < 0: all touched experts (table lookup);  >= 0: only that expert.
 //  x2_only: restrict to rows of X2 tokens (CG').
 //  tb_hint: upper bound on the rows of one expert (T); picks the tokens-per-pass instantiation (1, 2 or 4).
+// Token assignment folded into the first gate/up launch of a generation-phase call with few tokens (the launch of a
+// separate assignment kernel costs as much as reading tens of megabytes): every block derives the assignment of
+// the <= FUSED_ROUTE_MAX_T tokens itself and finds its expert from it; block (0, 0) also writes the tables that the
+// later launches of the call and the caller read.  logits == nullptr: dense layer (one expert, weight 1).
+constexpr int FUSED_ROUTE_MAX_T = 4;
+constexpr int FUSED_ROUTE_MAX_PAIRS = 8;
+struct FusedRoute {
+  const float* logits;
+  int T, E, k, has_shared, n_x1;
+  RouteOut user;
+};
 hipError_t launch_decode_gateup(const uint16_t* x, int M, const Plan& plan, int tb_hint, int expert_sel, int x2_only,
-                                int max_touched, const WeightView& wv, float* h, int ldh, hipStream_t stream);
+                                int max_touched, const WeightView& wv, float* h, int ldh, hipStream_t stream,
+                                const FusedRoute* fused_route = nullptr);
 // part[slot][row][m] = sum over the j of the slot of h[row][j] * Wd[j][m]
-hipError_t launch_decode_down(const float* h, int ldh, int M, const Plan& plan, int tb_hint, int expert_sel, int x2_only,
-                              int max_touched, const WeightView& wv, int slot0, int chunks_per_slot,
-                              float* part, size_t slot_stride, hipStream_t stream);
 // y[t][m] = sum_s w[t][s] * sum_slots part[slot][inv[t*k+s]][m] + shared rows + ycc[t][m]
 struct DecodeCombineArgs {
   const float* part; size_t slot_stride;
@@ -99,6 +108,10 @@ struct DecodeCombineArgs {
   const float* ycc;                         // [T1][M] or null
   int T, k, M, n_x1, has_shared;
 };
+// part[slot][row][m] = sum over the j of the slot of h[row][j] * Wd[j][m]
+hipError_t launch_decode_down(const float* h, int ldh, int M, const Plan& plan, int tb_hint, int expert_sel, int x2_only,
+                              int max_touched, const WeightView& wv, int slot0, int chunks_per_slot,
+                              float* part, size_t slot_stride, hipStream_t stream);
 hipError_t launch_decode_combine(const DecodeCombineArgs& a, const Plan& plan, float* y, hipStream_t stream);
 
 // prefill.hip --------------------------------------------------------------------------------

@@ -235,3 +235,42 @@ def test_unusual_shapes_and_knobs(oracle):
             assert_parity(y, oracle_y(oracle, cfg, w, xb, lg))
     finally:
         L.close()
+
+
+@pytest.mark.parametrize("shape", ["moe", "shared", "dense", "many_experts", "topk_all"])
+def test_resident_decode_two_launch_path(oracle, shape):
+    """Generation-phase calls of a fully resident layer with at most 4 tokens and 8 (token, expert) pairs derive the
+    token assignment inside the gate/up launch instead of by a kernel of its own.  Routing tables bit-exact,
+    outputs within the bar; repeated and interleaved calls (more tokens, fewer tokens, calls that take the separate
+    assignment kernel because they have more pairs) leave no state behind."""
+    if shape == "moe":
+        cfg = synth.scaled(synth.CONFIGS["phimoe"], d_model=512, d_ff=1280, n_experts=16)
+    elif shape == "shared":
+        cfg = synth.scaled(synth.CONFIGS["qwen_moe"], d_model=256, d_ff=384, d_ff_shared=1024, n_experts=64)
+    elif shape == "dense":
+        cfg = synth.scaled(synth.CONFIGS["llama2_70b"], d_model=512, d_ff=1792)
+    elif shape == "many_experts":
+        cfg = synth.scaled(synth.CONFIGS["qwen_moe"], d_model=128, d_ff=128, d_ff_shared=0, n_experts=256, top_k=6)
+    else:
+        cfg = synth.scaled(synth.CONFIGS["phimoe"], d_model=192, d_ff=640, n_experts=16, top_k=16)  # 4 x 16 = 64 pairs
+    w = synth.make_weights(cfg)
+    L = GpuLayer(cfg, w, (1.0, 0.0, 0.0), max_tokens=16)
+    try:
+        outs = {}
+        for T in (4, 1, 3, 7, 2, 4, 16, 1):
+            xb = synth.make_tokens(cfg, T, stream=40 + T)
+            lg = synth.make_router_logits(cfg, xb)
+            if lg is not None and T == 3:
+                lg[1] = lg[0]            # two tokens with identical logits
+                lg[2, :] = 0.25          # all experts tied: the lowest indices win
+            if lg is not None:
+                y, r = L.forward(xb, lg, mode=si.SI_DECODE, routing=True)
+                assert_routing_equal(r, oracle.route(lg, cfg.top_k), T, cfg.top_k)
+            else:
+                y = L.forward(xb, None, mode=si.SI_DECODE)
+            assert_parity(y, oracle_y(oracle, cfg, w, xb, lg))
+            if T in outs:
+                assert np.array_equal(outs[T], y)   # same call again after other calls: bit-identical
+            outs[T] = y
+    finally:
+        L.close()
