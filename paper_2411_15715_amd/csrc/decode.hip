@@ -321,13 +321,16 @@ __global__ __launch_bounds__(64) void k_decode_combine(DecodeCombineArgs a, Plan
 #pragma unroll
     for (int part = 0; part < 3; ++part) {
       const float* base = a.part + (size_t)(part * DOWN_SLOTS) * a.slot_stride + (size_t)row * a.M;
-      float4 tmp[DOWN_SLOTS];
+      // eight slots at a time: their loads are issued together, then added in slot order
+      for (int q0 = 0; q0 < n_part[part]; q0 += 8) {
+        float4 tmp[8];
 #pragma unroll
-      for (int q = 0; q < DOWN_SLOTS; ++q)
-        tmp[q] = q < n_part[part] ? reinterpret_cast<const float4*>(base + (size_t)q * a.slot_stride)[m4]
-                                  : make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int q = 0; q < 8; ++q)
+          tmp[q] = q0 + q < n_part[part] ? reinterpret_cast<const float4*>(base + (size_t)(q0 + q) * a.slot_stride)[m4]
+                                         : make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
-      for (int q = 0; q < DOWN_SLOTS; ++q) { v.x += tmp[q].x; v.y += tmp[q].y; v.z += tmp[q].z; v.w += tmp[q].w; }
+        for (int q = 0; q < 8; ++q) { v.x += tmp[q].x; v.y += tmp[q].y; v.z += tmp[q].z; v.w += tmp[q].w; }
+      }
     }
     acc.x = fmaf(wgt, v.x, acc.x); acc.y = fmaf(wgt, v.y, acc.y);
     acc.z = fmaf(wgt, v.z, acc.z); acc.w = fmaf(wgt, v.w, acc.w);

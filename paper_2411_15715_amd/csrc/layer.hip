@@ -412,7 +412,7 @@ int setup_staging(si_layer* L) {
   if (L->d_stage.empty()) {
     const size_t stage_bytes = (size_t)(L->desc.stage_mib == 0 ? 256 : L->desc.stage_mib) << 20;
     const int sc = (int)std::max<size_t>(1, stage_bytes / (L->ce * 2));
-    const int cps_max = std::max({ceil_div(L->H / CHUNK_J, DOWN_SLOTS), ceil_div(L->Hs / CHUNK_J, DOWN_SLOTS), 8});
+    const int cps_max = std::max({ceil_div(L->H / CHUNK_J, 16), ceil_div(L->Hs / CHUNK_J, 16), 8});  // the largest cps_of() can return
     L->stage_chunks = std::max(sc, cps_max);
     L->d_stage.assign(L->n_stage, nullptr);
     L->ev_ready.assign(L->n_stage, nullptr);
@@ -765,7 +765,14 @@ namespace {
 
 // chunks per j-slot of the decode down projection: at most DOWN_SLOTS slots per part, and at least 8 chunks
 // (256 KB of weights per block) so that small experts do not shatter into tiny blocks
-int cps_of(int ch) { return std::max(1, std::max(ceil_div(ch, DOWN_SLOTS), std::min(8, ch))); }
+// A launch over many experts gets at most 16 slots per expert; a launch over one large expert (a dense layer, a shared
+// expert) up to DOWN_SLOTS when 16 slots would leave fewer than two blocks per compute unit (each block walks its
+// chunks one after the other with eight loads per lane in flight, so few long blocks leave the memory system idle:
+// the shared expert of the Qwen-shaped layer went from 2.5 to 5 TB/s).
+int cps_of(int ch, bool single_expert, int M) {
+  const int slots = single_expert && ceil_div(M, 256) * 16 < 512 ? DOWN_SLOTS : 16;
+  return std::max(1, std::max(ceil_div(ch, slots), std::min(8, ch)));
+}
 
 // chunks per staged piece of a part with `cps` chunks per j-slot
 int piece_chunks(const si_layer* L, int path, int cps) {
@@ -778,7 +785,7 @@ int piece_chunks(const si_layer* L, int path, int cps) {
 int prefetch_cg(si_layer* N, int path) {
   if (N->E != 1 || N->has_shared || N->ch_cg <= 0 || N->pre_n > 0) return SI_OK;
   HIP_TRY(hipSetDevice(N->device));
-  const int piece_max = piece_chunks(N, path, cps_of(N->ch_cg));
+  const int piece_max = piece_chunks(N, path, cps_of(N->ch_cg, true, N->M));
   const uint16_t* hbase = N->h_routed;
   N->pre_segs.clear();
   N->pre_ev_used = 0;
@@ -924,9 +931,10 @@ int si_layer_forward(si_layer_t* L, const void* x_dev, const float* logits_dev, 
   const int max_touched = std::min(EX, T * k + L->has_shared);
   const int tiles_upper = (T * k) / TILE_ROWS + std::min(E, T * k);  // bound on the routed row tiles
   // (whole-expert placement: every routed expert has H/64 chunks wherever it lives)
-  const int cps_gg = cps_of(L->placed ? L->H / CHUNK_J : L->ch_gg), cps_cg = cps_of(L->placed ? L->H / CHUNK_J : L->ch_cg),
-            cps_cc = cps_of(L->placed ? L->H / CHUNK_J : L->ch_cc);
-  const int scps_gg = cps_of(L->sch_gg), scps_cg = cps_of(L->sch_cg), scps_cc = cps_of(L->sch_cc);
+  const bool one = E == 1;
+  const int cps_gg = cps_of(L->placed ? L->H / CHUNK_J : L->ch_gg, one, M), cps_cg = cps_of(L->placed ? L->H / CHUNK_J : L->ch_cg, one, M),
+            cps_cc = cps_of(L->placed ? L->H / CHUNK_J : L->ch_cc, one, M);
+  const int scps_gg = cps_of(L->sch_gg, true, M), scps_cg = cps_of(L->sch_cg, true, M), scps_cc = cps_of(L->sch_cc, true, M);
   const size_t slot_stride = (size_t)L->rows_dec * M;
   // k-splits of the prefill down projection: enough blocks to fill 256 CUs when there are few row tiles
   const int n_ntiles = ceil_div(M, 256);
@@ -1010,7 +1018,7 @@ int si_layer_forward(si_layer_t* L, const void* x_dev, const float* logits_dev, 
     if (path == SI_DECODE && L->placed) {
       // rows of experts that no launch of this call writes (CC experts of X1 tokens) must read as zero in the merge
       SegScope sc(L, stream, SI_K_FILL);
-      const int n_slots = ceil_div(L->H / CHUNK_J, cps_of(L->H / CHUNK_J));
+      const int n_slots = ceil_div(L->H / CHUNK_J, cps_of(L->H / CHUNK_J, one, M));
       for (int q = 0; q < n_slots; ++q) K_TRY(launch_fill_zero(L->d_part + (size_t)q * slot_stride, (size_t)T * k * M, stream));
     }
     if (E == 1) rc = run_part(L->d_gg, 0, 0, 0, 0, L->ch_gg, hch * CHUNK_J, 0, 0, 0, true);
@@ -1103,7 +1111,7 @@ int si_layer_forward(si_layer_t* L, const void* x_dev, const float* logits_dev, 
       a.part = L->d_part; a.slot_stride = slot_stride;
       a.n_slots_gg = ceil_div(L->ch_gg, cps_gg); a.n_slots_cg = ceil_div(L->ch_cg, cps_cg); a.n_slots_cc = need_cgp ? ceil_div(L->ch_cc, cps_cc) : 0;
       if (L->placed) {  // all parts of the routed experts share the first slot range
-        a.n_slots_gg = ceil_div(L->H / CHUNK_J, cps_of(L->H / CHUNK_J));
+        a.n_slots_gg = ceil_div(L->H / CHUNK_J, cps_of(L->H / CHUNK_J, one, M));
         a.n_slots_cg = a.n_slots_cc = 0;
       }
       a.s_slots_gg = ceil_div(L->sch_gg, scps_gg); a.s_slots_cg = ceil_div(L->sch_cg, scps_cg); a.s_slots_cc = need_cgp ? ceil_div(L->sch_cc, scps_cc) : 0;

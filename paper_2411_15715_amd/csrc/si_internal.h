@@ -20,7 +20,7 @@ constexpr int ROUTE_THREADS = 1024;   // block size of the assignment kernel
 constexpr int TILE_ROWS = 256;        // rows per row tile of the prefill GEMMs (the last tile of an expert holds what is left)
 constexpr int MAX_KSPLIT = 4;         // k-splits (output slabs) of the prefill down projection
 constexpr int DECODE_TB = 4;          // most tokens handled per weight pass in the GEMV kernels
-constexpr int DOWN_SLOTS = 16;        // j-splits of the decode down projection per part
+constexpr int DOWN_SLOTS = 32;        // j-splits of the decode down projection per part
 
 // Row tiles of an expert (or of its X2 rows) with `rows` rows.  The GEMM kernels run, per tile, the body
 // instantiated for the rows the tile really has (64, 128, 192 or 256): a block streams its weight tile whatever
