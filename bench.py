@@ -472,7 +472,9 @@ def stack_study(args, si, torch, cfg, w):
     a GPU-memory budget over the layers of a stack, and the measured generation step of the stack against the
     uniform assignment of the same budget (the paper's memory-assignment ablation, Section V-E.3)."""
     M, H, E, k = cfg.d_model, cfg.d_ff, cfg.n_experts, cfg.top_k
-    assert E == 1 and not cfg.d_ff_shared, "--stack is set up for dense layers"
+    if E > 1:
+        return stack_study_moe(args, si, torch, cfg, w)
+    assert not cfg.d_ff_shared
     n_layers, n_G = args.stack, 8
     T = cfg.t_decode
     dev = torch.device("cuda:0")
@@ -529,6 +531,59 @@ def stack_study(args, si, torch, cfg, w):
     print(json.dumps({"stack_study": cfg.name, "layers": n_layers, "n_G": n_G, "tokens": T, "model": prof["model"],
                       "t_star_ms_by_r_gg": [round(1e3 * t, 4) for t in t_star],
                       "r_cg_star_by_r_gg": [round(s["r_cg"], 4) for s in sols], "budgets": rows}))
+
+
+def stack_study_moe(args, si, torch, cfg, w):
+    """A stack of MoE layers of the config's shape at one split (--split, default 50/50/0): generation step with and
+    without cross-layer prefetch.  What can travel ahead of a layer's own token assignment is its shared expert's CG
+    part; reported per setting: step time, busy time of the host link (sum of the layers' copy times) and the time
+    the link idles per layer."""
+    import synth
+    split = tuple(float(v) for v in args.split.split(",")) if args.split else (0.5, 0.5, 0.0)
+    n_layers = args.stack
+    T = cfg.t_decode
+    dev = torch.device("cuda:0")
+    stream = torch.cuda.current_stream().cuda_stream
+    layers = [create_layer(si, cfg, w, split) for _ in range(n_layers)]
+    rows = []
+    try:
+        st = si.si_stack_create(layers)
+        xb = synth.make_tokens(cfg, T, stream=7)
+        lg = synth.make_router_logits(cfg, xb)
+        x = torch.from_numpy(xb.view(np.int16)).to(dev)
+        lgd = torch.from_numpy(lg).to(dev)
+        out = torch.empty((T, cfg.d_model), dtype=torch.float32, device=dev)
+        ptrs = [lgd.data_ptr()] * n_layers
+        for name, pf in (("no_prefetch", 0), ("prefetch", 3)):
+            for l in layers:
+                si.si_layer_set_profiling(l, 0)
+            ts = []
+            for i in range(10):
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                si.si_stack_forward(st, x.data_ptr(), ptrs, T, 0, si.SI_DECODE, out.data_ptr(), prefetch=pf, stream=stream)
+                torch.cuda.synchronize()
+                if i >= 2:
+                    ts.append(time.perf_counter() - t0)
+            for l in layers:
+                si.si_layer_set_profiling(l, 1)
+            busy = []
+            for i in range(4):
+                torch.cuda.synchronize()
+                si.si_stack_forward(st, x.data_ptr(), ptrs, T, 0, si.SI_DECODE, out.data_ptr(), prefetch=pf, stream=stream)
+                torch.cuda.synchronize()
+                stats = [si.si_layer_stats(l) for l in layers]
+                if i >= 1:
+                    busy.append(sum(s_["copy_ms"] for s_ in stats))
+            step_ms = 1e3 * float(np.median(ts))
+            rows.append({"setting": name, "step_ms": round(step_ms, 3), "link_busy_ms": round(float(np.mean(busy)), 3),
+                         "link_idle_ms_per_layer": round((step_ms - float(np.mean(busy))) / n_layers, 4),
+                         "streamed_MB_per_step": round(sum(s_["bytes_streamed"] for s_ in stats) / 1e6, 1)})
+        si.si_stack_destroy(st)
+    finally:
+        for l in layers:
+            si.si_layer_destroy(l)
+    print(json.dumps({"stack_study": cfg.name, "layers": n_layers, "tokens": T, "split": list(split), "rows": rows}))
 
 
 def placement_study(args, si, torch, cfg, w):

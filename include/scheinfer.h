@@ -304,8 +304,9 @@ void si_layer_destroy(si_layer_t* layer);
  *   x_0 = x,   x_{l+1} = bf16(x_l + Layer_l(x_l)),   h_out = x_{n-1} + Layer_{n-1}(x_{n-1})   (fp32, not rounded).
  * Each layer keeps its own slicing rates, e.g. the r_GG that si_assign_gpu_memory gave it (Section IV-A.4).
  * prefetch bit 0: the first CG pieces of layer l+1 are put on the host link as soon as the copies of layer l are
- * enqueued, before the host waits for layer l's CC workers, so that the link does not idle between layers
- * (dense layers only: which experts of an MoE layer are streamed depends on its own token assignment).
+ * enqueued, before the host waits for layer l's CC workers, so that the link does not idle between layers.  What
+ * travels ahead is what does not depend on layer l+1's own token assignment: the one expert of a dense layer, or
+ * the shared expert of an MoE layer (which that layer's call then takes first); routed experts never do.
  * prefetch bit 1: likewise layer 0's pieces after the last layer, for the next call on this stack (token by
  * token generation); they are used if that call takes the same path (decode / prefill) and copied again if not.
  *

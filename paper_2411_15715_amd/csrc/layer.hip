@@ -192,6 +192,7 @@ struct si_layer {
   // CG pieces copied ahead of the forward call that will use them (cross-layer prefetch in a stack):
   // the first pre_n pieces of the CG part, cut for path pre_path, sit in slots pre_slot[0..pre_n)
   int pre_n = 0, pre_path = 0;
+  bool pre_shared = false;       // the pieces belong to the shared expert (MoE layer), else to expert 0 of a dense layer
   std::vector<int> pre_slot;
   // timing events of the copies issued ahead of a call live in two pools of their own, used alternately: the call
   // that consumes the pieces merges pre_segs into its own list and flips the pool, so the events its statistics
@@ -779,14 +780,19 @@ int piece_chunks(const si_layer* L, int path, int cps) {
   return path == SI_DECODE ? std::max(cps, L->stage_chunks / cps * cps) : L->stage_chunks;
 }
 
-// Copy the first CG pieces of a dense layer into its staging ring ahead of its forward call (as many as the
-// ring has slots).  Only dense layers without a shared expert: which experts of an MoE layer are streamed is
-// known only after its own token assignment.
+// Copy the first CG pieces of a layer into its staging ring ahead of its forward call (as many as the ring has
+// slots): what can travel before the layer's own token assignment is known.  A dense layer: its one expert.  An MoE
+// layer: its shared expert, which every token uses (which routed experts are streamed is known only after the
+// assignment); the forward call then takes the shared expert first, while the ring still holds the pieces.
 int prefetch_cg(si_layer* N, int path) {
-  if (N->E != 1 || N->has_shared || N->ch_cg <= 0 || N->pre_n > 0) return SI_OK;
+  if (N->pre_n > 0) return SI_OK;
+  const bool dense = N->E == 1 && !N->has_shared && N->ch_cg > 0;
+  const bool shared = N->E > 1 && N->has_shared && N->sch_cg > 0 && !N->placed;
+  if (!dense && !shared) return SI_OK;
   HIP_TRY(hipSetDevice(N->device));
-  const int piece_max = piece_chunks(N, path, cps_of(N->ch_cg, true, N->M));
-  const uint16_t* hbase = N->h_routed;
+  const int n_cg = dense ? N->ch_cg : N->sch_cg, n_cc = dense ? N->ch_cc : N->sch_cc;
+  const int piece_max = piece_chunks(N, path, cps_of(n_cg, true, N->M));
+  const uint16_t* hbase = dense ? N->h_routed : N->h_shared;
   N->pre_segs.clear();
   N->pre_ev_used = 0;
   auto pre_event = [&]() -> hipEvent_t {
@@ -799,19 +805,20 @@ int prefetch_cg(si_layer* N, int path) {
     return pool[N->pre_ev_used++];
   };
   N->pre_slot.clear();
-  for (int c = 0; c < N->ch_cg && (int)N->pre_slot.size() < N->n_stage; c += piece_max) {
-    const int n = std::min(piece_max, N->ch_cg - c);
+  for (int c = 0; c < n_cg && (int)N->pre_slot.size() < N->n_stage; c += piece_max) {
+    const int n = std::min(piece_max, n_cg - c);
     const int slot = (int)(N->piece_counter++ % N->n_stage);
     if (N->slot_used[slot]) HIP_TRY(hipStreamWaitEvent(N->copy_stream, N->ev_free[slot], 0));
     hipEvent_t ea = N->profiling ? pre_event() : nullptr, eb = ea ? pre_event() : nullptr;
     if (eb) HIP_TRY(hipEventRecord(ea, N->copy_stream));
-    HIP_TRY(hipMemcpyAsync(N->d_stage[slot], hbase + (size_t)(N->ch_cc + c) * N->ce, (size_t)n * N->ce * 2, hipMemcpyHostToDevice, N->copy_stream));
+    HIP_TRY(hipMemcpyAsync(N->d_stage[slot], hbase + (size_t)(n_cc + c) * N->ce, (size_t)n * N->ce * 2, hipMemcpyHostToDevice, N->copy_stream));
     if (eb) { HIP_TRY(hipEventRecord(eb, N->copy_stream)); N->pre_segs.push_back({ea, eb, SEG_COPY, 0}); }
     HIP_TRY(hipEventRecord(N->ev_ready[slot], N->copy_stream));
     N->pre_slot.push_back(slot);
   }
   N->pre_n = (int)N->pre_slot.size();
   N->pre_path = path;
+  N->pre_shared = shared;
   return SI_OK;
 }
 
@@ -1038,7 +1045,9 @@ int si_layer_forward(si_layer_t* L, const void* x_dev, const float* logits_dev, 
 
   // ---- CG and CG' parts: copy (Stream-C) double-buffered against compute (Stream-D)
   if (any_cg || need_cgp) {
-    for (int e = 0; e < EX; ++e) {
+    const bool shared_first = L->pre_n > 0 && L->pre_shared;  // its first pieces are already in the ring
+    for (int ei = 0; ei < EX; ++ei) {
+      const int e = !shared_first ? ei : ei == 0 ? E : ei - 1;
       if (rows_all(e) <= 0) continue;
       const bool sh = e >= E;
       const int n_cc_e = L->e_chunks(e, 2), n_cg_e = L->e_chunks(e, 1);
@@ -1053,7 +1062,7 @@ int si_layer_forward(si_layer_t* L, const void* x_dev, const float* logits_dev, 
         for (int c = 0; c < pn; c += piece_max) {
           const int n = std::min(piece_max, pn - c);
           int slot;
-          if (part == 1 && !sh && c / piece_max < L->pre_n) {
+          if (part == 1 && sh == L->pre_shared && c / piece_max < L->pre_n) {
             slot = L->pre_slot[c / piece_max];  // already on its way (prefetched after the previous layer's copies)
           } else {
             slot = (int)(L->piece_counter++ % L->n_stage);

@@ -112,6 +112,36 @@ def test_moe_stack(oracle):
         S.close()
 
 
+def test_moe_stack_with_shared_expert_prefetch(oracle):
+    """MoE layers with a shared expert: the shared expert's CG pieces of the next layer travel ahead of that layer's
+    token assignment (they do not depend on it) and the layer takes the shared expert first.  Prefetching changes
+    when bytes move, not what is computed: every prefetch setting gives bit-identical output."""
+    base = synth.scaled(synth.CONFIGS["qwen_moe"], d_model=256, d_ff=384, d_ff_shared=1536, n_experts=16, top_k=4)
+    splits = [(0.5, 0.5, 0.0), (0.25, 0.5, 0.25), (0.0, 1.0, 0.0), (1.0, 0.0, 0.0)]
+    cfgs = [dataclasses.replace(base, seed=500 + i) for i in range(len(splits))]
+    weights = [synth.make_weights(c) for c in cfgs]
+    S = GpuStack(cfgs, weights, splits, max_tokens=200, stage_mib=1)
+    try:
+        for T, n_g, mode in ((3, 0, si.SI_DECODE), (200, 80, si.SI_PREFILL)):
+            xb = synth.make_tokens(base, T, stream=20 + T)
+            logits = [synth.make_router_logits(c, xb) for c in cfgs]
+            ho = oracle.stack_forward(xb, _oracle_layers(cfgs, weights, logits))
+            outs = [S.forward(xb, logits, n_g=n_g, mode=mode, prefetch=p) for p in (0, 1, 3, 3, 0)]
+            for h in outs:
+                assert_parity(h, ho)
+                assert np.array_equal(h, outs[0])
+        for l in S.layers:
+            si.si_layer_set_profiling(l, 1)
+        xb = synth.make_tokens(base, 3, stream=23)
+        logits = [synth.make_router_logits(c, xb) for c in cfgs]
+        ref = S.forward(xb, logits, mode=si.SI_DECODE, prefetch=0)
+        streamed = [si.si_layer_stats(l)["bytes_streamed"] for l in S.layers]
+        assert np.array_equal(S.forward(xb, logits, mode=si.SI_DECODE, prefetch=3), ref)
+        assert [si.si_layer_stats(l)["bytes_streamed"] for l in S.layers] == streamed   # the same bytes, earlier
+    finally:
+        S.close()
+
+
 def test_stack_statistics_survive_prefetch(oracle):
     """Per-layer statistics with cross-layer prefetch on: the copies issued ahead of a layer's call are counted in
     that call, and a prefetch for the next call (wrap-around, or a one-layer stack prefetching itself) leaves the
