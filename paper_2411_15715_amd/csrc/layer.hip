@@ -593,6 +593,12 @@ int create_impl(const si_layer_desc_t* desc, const WeightSource& src, const uint
       cols = std::max(cols, L->deq_chunks * CHUNK_J);
     }
     L->hact_elems = n_rows * (size_t)cols;
+    // the prompt-phase GEMMs address the rows of their A operands (x, then the activations) with 32-bit element offsets
+    if (L->hact_elems >= ((size_t)1 << 31) || (size_t)T * M >= ((size_t)1 << 31)) {
+      fail(SI_EINVAL, "max_tokens = %d too large: an operand of the prompt-phase GEMMs would exceed 2^31 elements", T);
+      si_layer_destroy(L);
+      return SI_EINVAL;
+    }
     TRY_OR_DESTROY(dev_alloc(&L->d_hact, L->hact_elems));
     L->yp_slab = n_rows * (size_t)M;
     TRY_OR_DESTROY(dev_alloc(&L->d_yp, (size_t)MAX_KSPLIT * L->yp_slab));

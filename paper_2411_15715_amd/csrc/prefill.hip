@@ -7,8 +7,9 @@
 //
 // Both GEMMs: one 512-thread block (8 waves, 2 per SIMD) per BM x 256 output tile, BK = 64, a ring of LDS
 // stages filled by direct global->LDS loads (global_load_lds_dwordx4, no VGPR staging), wave tile
-// (BM/2) x 64.  A row tile holds up to 256 rows (si_internal.h: n_row_tiles); the block runs the body
-// instantiated for BM = 64, 128, 192 or 256, the smallest that covers the rows the tile really has.
+// (BM/2) x 64.  A row tile holds up to 256 rows, the last one of an expert up to 320 (si_internal.h: n_row_tiles);
+// the block runs the body instantiated for BM = 64, 128, 192, 256 or 320, the smallest that covers the rows the
+// tile really has.
 // LDS rows hold 64 contraction elements (128 bytes); the 16-byte piece c of row r sits at piece
 // c ^ ((r >> 1) & 7): gfx950's LDS has 64 banks, so 16 consecutive rows x 16 bytes must cover 256
 // distinct bytes of bank space for the 128-bit MFMA operand reads to be conflict free (measured:
@@ -36,7 +37,7 @@ constexpr int KERNEL_LDS = 144 * 1024;  // the largest body
 template <int BM> struct Shape {
   static constexpr int NST = BM >= 192 ? 2 : 3;           // LDS stages
   static constexpr int STAGE = BM * 128 + B_BYTES;        // bytes per stage
-  static constexpr int LDS = NST * STAGE;                 // 120, 144, 112, 128 KB for BM = 64, 128, 192, 256
+  static constexpr int LDS = NST * STAGE;                 // 120, 144, 112, 128, 144 KB for BM = 64, 128, 192, 256, 320
   static constexpr int FA = BM / 64;                      // A fragments (32 rows each) per wave
   static constexpr int ALD = BM / 64;                     // A load instructions per wave per stage
   static constexpr int LPW = ALD + 4;                     // load instructions per wave per stage
@@ -332,20 +333,20 @@ __device__ __forceinline__ void gateup_body(const uint16_t* __restrict__ x, int 
                                             const WeightView& wv, uint16_t* __restrict__ hact, int ldh,
                                             unsigned char* lds) {
   using S = Shape<BM>;
-  const int tid = threadIdx.x, lane = tid % WAVE, w = tid / WAVE;
+  const int tid = threadIdx.x, lane = tid % WAVE, w = __builtin_amdgcn_readfirstlane(tid / WAVE);  // wave index, known to be uniform
   const int wr = w >> 2, wc = w & 3;
   const uint16_t* ebase = wv.base + (size_t)ti.se * wv.expert_stride;
 
   // loader: a wave instruction fills 8 LDS rows (1 KB); lane/8 is the row, lane%8 the slot inside the
   // 128-byte row, which holds logical piece slot ^ ((row >> 1) & 7)
   const int lrow = lane >> 3, lpp = lane & 7;
-  const uint16_t* a_src[S::ALD];
+  uint32_t a_src[S::ALD];  // element offsets from x (the host checks that x spans less than 2^31 elements)
 #pragma unroll
   for (int i = 0; i < S::ALD; ++i) {
     const int lr = w * (BM / 8) + i * 8 + lrow;  // LDS row of the A tile
     int row = ti.row0 + lr;
     row = row < ti.row_end ? row : ti.row_end - 1;
-    a_src[i] = x + (size_t)p.row_token[row] * M + ((lpp ^ ((lr >> 1) & 7)) * 8);
+    a_src[i] = (uint32_t)p.row_token[row] * (uint32_t)M + ((lpp ^ ((lr >> 1) & 7)) * 8);
   }
   // B: LDS row w*32 + i*8 + lrow  ->  chunk 2*tc + w/4, f = w%2 (gate / up block), column-in-chunk
   // jc = ((w/2)%2)*32 + i*8 + lrow.  Blocks are [M/PW panels][64 j][PW m] (cc_worker.h).
@@ -361,7 +362,7 @@ __device__ __forceinline__ void gateup_body(const uint16_t* __restrict__ x, int 
     const int k0 = kt * BK;
 #pragma unroll
     for (int i = 0; i < S::ALD; ++i)
-      __builtin_amdgcn_global_load_lds(SI_GPTR(a_src[i] + k0), SI_LPTR(sa + i * 1024), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds(SI_GPTR(x + (a_src[i] + (uint32_t)k0)), SI_LPTR(sa + i * 1024), 16, 0, 0);
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int m0 = k0 + (((i & 1) ? (lc0 ^ 4) : lc0) * 8);
@@ -387,12 +388,28 @@ __device__ __forceinline__ void gateup_body(const uint16_t* __restrict__ x, int 
 }
 
 // A block picks the body for the rows its tile really has (whole-block branch), so a 40-row tile costs a 64-row
-// body and a 140-row tile a 192-row one.
+// body and a 140-row tile a 192-row one.  The 320-row body (five A fragments per wave, 144 KB of LDS, every one of
+// the 256 registers a wave may have at two waves per SIMD) exists for the last tile of an expert only.
 #define SI_PICK_BODY(rows, CALL)                 \
   if ((rows) <= 64) CALL(64);                    \
   else if ((rows) <= 128) CALL(128);             \
   else if ((rows) <= 192) CALL(192);             \
-  else CALL(256)
+  else if ((rows) <= 256) CALL(256);             \
+  else CALL(320)
+// The 4-bit bodies stop at 256 rows (their B operand passes through registers, which leaves no room for a fifth
+// A fragment): the rows a last tile holds beyond 256 take a second pass of the same block.  No wave still reads
+// the LDS ring when a body returns (its last barrier follows every fragment read), so the next pass may refill it.
+#define SI_PICK_BODY_2PASS(ti, CALL)                                  \
+  for (const int row_end_all_ = (ti).row_end;;) {                     \
+    (ti).row_end = min(row_end_all_, (ti).row0 + TILE_ROWS);          \
+    const int rows_ = (ti).row_end - (ti).row0;                       \
+    if (rows_ <= 64) CALL(64);                                        \
+    else if (rows_ <= 128) CALL(128);                                 \
+    else if (rows_ <= 192) CALL(192);                                 \
+    else CALL(256);                                                   \
+    if ((ti).row_end >= row_end_all_) break;                          \
+    (ti).row0 = (ti).row_end;                                         \
+  }
 
 __global__ __launch_bounds__(THREADS, 1) void k_prefill_gateup(const uint16_t* __restrict__ x, int M, Plan p,
                                                                int expert_sel, int x2_only, int n_cu,
@@ -423,28 +440,28 @@ __device__ __forceinline__ void down_body(const uint16_t* __restrict__ hact, int
   const int nt = inner % n_ntiles, split = inner / n_ntiles;
   const int c_begin = (int)((long)wv.n_chunks * split / n_split), c_end = (int)((long)wv.n_chunks * (split + 1) / n_split);
   if (c_begin >= c_end && accumulate) return;  // nothing to add
-  const int tid = threadIdx.x, lane = tid % WAVE, w = tid / WAVE;
+  const int tid = threadIdx.x, lane = tid % WAVE, w = __builtin_amdgcn_readfirstlane(tid / WAVE);  // wave index, known to be uniform
   const int wr = w >> 2, wc = w & 3;
   const int n0 = nt * BN;
   const uint16_t* ebase = wv.base + (size_t)ti.se * wv.expert_stride;
   float* out = yp + (size_t)split * slab_stride;
 
   const int lrow = lane >> 3, lpp = lane & 7;
-  const uint16_t* a_src[S::ALD];
+  uint32_t a_src[S::ALD];  // element offsets from hact (the host checks that it spans less than 2^31 elements)
 #pragma unroll
   for (int i = 0; i < S::ALD; ++i) {
     const int lr = w * (BM / 8) + i * 8 + lrow;
     int row = ti.row0 + lr;
     row = row < ti.row_end ? row : ti.row_end - 1;
-    a_src[i] = hact + (size_t)row * ldh + wv.col0 + ((lpp ^ ((lr >> 1) & 7)) * 8);
+    a_src[i] = (uint32_t)row * (uint32_t)ldh + wv.col0 + ((lpp ^ ((lr >> 1) & 7)) * 8);
   }
   // B: wave w loads group q = w of the chunk's down block ([M/NW tiles][8 q][NW m][8 i]), 4 x 64 output columns
   const int NW = ntile_width(M);
-  size_t b_off[4];
+  uint32_t b_off[4];  // inside one chunk's down block: below 64 * M elements
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const int n = min(n0 + i * 64 + lane, M - 1);
-    b_off[i] = (((size_t)(n / NW) * 8 + w) * NW + (n % NW)) * 8;
+    b_off[i] = (((uint32_t)(n / NW) * 8 + w) * NW + (n % NW)) * 8;
   }
 
   auto issue = [&](int stage, int kt) {
@@ -454,7 +471,7 @@ __device__ __forceinline__ void down_body(const uint16_t* __restrict__ hact, int
     const uint16_t* dblk = ebase + (size_t)(wv.chunk0 + c) * 3 * CHUNK_J * M + (size_t)2 * CHUNK_J * M;
 #pragma unroll
     for (int i = 0; i < S::ALD; ++i)
-      __builtin_amdgcn_global_load_lds(SI_GPTR(a_src[i] + c * CHUNK_J), SI_LPTR(sa + i * 1024), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds(SI_GPTR(hact + (a_src[i] + (uint32_t)(c * CHUNK_J))), SI_LPTR(sa + i * 1024), 16, 0, 0);
 #pragma unroll
     for (int i = 0; i < 4; ++i)
       __builtin_amdgcn_global_load_lds(SI_GPTR(dblk + b_off[i]), SI_LPTR(sb + i * 1024), 16, 0, 0);
@@ -510,7 +527,7 @@ __device__ __forceinline__ void gateup_body_q4(const uint16_t* __restrict__ x, i
                                                const WeightView& wv, uint16_t* __restrict__ hact, int ldh,
                                                unsigned char* lds) {
   using S = Shape<BM>;
-  const int tid = threadIdx.x, lane = tid % WAVE, w = tid / WAVE;
+  const int tid = threadIdx.x, lane = tid % WAVE, w = __builtin_amdgcn_readfirstlane(tid / WAVE);  // wave index, known to be uniform
   const int wr = w >> 2, wc = w & 3;
   const unsigned char* ebase = reinterpret_cast<const unsigned char*>(wv.base + (size_t)ti.se * wv.expert_stride);
 
@@ -581,7 +598,7 @@ __global__ __launch_bounds__(THREADS, 1) void k_prefill_gateup_q4(const uint16_t
   if (!block_tile(p, expert_sel, x2_only, n_ctiles, n_cu, tc, ti)) return;
   if (!storage_index(wv, ti.e, ti.se)) return;
 #define SI_CALL_GU(BMV) gateup_body_q4<BMV>(x, M, p, tc, ti, wv, hact, ldh, lds)
-  SI_PICK_BODY(ti.row_end - ti.row0, SI_CALL_GU);
+  SI_PICK_BODY_2PASS(ti, SI_CALL_GU);
 #undef SI_CALL_GU
 }
 
@@ -593,7 +610,7 @@ __device__ __forceinline__ void down_body_q4(const uint16_t* __restrict__ hact, 
   const int nt = inner % n_ntiles, split = inner / n_ntiles;
   const int c_begin = (int)((long)wv.n_chunks * split / n_split), c_end = (int)((long)wv.n_chunks * (split + 1) / n_split);
   if (c_begin >= c_end && accumulate) return;
-  const int tid = threadIdx.x, lane = tid % WAVE, w = tid / WAVE;
+  const int tid = threadIdx.x, lane = tid % WAVE, w = __builtin_amdgcn_readfirstlane(tid / WAVE);  // wave index, known to be uniform
   const int wr = w >> 2, wc = w & 3;
   const int n0 = nt * BN;
   const unsigned char* ebase = reinterpret_cast<const unsigned char*>(wv.base + (size_t)ti.se * wv.expert_stride);
@@ -675,7 +692,7 @@ __global__ __launch_bounds__(THREADS, 1) void k_prefill_down_q4(const uint16_t* 
   if (!block_tile(p, expert_sel, x2_only, n_ntiles * n_split, n_cu, inner, ti)) return;
   if (!storage_index(wv, ti.e, ti.se)) return;
 #define SI_CALL_DN(BMV) down_body_q4<BMV>(hact, ldh, M, inner, ti, n_ntiles, n_split, wv, yp, slab_stride, accumulate, lds)
-  SI_PICK_BODY(ti.row_end - ti.row0, SI_CALL_DN);
+  SI_PICK_BODY_2PASS(ti, SI_CALL_DN);
 #undef SI_CALL_DN
 }
 

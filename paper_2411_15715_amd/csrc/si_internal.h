@@ -17,15 +17,23 @@ inline size_t chunk_bytes(int M) { return chunk_elems(M) * 2; }
 
 constexpr int MAX_EXPERTS = 256;      // routed experts (a shared expert adds one more table entry)
 constexpr int ROUTE_THREADS = 1024;   // block size of the assignment kernel
-constexpr int TILE_ROWS = 256;        // rows per row tile of the prefill GEMMs (the last tile of an expert holds what is left)
+constexpr int TILE_ROWS = 256;        // rows per row tile of the prefill GEMMs (the last tile of an expert: see n_row_tiles)
 constexpr int MAX_KSPLIT = 4;         // k-splits (output slabs) of the prefill down projection
 constexpr int DECODE_TB = 4;          // most tokens handled per weight pass in the GEMV kernels
 constexpr int DOWN_SLOTS = 32;        // j-splits of the decode down projection per part
 
 // Row tiles of an expert (or of its X2 rows) with `rows` rows.  The GEMM kernels run, per tile, the body
-// instantiated for the rows the tile really has (64, 128, 192 or 256): a block streams its weight tile whatever
+// instantiated for the rows the tile really has (64, 128, 192, 256 or 320): a block streams its weight tile whatever
 // the number of rows, so an expert with 140 rows gets one 192-row block, not two blocks of 128.
-inline SI_HD int n_row_tiles(int rows) { return rows <= 0 ? 0 : (rows + TILE_ROWS - 1) / TILE_ROWS; }
+// A tile costs nearly the same whether it holds 10 rows or 256 (it streams the same weights, and its ring of LDS
+// stages is latency bound when the rows are few: measured, 128 extra tiles of 5 rows cost a 2048-tile GEMM as much
+// as 128 extra tiles of 256), so a remainder of at most TILE_ROWS_SPILL rows rides with the last full tile instead
+// of becoming a tile of its own.  With a balanced router and a batch that gives each expert a multiple of 256 rows
+// on average, about half the experts end a few rows past such a multiple.
+constexpr int TILE_ROWS_SPILL = 64;  // the last tile of an expert also takes up to this many rows beyond TILE_ROWS
+inline SI_HD int n_row_tiles(int rows) {
+  return rows <= 0 ? 0 : rows <= TILE_ROWS ? 1 : (rows - TILE_ROWS_SPILL + TILE_ROWS - 1) / TILE_ROWS;
+}
 
 // Device-side result of the token assignment plus the launch tables derived from it.
 // Expert tables have EX = E + (shared ? 1 : 0) entries; the shared expert is entry E and owns the
