@@ -48,6 +48,26 @@ template <int BM> struct Shape {
   // than stages.
 };
 
+// Ring shapes of the streaming loop, which tiles of at most 192 rows run.  Such a tile is latency bound, not
+// matrix-core bound: what it needs is weight bytes in flight, and the LDS ring above holds at most two k-tiles
+// of them (64 KB per CU; the chip needs about 25 MB in flight to saturate its HBM, i.e. 100 KB per CU).  Here only
+// the A operand keeps a ring of DA stages in LDS; the B operand (the weights) travels through registers, R = DA - 1
+// k-tiles of it in flight per wave, and is written into one of two B stages in LDS one iteration before it is read.
+template <int BM> struct StreamShape {
+  static constexpr int DA = BM <= 64 ? 6 : BM <= 128 ? 5 : 3;  // A stages = prefetch distance in k-tiles
+  static constexpr int R = DA - 1;                              // register sets holding B tiles in flight
+  static constexpr int A_STAGE = BM * 128;
+  static constexpr int B0 = DA * A_STAGE;                       // offset of the two B stages
+  static constexpr int LDS = B0 + 2 * B_BYTES;                  // 112, 144, 136 KB for BM = 64, 128, 192
+  static constexpr int GL = 4;                                  // B register loads per wave and k-tile
+  static constexpr int ALD = BM / 64;                           // A load instructions per wave and k-tile
+  // waits of the steady state: a wave issues, per k-tile and in this order, GL register loads (B) and ALD
+  // direct-to-LDS loads (A); younger than B of tile t+1 are A of tile t+1 and the tiles t+2 .. t+DA-1
+  static constexpr int WAIT_B = (DA - 2) * (GL + ALD) + ALD;
+  static constexpr int WAIT_A = (DA - 2) * (GL + ALD);
+  static_assert(LDS <= KERNEL_LDS && WAIT_B < 64, "ring does not fit");
+};
+
 __device__ inline uint16_t f32_to_bf16(float f) {
   uint32_t u = __float_as_uint(f);
   u += 0x7fffu + ((u >> 16) & 1u);
@@ -107,7 +127,9 @@ __device__ inline bool map_block(int b, int N, int n_cu, int& L, int& half, int&
   return true;
 }
 
-struct TileInfo { int e, row0, row_end, se; };  // se: index of the expert inside the launch's weight storage
+// se: index of the expert inside the launch's weight storage; solo: the tile holds all rows of its expert, so
+// nobody else reads its weight tiles (they come from HBM, not from a sibling's trail in the L2)
+struct TileInfo { int e, row0, row_end, se, solo; };
 
 // Number of logical tile ids with work in this launch (row tiles x inner tiles).
 __device__ inline int launch_extent(const Plan& p, int expert_sel, int x2_only, int n_inner) {
@@ -147,6 +169,7 @@ __device__ inline bool decode_tile(const Plan& p, int expert_sel, int x2_only, i
   ti.e = e;
   ti.row0 = start + r * TILE_ROWS;
   ti.row_end = r == nrt - 1 ? end : ti.row0 + TILE_ROWS;
+  ti.solo = nrt == 1;
   return true;
 }
 
@@ -159,6 +182,7 @@ __device__ inline bool block_tile(const Plan& p, int expert_sel, int x2_only, in
   if (halves == 2) {
     const int rows = ti.row_end - ti.row0;
     if (rows <= 128) return half == 0;  // too few rows to share: the first block takes them all
+    ti.solo = 0;
     const int hs = ((rows + 1) / 2 + 31) / 32 * 32;
     ti.row0 += half * hs;
     ti.row_end = min(ti.row_end, ti.row0 + hs);
@@ -196,6 +220,16 @@ __device__ inline bool block_tile(const Plan& p, int expert_sel, int x2_only, in
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[buf][i], fb[buf][j], acc[i][j], 0, 0, 0);         \
   };
 
+// register loads and the dependency tie used by the loops whose B operand travels through registers
+__device__ inline void gload_b128(u32x4& q, const void* p) {
+  asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(q) : "v"(p) : "memory");
+}
+__device__ inline void gload_u16(uint32_t& z, const void* p) {
+  asm volatile("global_load_ushort %0, %1, off" : "=v"(z) : "v"(p) : "memory");
+}
+struct BRegs { u32x4 q[4]; };  // one lane's share of a bf16 B tile
+__device__ inline void bready(BRegs& r) { asm volatile("" : "+v"(r.q[0]), "+v"(r.q[1]), "+v"(r.q[2]), "+v"(r.q[3])::"memory"); }
+
 #define SI_GEMM_MAIN_LOOP(NK, ISSUE)                                                                  \
   {                                                                                                              \
     const int nk_ = (NK);                                                                                        \
@@ -223,14 +257,77 @@ __device__ inline bool block_tile(const Plan& p, int expert_sel, int x2_only, in
     }                                                                                                            \
   }
 
-// register loads and the dependency tie used by the 4-bit loop below
-__device__ inline void gload_b128(u32x4& q, const void* p) {
-  asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(q) : "v"(p) : "memory");
-}
-__device__ inline void gload_u16(uint32_t& z, const void* p) {
-  asm volatile("global_load_ushort %0, %1, off" : "=v"(z) : "v"(p) : "memory");
-}
 struct Q4Regs { u32x4 q; uint32_t z; };  // codes and scale of one lane's share of a B tile
+
+// The streaming loop (StreamShape).  ISSUE_A(a_stage, kt): direct-to-LDS loads of A tile kt; BLOAD(kt, regs): register
+// loads of B tile kt; BSTORE(b_stage, regs, i): 16-byte LDS store of the i-th of them.  Iteration `it` computes tile
+// `it` (A stage it % DA, B stage it % 2), writes B of tile it+1 (fetched DA-1 iterations earlier) into the other B
+// stage between its matrix instructions, and after its barrier fetches tile it+DA into the A stage and the register
+// set it has just released.  The loop is unrolled by R so that every register set is named statically.  Near the end
+// of the contraction (fewer than DA-1 tiles ahead) the hand-counted waits no longer hold and the loop drains instead.
+#define SI_GEMM_DECLS_STREAM(BFRAG_OFF)                                                                          \
+  using SS = StreamShape<BM>;                                                                                    \
+  f32x16 acc[S::FA][2];                                                                                          \
+  _Pragma("unroll") for (int i = 0; i < S::FA; ++i) _Pragma("unroll") for (int j = 0; j < 2; ++j)                \
+      _Pragma("unroll") for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;                                         \
+  bf16x8 fa[2][S::FA], fb[2][2];                                                                                 \
+  auto ldfrag = [&](int sta, int stb, int ks, int buf) {                                                         \
+    const unsigned char* sa = lds + sta * SS::A_STAGE;                                                           \
+    const unsigned char* sb = lds + SS::B0 + stb * B_BYTES;                                                      \
+    const int pc = ks * 2 + (lane >> 5);                                                                         \
+    _Pragma("unroll") for (int i = 0; i < S::FA; ++i) fa[buf][i] = as_bf16x8(                                    \
+        *reinterpret_cast<const u32x4*>(sa + swz(wr * (BM / 2) + i * 32 + (lane & 31), pc)));                    \
+    _Pragma("unroll") for (int j = 0; j < 2; ++j) fb[buf][j] = as_bf16x8(                                        \
+        *reinterpret_cast<const u32x4*>(sb + BFRAG_OFF(wc * 64 + j * 32 + (lane & 31), pc)));                    \
+  };                                                                                                             \
+  auto mma = [&](int buf) {                                                                                      \
+    _Pragma("unroll") for (int i = 0; i < S::FA; ++i) _Pragma("unroll") for (int j = 0; j < 2; ++j)              \
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[buf][i], fb[buf][j], acc[i][j], 0, 0, 0);         \
+  };
+
+#define SI_GEMM_MAIN_LOOP_STREAM(NK, ISSUE_A, BLOAD, BSTORE)                                                     \
+  {                                                                                                              \
+    const int nk_ = (NK);                                                                                        \
+    BRegs rs[SS::R];                                                                                             \
+    /* tile 0 goes straight through; then the tiles 1 .. DA-1 are set off */                                     \
+    BLOAD(0, rs[0]); ISSUE_A(0, 0);                                                                              \
+    wait_vmcnt<SS::ALD>(); bready(rs[0]);                                                                        \
+    _Pragma("unroll") for (int i = 0; i < 4; ++i) BSTORE(0, rs[0], i);                                           \
+    _Pragma("unroll") for (int t = 1; t < SS::DA; ++t) if (t < nk_) { BLOAD(t, rs[t % SS::R]); ISSUE_A(t, t); }  \
+    if (SS::DA - 1 < nk_) wait_vmcnt<(SS::DA - 1) * (SS::GL + SS::ALD)>(); else wait_vmcnt<0>(); /* A of tile 0 */ \
+    wait_lgkmcnt0();                                                                                             \
+    block_barrier();                                                                                             \
+    ldfrag(0, 0, 0, 0);                                                                                          \
+    int sta = 0;                                                                                                 \
+    auto step = [&](int it, BRegs& rc) { /* rc: B of tile it+1 */                                                \
+      const int stb = it & 1;                                                                                    \
+      const int nsta = sta + 1 == SS::DA ? 0 : sta + 1;                                                          \
+      const bool full = it + SS::DA - 1 < nk_; /* the tiles it+1 .. it+DA-1 have all been set off */             \
+      const bool more = it + 1 < nk_;                                                                            \
+      ldfrag(sta, stb, 1, 1); mma(0);                                                                            \
+      if (full) wait_vmcnt<SS::WAIT_B>(); else wait_vmcnt<0>();                                                  \
+      bready(rc);                                                                                                \
+      if (more) BSTORE(stb ^ 1, rc, 0);                                                                          \
+      ldfrag(sta, stb, 2, 0); mma(1);                                                                            \
+      if (more) BSTORE(stb ^ 1, rc, 1);                                                                          \
+      ldfrag(sta, stb, 3, 1); mma(0);                                                                            \
+      if (more) { BSTORE(stb ^ 1, rc, 2); BSTORE(stb ^ 1, rc, 3); }                                              \
+      /* A of tile it+1 landed, B of tile it+1 written, every read of the two stages complete */                 \
+      if (full) wait_vmcnt<SS::WAIT_A>(); else wait_vmcnt<0>();                                                  \
+      wait_lgkmcnt0();                                                                                           \
+      block_barrier();                                                                                           \
+      if (more) ldfrag(nsta, stb ^ 1, 0, 0);                                                                     \
+      if (it + SS::DA < nk_) { BLOAD(it + SS::DA, rc); ISSUE_A(sta, it + SS::DA); }                              \
+      __builtin_amdgcn_s_setprio(1);                                                                             \
+      mma(1);                                                                                                    \
+      __builtin_amdgcn_s_setprio(0);                                                                             \
+      sta = nsta;                                                                                                \
+    };                                                                                                           \
+    for (int it = 0; it < nk_; it += SS::R) {                                                                    \
+      _Pragma("unroll") for (int u = 0; u < SS::R; ++u) if (it + u < nk_) step(it + u, rs[(u + 1) % SS::R]);     \
+    }                                                                                                            \
+  }
+
 
 // The same loop for weights in the 4-bit storage form.  The A operand still arrives by direct global->LDS loads;
 // the B operand cannot (it has to be turned into bf16 on the way), so every lane fetches 16 bytes of codes (32
@@ -328,7 +425,7 @@ __device__ inline uint32_t q4_pair(uint32_t bytes, int b0, int b1, float sc, flo
 // f = 0 the gate row and f = 1 the up row of column 32 wc + jj; SiLU(gate)*up is then formed in
 // registers from the two accumulator tiles of a wave.
 // ---------------------------------------------------------------------------------------------
-template <int BM>
+template <int BM, bool STREAM>
 __device__ __forceinline__ void gateup_body(const uint16_t* __restrict__ x, int M, const Plan& p, int tc, const TileInfo& ti,
                                             const WeightView& wv, uint16_t* __restrict__ hact, int ldh,
                                             unsigned char* lds) {
@@ -370,32 +467,82 @@ __device__ __forceinline__ void gateup_body(const uint16_t* __restrict__ x, int 
                                        SI_LPTR(sb + i * 1024), 16, 0, 0);
     }
   };
-  SI_GEMM_DECLS(SI_BOFF_SWZ)
-  SI_GEMM_MAIN_LOOP(M / BK, issue)
   // epilogue: element (row 8*(r/4) + 4*(lane/32) + r%4, column lane%32) of each 32x32 tile;
   // acc[i][0] is the gate tile and acc[i][1] the up tile of the same 32 hidden columns
-  const int jl = wc * 32 + (lane & 31);  // hidden column inside the 128-column tile
-  if (2 * tc + (jl >> 6) < wv.n_chunks) {
-    const int col = wv.col0 + tc * 128 + jl;
+  auto epilogue = [&](const f32x16 (&acc)[S::FA][2]) {
+    const int jl = wc * 32 + (lane & 31);  // hidden column inside the 128-column tile
+    if (2 * tc + (jl >> 6) < wv.n_chunks) {
+      const int col = wv.col0 + tc * 128 + jl;
 #pragma unroll
-    for (int i = 0; i < S::FA; ++i)
+      for (int i = 0; i < S::FA; ++i)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int row = ti.row0 + wr * (BM / 2) + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-        if (row < ti.row_end) hact[(size_t)row * ldh + col] = f32_to_bf16(silu_f(acc[i][0][r]) * acc[i][1][r]);
+        for (int r = 0; r < 16; ++r) {
+          const int row = ti.row0 + wr * (BM / 2) + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+          if (row < ti.row_end) hact[(size_t)row * ldh + col] = f32_to_bf16(silu_f(acc[i][0][r]) * acc[i][1][r]);
+        }
+    }
+  };
+  if constexpr (STREAM) {
+    // the same loads, with B through registers: lane (lrow, lpp) of instruction i fetches the piece that the
+    // direct load would have put at byte lane * 16 of the wave's KB i, and stores it there
+    auto issue_a = [&](int sta, int kt) {
+      unsigned char* sa = lds + sta * StreamShape<BM>::A_STAGE + w * (BM / 8) * 128;
+#pragma unroll
+      for (int i = 0; i < S::ALD; ++i)
+        __builtin_amdgcn_global_load_lds(SI_GPTR(x + (a_src[i] + (uint32_t)(kt * BK))), SI_LPTR(sa + i * 1024), 16, 0, 0);
+    };
+    auto bload = [&](int kt, BRegs& r) {
+      const int k0 = kt * BK;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int m0 = k0 + (((i & 1) ? (lc0 ^ 4) : lc0) * 8);
+        gload_b128(r.q[i], b_blk + ((size_t)(m0 / PW) * CHUNK_J + jc0 + i * 8) * PW + (m0 % PW));
       }
+    };
+    auto bstore = [&](int stb, const BRegs& r, int i) {
+      lds_store_b128(lds + StreamShape<BM>::B0 + stb * B_BYTES + w * 4096 + i * 1024 + lane * 16, r.q[i]);
+    };
+    SI_GEMM_DECLS_STREAM(SI_BOFF_SWZ)
+    SI_GEMM_MAIN_LOOP_STREAM(M / BK, issue_a, bload, bstore)
+    epilogue(acc);
+  } else {
+    SI_GEMM_DECLS(SI_BOFF_SWZ)
+    SI_GEMM_MAIN_LOOP(M / BK, issue)
+    epilogue(acc);
   }
 }
 
 // A block picks the body for the rows its tile really has (whole-block branch), so a 40-row tile costs a 64-row
 // body and a 140-row tile a 192-row one.  The 320-row body (five A fragments per wave, 144 KB of LDS, every one of
-// the 256 registers a wave may have at two waves per SIMD) exists for the last tile of an expert only.
-#define SI_PICK_BODY(rows, CALL)                 \
-  if ((rows) <= 64) CALL(64);                    \
-  else if ((rows) <= 128) CALL(128);             \
-  else if ((rows) <= 192) CALL(192);             \
-  else if ((rows) <= 256) CALL(256);             \
-  else CALL(320)
+// the 256 registers a wave may have at two waves per SIMD) exists for the last tile of an expert only.  A tile that
+// holds all rows of its expert, at most 192, runs the streaming loop (StreamShape): its weights come from HBM.
+// (Two spellings of the same choice: with the 320-row body at the very limit of the register file, the order of the
+// tests decides where the compiler places what several bodies have in common, and each kernel has one order that
+// leaves it without a spill; ensure_lds_attr() refuses a build that has one.)
+#define SI_PICK_BODY_GU(ti, CALL)                               \
+  {                                                             \
+    const int rows_ = (ti).row_end - (ti).row0;                 \
+    if (rows_ <= 64) CALL(64, true);                            \
+    else if ((ti).solo && rows_ <= 192) {                       \
+      if (rows_ <= 128) CALL(128, true);                        \
+      else CALL(192, true);                                     \
+    } else if (rows_ <= 128) CALL(128, false);                  \
+    else if (rows_ <= 192) CALL(192, false);                    \
+    else if (rows_ <= 256) CALL(256, false);                    \
+    else CALL(320, false);                                      \
+  }
+#define SI_PICK_BODY_DN(ti, CALL)                               \
+  {                                                             \
+    const int rows_ = (ti).row_end - (ti).row0;                 \
+    if (rows_ > 256) CALL(320, false);                          \
+    else if (rows_ > 192) CALL(256, false);                     \
+    else if (rows_ <= 64) CALL(64, true);                       \
+    else if ((ti).solo) {                                       \
+      if (rows_ <= 128) CALL(128, true);                        \
+      else CALL(192, true);                                     \
+    } else if (rows_ <= 128) CALL(128, false);                  \
+    else CALL(192, false);                                      \
+  }
 // The 4-bit bodies stop at 256 rows (their B operand passes through registers, which leaves no room for a fifth
 // A fragment): the rows a last tile holds beyond 256 take a second pass of the same block.  No wave still reads
 // the LDS ring when a body returns (its last barrier follows every fragment read), so the next pass may refill it.
@@ -420,8 +567,8 @@ __global__ __launch_bounds__(THREADS, 1) void k_prefill_gateup(const uint16_t* _
   TileInfo ti;
   if (!block_tile(p, expert_sel, x2_only, n_ctiles, n_cu, tc, ti)) return;
   if (!storage_index(wv, ti.e, ti.se)) return;
-#define SI_CALL_GU(BMV) gateup_body<BMV>(x, M, p, tc, ti, wv, hact, ldh, lds)
-  SI_PICK_BODY(ti.row_end - ti.row0, SI_CALL_GU);
+#define SI_CALL_GU(BMV, ST) gateup_body<BMV, ST>(x, M, p, tc, ti, wv, hact, ldh, lds)
+  SI_PICK_BODY_GU(ti, SI_CALL_GU)
 #undef SI_CALL_GU
 }
 
@@ -432,7 +579,7 @@ __global__ __launch_bounds__(THREADS, 1) void k_prefill_gateup(const uint16_t* _
 // LDS ([group][256 m] x 16 bytes), read conflict free by consecutive lanes.
 // Output slab `split` of yp: rows x M fp32; overwritten or accumulated.
 // ---------------------------------------------------------------------------------------------
-template <int BM>
+template <int BM, bool STREAM>
 __device__ __forceinline__ void down_body(const uint16_t* __restrict__ hact, int ldh, int M, int inner, const TileInfo& ti,
                                           int n_ntiles, int n_split, const WeightView& wv, float* __restrict__ yp,
                                           size_t slab_stride, int accumulate, unsigned char* lds) {
@@ -457,11 +604,12 @@ __device__ __forceinline__ void down_body(const uint16_t* __restrict__ hact, int
   }
   // B: wave w loads group q = w of the chunk's down block ([M/NW tiles][8 q][NW m][8 i]), 4 x 64 output columns
   const int NW = ntile_width(M);
+  const int nw_shift = __builtin_ctz(NW);
   uint32_t b_off[4];  // inside one chunk's down block: below 64 * M elements
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const int n = min(n0 + i * 64 + lane, M - 1);
-    b_off[i] = (((uint32_t)(n / NW) * 8 + w) * NW + (n % NW)) * 8;
+    b_off[i] = (((uint32_t)(n >> nw_shift) * 8 + w) * NW + (n & (NW - 1))) * 8;  // NW is a power of two
   }
 
   auto issue = [&](int stage, int kt) {
@@ -476,23 +624,50 @@ __device__ __forceinline__ void down_body(const uint16_t* __restrict__ hact, int
     for (int i = 0; i < 4; ++i)
       __builtin_amdgcn_global_load_lds(SI_GPTR(dblk + b_off[i]), SI_LPTR(sb + i * 1024), 16, 0, 0);
   };
-  if (c_begin < c_end) {
-    SI_GEMM_DECLS(SI_BOFF_K8)
-    SI_GEMM_MAIN_LOOP(c_end - c_begin, issue)
+  auto epilogue = [&](const f32x16 (&acc)[S::FA][2]) {
+    // (the lane index is made opaque here so that the output addresses are formed after the main loop: formed
+    // ahead of it they are live through it, which the 320-row body has no registers for)
+    int el = lane;
+    asm volatile("" : "+v"(el));
 #pragma unroll
     for (int i = 0; i < S::FA; ++i)
 #pragma unroll
       for (int j = 0; j < 2; ++j) {
-        const int m = n0 + wc * 64 + j * 32 + (lane & 31);
+        const int m = n0 + wc * 64 + j * 32 + (el & 31);
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          const int row = ti.row0 + wr * (BM / 2) + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+          const int row = ti.row0 + wr * (BM / 2) + i * 32 + 8 * (r >> 2) + 4 * (el >> 5) + (r & 3);
           if (row < ti.row_end && m < M) {
             float* dst = out + (size_t)row * M + m;
             *dst = accumulate ? *dst + acc[i][j][r] : acc[i][j][r];
           }
         }
       }
+  };
+  if (c_begin < c_end) {
+    if constexpr (STREAM) {
+      auto issue_a = [&](int sta, int kt) {
+        unsigned char* sa = lds + sta * StreamShape<BM>::A_STAGE + w * (BM / 8) * 128;
+#pragma unroll
+        for (int i = 0; i < S::ALD; ++i)
+          __builtin_amdgcn_global_load_lds(SI_GPTR(hact + (a_src[i] + (uint32_t)((c_begin + kt) * CHUNK_J))), SI_LPTR(sa + i * 1024), 16, 0, 0);
+      };
+      auto bload = [&](int kt, BRegs& r) {
+        const uint16_t* dblk = ebase + (size_t)(wv.chunk0 + c_begin + kt) * 3 * CHUNK_J * M + (size_t)2 * CHUNK_J * M;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) gload_b128(r.q[i], dblk + b_off[i]);
+      };
+      auto bstore = [&](int stb, const BRegs& r, int i) {
+        lds_store_b128(lds + StreamShape<BM>::B0 + stb * B_BYTES + w * 4096 + i * 1024 + lane * 16, r.q[i]);
+      };
+      SI_GEMM_DECLS_STREAM(SI_BOFF_K8)
+      SI_GEMM_MAIN_LOOP_STREAM(c_end - c_begin, issue_a, bload, bstore)
+      epilogue(acc);
+    } else {
+      SI_GEMM_DECLS(SI_BOFF_K8)
+      SI_GEMM_MAIN_LOOP(c_end - c_begin, issue)
+      epilogue(acc);
+    }
   } else {
     // an empty k-split of an overwriting launch still has to define its slab
     for (int i = tid; i < BM * BN; i += THREADS) {
@@ -513,8 +688,8 @@ __global__ __launch_bounds__(THREADS, 1) void k_prefill_down(const uint16_t* __r
   // (XCD ranges: one expert's Hact rows, the A operand, stay in one L2)
   if (!block_tile(p, expert_sel, x2_only, n_ntiles * n_split, n_cu, inner, ti)) return;
   if (!storage_index(wv, ti.e, ti.se)) return;
-#define SI_CALL_DN(BMV) down_body<BMV>(hact, ldh, M, inner, ti, n_ntiles, n_split, wv, yp, slab_stride, accumulate, lds)
-  SI_PICK_BODY(ti.row_end - ti.row0, SI_CALL_DN);
+#define SI_CALL_DN(BMV, ST) down_body<BMV, ST>(hact, ldh, M, inner, ti, n_ntiles, n_split, wv, yp, slab_stride, accumulate, lds)
+  SI_PICK_BODY_DN(ti, SI_CALL_DN)
 #undef SI_CALL_DN
 }
 

@@ -34,6 +34,24 @@ def test_ring_depth_bf16(oracle, d_model, d_ff):
         L.close()
 
 
+@pytest.mark.parametrize("d_model,d_ff", [(384, 1536), (448, 1792), (512, 2048), (1024, 4096)])
+def test_ring_depth_streaming(oracle, d_model, d_ff):
+    """Tiles of at most 192 rows run a loop whose weights travel through registers, up to five k-tiles ahead: its
+    hand-counted waits reach their steady state only with at least 6 (64 rows), 5 (128) or 3 (192) k-tiles, so
+    here FC1 has 6, 7, 8 and 16 k-tiles and a k-split of FC2 as many."""
+    cfg = synth.scaled(synth.CONFIGS["llama2_70b"], d_model=d_model, d_ff=d_ff, seed=300 + d_model)
+    w = synth.make_weights(cfg)
+    L = GpuLayer(cfg, w, (1.0, 0.0, 0.0), max_tokens=max(ROWS))
+    try:
+        xp = synth.make_tokens(cfg, max(ROWS))
+        yo = oracle.layer_forward(xp, w["w_gate"], w["w_up"], w["w_down"])
+        for T in ROWS:
+            print("ring depth streaming M=%d H=%d T=%d" % (d_model, d_ff, T), flush=True)
+            assert_parity(L.forward(xp[:T], None, mode=si.SI_PREFILL), yo[:T])
+    finally:
+        L.close()
+
+
 @pytest.mark.parametrize("d_model", [64, 128, 192, 256])
 @pytest.mark.parametrize("d_ff", [64, 512, 768, 1024])
 def test_ring_depth_q4(oracle, d_model, d_ff):
