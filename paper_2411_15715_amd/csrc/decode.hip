@@ -146,7 +146,17 @@ __global__ __launch_bounds__(GU_THREADS) void k_decode_gateup(const uint16_t* __
   __shared__ typename std::conditional<FUSED != 0, BlockRoute, int>::type s_br;  // (4 bytes when the tables are given)
   int e, r0, r1;
   const int* row_token = p.row_token;
+  constexpr int X_EARLY_MAX = 4;  // 16-byte pieces per thread: d_model <= 8192
+  u32x4 x_reg[X_EARLY_MAX];
+  bool x_early = false;
   if constexpr (FUSED != 0) {
+    // with a single token every row is token 0
+    x_early = TB == 1 && fr.T == 1 && M / 8 <= X_EARLY_MAX * GU_THREADS;
+    if (x_early) {
+#pragma unroll
+      for (int i = 0; i < X_EARLY_MAX; ++i)
+        if ((int)threadIdx.x + i * GU_THREADS < M / 8) x_reg[i] = reinterpret_cast<const u32x4*>(x)[threadIdx.x + i * GU_THREADS];
+    }
     BlockRoute& br = s_br;
     block_route(fr, br, p, blockIdx.x == 0 && blockIdx.y == 0);
     if (expert_sel >= 0) {
@@ -178,13 +188,35 @@ __global__ __launch_bounds__(GU_THREADS) void k_decode_gateup(const uint16_t* __
   const int PW = panel_width(M), PW8 = PW / 8;
   const int jcol = wv.col0 + (blockIdx.x / blocks_per_chunk) * CHUNK_J + jj0;
 
+  // One-row launches (TB == 1, the generation phase proper): the weights of a wave's first step are fetched before
+  // the row of x is staged (and, with a single token, x before the token assignment is derived), so that a block's
+  // first bytes are on their way while it waits, not after.  With more rows per pass the peeled first step costs
+  // registers, i.e. waves per SIMD, and the plain loop stays.
+  constexpr bool EARLY = TB == 1;
+  u32x4 wg[GU_JPW], wu[GU_JPW];
+  auto wload = [&](int c) {
+    const size_t poff = (size_t)(c / PW8) * CHUNK_J * PW8 + (c % PW8);  // panel base + position in the row segment
+#pragma unroll
+    for (int j = 0; j < GU_JPW; ++j) {
+      wg[j] = __builtin_nontemporal_load(gblk + poff + (size_t)(jj0 + j) * PW8);
+      wu[j] = __builtin_nontemporal_load(ublk + poff + (size_t)(jj0 + j) * PW8);
+    }
+  };
+  if (EARLY && lane < M8) wload(lane);
+
   for (int rb = r0; rb < r1; rb += TB) {
     const int nt = min(TB, r1 - rb);
     __syncthreads();
-    for (int i = tid; i < nt * M8; i += GU_THREADS) {
-      int tb = i / M8, c = i % M8;
-      int tok = row_token[rb + tb];
-      s_x[tb * M8 + c] = reinterpret_cast<const u32x4*>(x + (size_t)tok * M)[c];
+    if (x_early) {
+#pragma unroll
+      for (int i = 0; i < X_EARLY_MAX; ++i)
+        if (tid + i * GU_THREADS < M8) s_x[tid + i * GU_THREADS] = x_reg[i];
+    } else {
+      for (int i = tid; i < nt * M8; i += GU_THREADS) {
+        int tb = i / M8, c = i % M8;
+        int tok = row_token[rb + tb];
+        s_x[tb * M8 + c] = reinterpret_cast<const u32x4*>(x + (size_t)tok * M)[c];
+      }
     }
     __syncthreads();
     float ag[GU_JPW][TB], au[GU_JPW][TB];
@@ -192,14 +224,7 @@ __global__ __launch_bounds__(GU_THREADS) void k_decode_gateup(const uint16_t* __
     for (int j = 0; j < GU_JPW; ++j)
 #pragma unroll
       for (int tb = 0; tb < TB; ++tb) { ag[j][tb] = 0.f; au[j][tb] = 0.f; }
-    for (int c = lane; c < M8; c += WAVE) {
-      u32x4 wg[GU_JPW], wu[GU_JPW];
-      const size_t poff = (size_t)(c / PW8) * CHUNK_J * PW8 + (c % PW8);  // panel base + position in the row segment
-#pragma unroll
-      for (int j = 0; j < GU_JPW; ++j) {
-        wg[j] = __builtin_nontemporal_load(gblk + poff + (size_t)(jj0 + j) * PW8);
-        wu[j] = __builtin_nontemporal_load(ublk + poff + (size_t)(jj0 + j) * PW8);
-      }
+    auto fma_step = [&](int c) {
 #pragma unroll
       for (int tb = 0; tb < TB; ++tb) {
         if (tb < nt) {
@@ -220,6 +245,21 @@ __global__ __launch_bounds__(GU_THREADS) void k_decode_gateup(const uint16_t* __
             ag[j][tb] = g; au[j][tb] = u;
           }
         }
+      }
+    };
+    if constexpr (EARLY) {
+      if (lane < M8) {
+        if (rb != r0) wload(lane);  // a further pass over the same weights starts over
+        fma_step(lane);
+      }
+      for (int c = lane + WAVE; c < M8; c += WAVE) {
+        wload(c);
+        fma_step(c);
+      }
+    } else {
+      for (int c = lane; c < M8; c += WAVE) {
+        wload(c);
+        fma_step(c);
       }
     }
 #pragma unroll
