@@ -64,7 +64,9 @@ typedef struct {
   int32_t d_ff_shared; /* 0 = no shared expert; else multiple of granule */
   float r_gg, r_cg, r_cc;
   int32_t granule;     /* hidden columns per slicing unit; 0 -> 64; must be a multiple of 64 */
-  int32_t max_tokens;  /* largest T a forward call may pass; sizes the workspaces */
+  int32_t max_tokens;  /* largest T a forward call may pass; sizes the workspaces.  max_tokens * d_model and
+                          max_tokens * (top_k + 1 if shared) * max(d_ff, d_ff_shared) must stay below 2^31
+                          (the prompt-phase GEMMs address operand rows with 32-bit element offsets) */
   int32_t cc_threads;  /* host threads for the CC part; 0 -> min(16, hardware threads) */
   int32_t device;      /* HIP device ordinal */
   int32_t stage_mib;   /* size of one staging buffer for CG copies in MiB; 0 -> 256 */
@@ -132,7 +134,7 @@ typedef struct {
  * d_model); gate and up are the two halves of FC1 (sliced by columns j), down is FC2 (sliced by
  * rows j).  shared_*: HOST, bf16 [d_ff_shared][d_model], or NULL when d_ff_shared == 0.
  * The caller keeps ownership; the library repacks during the call and never reads them again.
- * Errors: SI_EINVAL (null pointer, bad shape/rate/granule), SI_ENOMEM, SI_EHIP.
+ * Errors: SI_EINVAL (null pointer, bad shape/rate/granule, max_tokens beyond the limit above), SI_ENOMEM, SI_EHIP.
  */
 int si_layer_create(const si_layer_desc_t* desc, const uint16_t* w_gate, const uint16_t* w_up,
                     const uint16_t* w_down, const uint16_t* shared_gate, const uint16_t* shared_up,

@@ -166,6 +166,18 @@ def test_split_does_not_change_gpu_output(oracle):
         assert np.max(np.abs(yd - ys[0][1])) <= 1e-4 * rms
 
 
+def test_max_tokens_beyond_32bit_offsets_is_refused():
+    """The prompt-phase GEMMs address operand rows with 32-bit element offsets: a layer whose max_tokens would
+    take x (or the activations) to 2^31 elements is refused at creation, before anything large is allocated."""
+    cfg = synth.scaled(synth.CONFIGS["llama2_70b"], d_model=8192, d_ff=64)
+    w = synth.make_weights(cfg)
+    with pytest.raises(si.ScheInferError) as ei:
+        GpuLayer(cfg, w, (1.0, 0.0, 0.0), max_tokens=(1 << 31) // 8192)
+    assert ei.value.code == si.SI_EINVAL
+    L = GpuLayer(cfg, w, (1.0, 0.0, 0.0), max_tokens=1024)  # a sane limit still creates
+    L.close()
+
+
 def test_edge_cases(oracle):
     cfg = synth.scaled(synth.CONFIGS["mixtral_8x7b"], d_model=128, d_ff=256)
     w = synth.make_weights(cfg)
