@@ -319,6 +319,10 @@ def roofline_of(name, ent, cfg_name=None, split=None):
     if measured:
         out["measured_peak"] = round(measured, 1)
         out["frac_of_measured_peak"] = round(a / measured, 4)
+    if ent["bound"] != "hbm" and MEASURED_PEAKS and MEASURED_PEAKS.get("mfma_bf16_random_tflops"):
+        # the register-resident matrix loop on operands that look like data (the chip clocks lower on them)
+        out["measured_peak_random_operands"] = round(MEASURED_PEAKS["mfma_bf16_random_tflops"], 1)
+        out["frac_of_measured_peak_random_operands"] = round(a / MEASURED_PEAKS["mfma_bf16_random_tflops"], 4)
     return out
 
 

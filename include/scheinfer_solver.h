@@ -155,7 +155,10 @@ int si_profile(const si_profile_desc_t* desc, si_profile_result_t* out);
  * What this machine sustains on the resources that bound the layer, from the simplest kernels that can reach
  * them (each the best of 4 runs): a read-only stream over 2 GiB of device memory, a 1 GiB device-to-device copy
  * (bytes read + written), a register-resident bf16 MFMA loop on every compute unit, one 256 MiB copy from pinned
- * host memory.  Needs a GPU and ~3.3 GiB of free device memory; allocates and frees its own buffers.
+ * host memory.  The MFMA loop is run twice: on near-constant operands (the most the matrix cores can do) and on
+ * pseudo-random ones that change from instruction to instruction (what they sustain on data: the clock the chip
+ * grants depends on the power the operands make the multipliers draw).
+ * Needs a GPU and ~3.3 GiB of free device memory; allocates and frees its own buffers.
  */
 typedef struct {
   double hbm_read_gbs;
@@ -163,6 +166,7 @@ typedef struct {
   double mfma_bf16_tflops;
   double h2d_gbs;
   int32_t n_cu;
+  double mfma_bf16_random_tflops;
 } si_peaks_t;
 int si_measure_peaks(int32_t device, si_peaks_t* out);
 

@@ -81,7 +81,7 @@ class si_ng_solution_t(ctypes.Structure):
 
 class si_peaks_t(ctypes.Structure):
     _fields_ = [("hbm_read_gbs", ctypes.c_double), ("hbm_copy_gbs", ctypes.c_double), ("mfma_bf16_tflops", ctypes.c_double),
-                ("h2d_gbs", ctypes.c_double), ("n_cu", ctypes.c_int32)]
+                ("h2d_gbs", ctypes.c_double), ("n_cu", ctypes.c_int32), ("mfma_bf16_random_tflops", ctypes.c_double)]
 
 
 class si_profile_desc_t(ctypes.Structure):

@@ -49,6 +49,36 @@ __global__ __launch_bounds__(512) void k_mfma_loop(int iters, float* __restrict_
   if (s == 123.456f) sink[0] = s;
 }
 
+// The same loop on operands that look like data: pseudo-random signs, exponents and mantissas, four A and four B
+// register sets paired differently from one matrix instruction to the next.  The matrix cores draw more power on
+// such operands than on the near-constant ones above, and the clock the chip grants follows.  (The sets are not
+// refreshed while the loop runs: measured, fresh values change nothing, but the vector instructions that would
+// produce them take issue slots from the matrix instructions and cost 13 %.)
+__global__ __launch_bounds__(512) void k_mfma_loop_random(int iters, float* __restrict__ sink) {
+  bf16x8 a[4], b[4];
+  uint32_t h = (blockIdx.x * 512u + threadIdx.x) * 2654435761u + 12345u;
+  auto next16 = [&]() {
+    h ^= h << 13; h ^= h >> 17; h ^= h << 5;
+    const uint32_t bits = (h & 0x807fu) | ((120u + ((h >> 8) & 7u)) << 7);  // +-2^-7 .. 2^0 times 1.mantissa
+    return __builtin_bit_cast(__bf16, (uint16_t)bits);
+  };
+  for (int s = 0; s < 4; ++s)
+    for (int i = 0; i < 8; ++i) { a[s][i] = next16(); b[s][i] = next16(); }
+  f32x16 acc[8];
+  for (int t = 0; t < 8; ++t)
+    for (int r = 0; r < 16; ++r) acc[t][r] = 0.f;
+  for (int it = 0; it < iters; it += 2) {
+#pragma unroll
+    for (int t = 0; t < 8; ++t) acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[t & 3], b[(t >> 1) & 3], acc[t], 0, 0, 0);
+#pragma unroll
+    for (int t = 0; t < 8; ++t) acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[(t + 1) & 3], b[(t + 2) & 3], acc[t], 0, 0, 0);
+  }
+  float s = 0.f;
+  for (int t = 0; t < 8; ++t)
+    for (int r = 0; r < 16; ++r) s += acc[t][r];
+  if (s == 123.456f) sink[0] = s;
+}
+
 #define PK_HIP(expr)                                                                                     \
   do {                                                                                                   \
     hipError_t _e = (expr);                                                                              \
@@ -108,6 +138,11 @@ extern "C" int si_measure_peaks(int32_t device, si_peaks_t* out) {
       return hipGetLastError();
     }));
     out->mfma_bf16_tflops = (double)blocks * 8 /*waves*/ * iters * 8 /*tiles*/ * (2.0 * 32 * 32 * 16) / (best * 1e-3) / 1e12;
+    PK_HIP(timed([&] {
+      hipLaunchKernelGGL(k_mfma_loop_random, dim3(blocks), dim3(512), 0, stream, iters, (float*)sink);
+      return hipGetLastError();
+    }));
+    out->mfma_bf16_random_tflops = (double)blocks * 8 * iters * 8 * (2.0 * 32 * 32 * 16) / (best * 1e-3) / 1e12;
     PK_HIP(timed([&] { return hipMemcpyAsync(buf2, pin, host_n, hipMemcpyHostToDevice, stream); }));
     out->h2d_gbs = (double)host_n / (best * 1e-3) / 1e9;
     out->n_cu = n_cu;
