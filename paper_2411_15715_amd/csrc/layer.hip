@@ -570,7 +570,7 @@ int create_impl(const si_layer_desc_t* desc, const WeightSource& src, const uint
     L->plan.idx = b + o_idx; L->plan.w = reinterpret_cast<float*>(b + o_w); L->plan.count = b + o_count;
     L->plan.off = b + o_off; L->plan.count1 = b + o_count1; L->plan.perm = b + o_perm; L->plan.inv = b + o_inv;
     L->plan.row_token = b + o_rt; L->plan.touched = b + o_touched; L->plan.n_touched = b + o_nt;
-    L->plan.n_tiles = b + o_nt + 1; L->plan.n_tiles_x2 = b + o_nt + 2;
+    L->plan.n_tiles = b + o_nt + 1; L->plan.n_tiles_x2 = b + o_nt + 2; L->plan.tile_flags = b + o_nt + 3;
     L->plan.n_routed = E;
     L->plan.tile_e = b + o_te; L->plan.tile_r = b + o_tr; L->plan.tile_e_x2 = b + o_te2; L->plan.tile_r_x2 = b + o_tr2;
   }

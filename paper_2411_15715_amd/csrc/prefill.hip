@@ -105,16 +105,20 @@ __device__ inline void block_barrier() {
 //    ranges are cut from the number of ids that really have work (known on the device only), so that no
 //    XCD is handed a range of empty ids (with ranges cut from the grid's upper bound the remap cost more than
 //    it saved on small tiles: the last XCD idled while the others carried its share).
+//    When no expert of the launch has more than one row tile nothing is shared through the L2 but the few rows
+//    of x, and tiles of different experts differ in cost (a 192-row tile streams its weights a quarter slower than
+//    a 128-row one): the ids are then dealt round-robin (`interleave`), every XCD gets the same mix, and the launch
+//    takes the mean of the experts' times instead of the slowest XCD's.
 //  * Tail split: N tiles on n_cu compute units run in ceil(N / n_cu) rounds; when the last round is at most
 //    half full each of its tiles gets two blocks, which share its rows if it has more than 128 (LLaMA-shaped
 //    gate/up GEMM: 896 tiles = 3.5 rounds; the last round then costs about half a round).
-__device__ inline bool map_block(int b, int N, int n_cu, int& L, int& half, int& halves) {
+__device__ inline bool map_block(int b, int N, int n_cu, int interleave, int& L, int& half, int& halves) {
   int r = N % n_cu;
   if (2 * r > n_cu) r = 0;
   const int main_n = N - r;
   const int per = (main_n + 7) / 8;
   if (b < 8 * per) {
-    L = (b % 8) * per + b / 8;
+    L = interleave ? b : (b % 8) * per + b / 8;
     half = 0;
     halves = 1;
     return L < main_n;
@@ -131,12 +135,16 @@ __device__ inline bool map_block(int b, int N, int n_cu, int& L, int& half, int&
 // nobody else reads its weight tiles (they come from HBM, not from a sibling's trail in the L2)
 struct TileInfo { int e, row0, row_end, se, solo; };
 
-// Number of logical tile ids with work in this launch (row tiles x inner tiles).
-__device__ inline int launch_extent(const Plan& p, int expert_sel, int x2_only, int n_inner) {
+// Number of logical tile ids with work in this launch (row tiles x inner tiles); single: no expert of the launch
+// has more than one row tile.
+__device__ inline int launch_extent(const Plan& p, int expert_sel, int x2_only, int n_inner, int& single) {
   if (expert_sel >= 0) {
     const int start = p.off[expert_sel] + (x2_only ? p.count1[expert_sel] : 0);
-    return n_row_tiles(p.off[expert_sel + 1] - start) * n_inner;
+    const int nrt = n_row_tiles(p.off[expert_sel + 1] - start);
+    single = nrt <= 1;
+    return nrt * n_inner;
   }
+  single = (*p.tile_flags >> (x2_only ? 1 : 0)) & 1;
   return (x2_only ? *p.n_tiles_x2 : *p.n_tiles) * n_inner;  // row tiles of the routed experts
 }
 
@@ -174,10 +182,12 @@ __device__ inline bool decode_tile(const Plan& p, int expert_sel, int x2_only, i
 }
 
 // block id -> tile of this block (false: nothing to do)
-__device__ inline bool block_tile(const Plan& p, int expert_sel, int x2_only, int n_inner, int n_cu, int& inner,
-                                  TileInfo& ti) {
-  int L, half, halves;
-  if (!map_block(blockIdx.x, launch_extent(p, expert_sel, x2_only, n_inner), n_cu, L, half, halves)) return false;
+// spread: deal single-tile launches round-robin over the XCDs (see map_block)
+__device__ inline bool block_tile(const Plan& p, int expert_sel, int x2_only, int n_inner, int n_cu, int spread,
+                                  int& inner, TileInfo& ti) {
+  int L, half, halves, single;
+  const int extent = launch_extent(p, expert_sel, x2_only, n_inner, single);
+  if (!map_block(blockIdx.x, extent, n_cu, single && spread, L, half, halves)) return false;
   if (!decode_tile(p, expert_sel, x2_only, L, n_inner, inner, ti)) return false;
   if (halves == 2) {
     const int rows = ti.row_end - ti.row0;
@@ -565,7 +575,7 @@ __global__ __launch_bounds__(THREADS, 1) void k_prefill_gateup(const uint16_t* _
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
   int tc;
   TileInfo ti;
-  if (!block_tile(p, expert_sel, x2_only, n_ctiles, n_cu, tc, ti)) return;
+  if (!block_tile(p, expert_sel, x2_only, n_ctiles, n_cu, 1, tc, ti)) return;
   if (!storage_index(wv, ti.e, ti.se)) return;
 #define SI_CALL_GU(BMV, ST) gateup_body<BMV, ST>(x, M, p, tc, ti, wv, hact, ldh, lds)
   SI_PICK_BODY_GU(ti, SI_CALL_GU)
@@ -685,8 +695,10 @@ __global__ __launch_bounds__(THREADS, 1) void k_prefill_down(const uint16_t* __r
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
   int inner;
   TileInfo ti;
-  // (XCD ranges: one expert's Hact rows, the A operand, stay in one L2)
-  if (!block_tile(p, expert_sel, x2_only, n_ntiles * n_split, n_cu, inner, ti)) return;
+  // (XCD ranges also when every expert has a single row tile: one expert's Hact rows, the A operand, a few MB,
+  // then stay in one L2; dealt round-robin every XCD re-reads every expert's rows for each of its column tiles,
+  // which measured 3 % slower although the XCDs finish together)
+  if (!block_tile(p, expert_sel, x2_only, n_ntiles * n_split, n_cu, 0, inner, ti)) return;
   if (!storage_index(wv, ti.e, ti.se)) return;
 #define SI_CALL_DN(BMV, ST) down_body<BMV, ST>(hact, ldh, M, inner, ti, n_ntiles, n_split, wv, yp, slab_stride, accumulate, lds)
   SI_PICK_BODY_DN(ti, SI_CALL_DN)
@@ -770,7 +782,7 @@ __global__ __launch_bounds__(THREADS, 1) void k_prefill_gateup_q4(const uint16_t
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
   int tc;
   TileInfo ti;
-  if (!block_tile(p, expert_sel, x2_only, n_ctiles, n_cu, tc, ti)) return;
+  if (!block_tile(p, expert_sel, x2_only, n_ctiles, n_cu, 1, tc, ti)) return;
   if (!storage_index(wv, ti.e, ti.se)) return;
 #define SI_CALL_GU(BMV) gateup_body_q4<BMV>(x, M, p, tc, ti, wv, hact, ldh, lds)
   SI_PICK_BODY_2PASS(ti, SI_CALL_GU);
@@ -864,7 +876,7 @@ __global__ __launch_bounds__(THREADS, 1) void k_prefill_down_q4(const uint16_t* 
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
   int inner;
   TileInfo ti;
-  if (!block_tile(p, expert_sel, x2_only, n_ntiles * n_split, n_cu, inner, ti)) return;
+  if (!block_tile(p, expert_sel, x2_only, n_ntiles * n_split, n_cu, 0, inner, ti)) return;
   if (!storage_index(wv, ti.e, ti.se)) return;
 #define SI_CALL_DN(BMV) down_body_q4<BMV>(hact, ldh, M, inner, ti, n_ntiles, n_split, wv, yp, slab_stride, accumulate, lds)
   SI_PICK_BODY_2PASS(ti, SI_CALL_DN);

@@ -54,15 +54,18 @@ __device__ __forceinline__ void assign_body(int T, int E, int k, int has_shared,
     for (int e = 0; e < EX; ++e) { s_off[e] = acc; acc += s_count[e]; }
     s_off[EX] = acc;
     // touched list and row-tile tables
-    int nt = 0, a = 0, b = 0;
+    int nt = 0, a = 0, b = 0, single = 3;
     for (int e = 0; e < EX; ++e) {
       if (s_count[e] > 0 && p.touched) p.touched[nt] = e;
       if (s_count[e] > 0) ++nt;
       s_tiles[0][e] = a;
       s_tiles[1][e] = b;
-      a += n_row_tiles(s_count[e]);
-      b += n_row_tiles(s_count[e] - s_count1[e]);
+      const int ta = n_row_tiles(s_count[e]), tb = n_row_tiles(s_count[e] - s_count1[e]);
+      a += ta;
+      b += tb;
+      if (e < E) single &= (ta <= 1 ? 1 : 0) | (tb <= 1 ? 2 : 0);
     }
+    if (p.tile_flags) *p.tile_flags = single;
     s_tiles[0][EX] = a;
     s_tiles[1][EX] = b;
     if (p.n_touched) *p.n_touched = nt;

@@ -55,6 +55,7 @@ struct Plan {
   int32_t* tile_e_x2;  // the same for the X2 rows only (CG')
   int32_t* tile_r_x2;
   int32_t* n_tiles_x2;  // [1]
+  int32_t* tile_flags;  // [1] bit 0: no routed expert has more than one row tile; bit 1: the same for the X2 rows
   int32_t n_routed;    // E: launches over "all experts" cover entries < n_routed only (the shared
                        // expert's weights live in their own buffer and get their own launch)
 };
