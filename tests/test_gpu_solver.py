@@ -27,9 +27,10 @@ def test_profile_points_and_fits(profile):
     m = p["model"]
     assert all(v >= 0.0 for v in m.values())
     assert m["beta_g"] > 0 and m["beta_c"] > 0 and m["beta_c2g"] > 0
-    # this machine: copies run at 10..70 GB/s, a launch costs 1..200 us, the GPU beats the host per unit of work
+    # this machine: copies run at 10..70 GB/s, enqueueing a launch costs 0.2..200 us of host time (0.68 us has been
+    # seen on a quiet box), the GPU beats the host per unit of work
     assert 1.0 / 70e9 < m["beta_c2g"] < 1.0 / 10e9
-    assert 1e-6 < m["t_launch"] < 2e-4 and p["sigma_launch"] < m["t_launch"]
+    assert 2e-7 < m["t_launch"] < 2e-4 and p["sigma_launch"] < m["t_launch"]
     assert m["beta_g"] < m["beta_c"]
     assert p["r2_c2g"] > 0.98 and p["r2_g"] > 0.8
     # the library's fit of its own points is the least-squares one
